@@ -1,0 +1,160 @@
+"""Benchmark of the quantized GEMV hot path on one MI355X.
+
+A step is one pass of the whole path over the LLaMA-7B-shaped decoder layer set at batch 1,
+4-bit codes, group 128 (seven matrices: four 4096x4096, two 11008x4096, one 4096x11008, each
+with its own fp32 x): ONE grouped kernel launch reading the packed weights from HBM.
+Weights are quantized and packed by the library before the timed region and stay resident
+in HBM; to keep the 256 MB last-level cache from serving them, the timed loop rotates over
+enough distinct packed copies of the set that consecutive uses of a copy are more than 1.2 GB
+of traffic apart.
+
+Prints one JSON line.  `value` is microseconds per layer set; `roofline` prices the GEMV
+kernel against the 8 TB/s HBM peak with the algorithmic bytes of the set (codes + fp32 scale
++ b-bit zero per group + x + y); `cpu_baseline` is the CPU oracle on the same packed data.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+HBM_PEAK_GBS = 8000.0          # MI355X public peak
+ROTATE_BYTES = 1.3e9           # distinct packed bytes touched between two uses of one copy
+
+
+def algorithmic_bytes(cfg) -> int:
+    """Bytes the method itself has to move for one layer set: b bits per weight, one fp32
+    scale and one b-bit zero per group (the paper's memory formula, Section 3, with K/G
+    groups per output), x read once and y written once per matrix."""
+    total = 0
+    for n, k in cfg.shapes:
+        bits = cfg.bits * n * k + (32 + cfg.bits) * n * (k // cfg.group)
+        total += bits // 8 + 4 * k + 4 * n
+    return total
+
+
+def prepare_set(cfg, qg):
+    """Quantize and pack every matrix of the set on the GPU; returns problem dicts."""
+    from paper_2307_03738_amd import synth
+    problems = []
+    for i, (n, k) in enumerate(cfg.shapes):
+        W, (x,) = synth.matrix(cfg, i)
+        Wd = torch.from_numpy(W).cuda()
+        q, s, z = qg.qg_quantize(Wd, cfg.bits, cfg.group)
+        blob = qg.qg_pack(q, s, z, cfg.bits, cfg.group)
+        problems.append(dict(packed=blob, N=n, K=k, bits=cfg.bits, group=cfg.group,
+                             x=torch.from_numpy(x).cuda(),
+                             y=torch.empty(n, dtype=torch.float32, device="cuda"),
+                             host=(q.cpu().numpy(), s.cpu().numpy(), z.cpu().numpy(), x)))
+        del Wd, q, s, z
+    torch.cuda.synchronize()
+    return problems
+
+
+def cpu_baseline(cfg, problems, passes=5):
+    """The oracle's packed-format matvec over the whole layer set on the host cores."""
+    from oracle import oracle
+    packed = []
+    for p in problems:
+        q, s, z, x = p["host"]
+        packed.append((oracle.pack_codes(q, cfg.bits), oracle.transpose_scales(s),
+                       oracle.pack_zeros(z, cfg.bits), p["K"], x))
+    times = []
+    for _ in range(passes):
+        t0 = time.perf_counter()
+        for P, St, Zp, K, x in packed:
+            oracle.matvec_packed(P, St, Zp, K, cfg.bits, cfg.group, x)
+        times.append(time.perf_counter() - t0)
+    return {"value": round(float(np.median(times)) * 1e6, 1), "unit": "us per layer set",
+            "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"full {cfg.name} layer set from the canonical packed format, median of {passes} passes"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--config", default="C2", choices=["C2", "C3", "C4"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--wpb", type=int, default=0)
+    ap.add_argument("--bytes-per-wave", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: the path has no multi-GPU part (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    from paper_2307_03738_amd import binding as qg, synth
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    qg.qg_set_gemv_tuning(args.wpb, args.bytes_per_wave)
+
+    base = prepare_set(cfg, qg)
+    set_bytes = sum(p["packed"].numel() for p in base)
+    copies = max(2, int(np.ceil(ROTATE_BYTES / set_bytes)))
+    launches = []
+    for c in range(copies):
+        probs = [dict(p, packed=(p["packed"] if c == 0 else p["packed"].clone())) for p in base]
+        launches.append(qg.GroupedGemv(probs))
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream().cuda_stream
+    for i in range(args.warmup):
+        launches[i % copies].launch(stream)
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for i in range(args.steps):
+        launches[i % copies].launch(stream)
+    stop.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = start.elapsed_time(stop) / args.steps
+
+    # the same launches on a single copy: weights served largely by the last-level cache
+    for i in range(20):
+        launches[0].launch(stream)
+    torch.cuda.synchronize()
+    start.record()
+    for i in range(args.steps):
+        launches[0].launch(stream)
+    stop.record()
+    torch.cuda.synchronize()
+    warm_ms = start.elapsed_time(stop) / args.steps
+
+    alg = algorithmic_bytes(cfg)
+    achieved = alg / (ms_per_step * 1e-3) / 1e9
+    out = {
+        "metric": "us per LLaMA-7B-shaped 4-bit g128 GEMV layer set (batch 1); % of HBM peak"
+                  if args.config == "C2" else f"us per {cfg.name} GEMV layer set (batch 1); % of HBM peak",
+        "value": round(ms_per_step * 1e3, 3), "unit": "us",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: decoder layer set {list(cfg.shapes)}, {cfg.bits}-bit, "
+                               f"group {cfg.group}, batch 1, one grouped launch per set",
+                   "packed_copies_rotated": copies, "packed_bytes_per_set": set_bytes,
+                   "algorithmic_bytes_per_set": alg},
+        "effective_weight_GBps": round(achieved, 1),
+        "pct_of_hbm_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
+        "cache_warm_single_copy_us": round(warm_ms * 1e3, 3),
+        "host_wall_ms_per_step": round(wall_ms / args.steps, 6),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, base)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

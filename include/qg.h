@@ -1,0 +1,139 @@
+/*
+ * qg -- group-quantized matrix-vector and small-batch matrix products on MI355X (gfx950).
+ *
+ * The operation is the one of QIGen (arXiv 2307.03738): a weight matrix is stored as b-bit
+ * integer codes q with one scale s and one zero-point z per group of G consecutive inputs,
+ * What = s * (q - z) (Section 2, quantization and dequantization, eq. (1)), and the hot path
+ * is y = What x computed straight from the packed codes (eq. (2), Algorithm 1), plus its
+ * matrix form for a few prompt tokens.
+ *
+ * Orientation: W is [N][K] row-major, N outputs, K inputs (the paper writes the transpose:
+ * its n is K here, its m is N).  Groups run along k.  b is 2, 3 or 4.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers owned by the caller, unless a parameter is
+ *     marked HOST.  The library never allocates or frees device memory and never
+ *     synchronises: work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns at once.  Buffers must stay valid until that
+ *     work has run.
+ *   - Return value: QG_OK (0) or a positive qg_status.  On an error nothing is enqueued and
+ *     no output is touched.  No exceptions, no abort.
+ *   - Outputs are overwritten, never accumulated into.  Results do not depend on the launch
+ *     order of workgroups: there are no floating-point atomics.
+ *   - NaN or Inf in W, x or X: unspecified.
+ */
+#ifndef QG_H
+#define QG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QG_OK = 0,
+    QG_ERR_NULL = 1,        /* a required pointer is NULL */
+    QG_ERR_SHAPE = 2,       /* N, K, M <= 0; K % G != 0; G not a multiple of the cell size */
+    QG_ERR_UNSUPPORTED = 3, /* bits not in {2,3,4}; unknown layout; too many grouped problems */
+    QG_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned */
+    QG_ERR_WORKSPACE = 5,   /* workspace missing or smaller than qg_workspace_bytes() */
+    QG_ERR_DEVICE = 6       /* the HIP runtime refused the launch */
+} qg_status;
+
+typedef enum {
+    /* The paper's format (Section 3 "Data format", Algorithm 2): per output n the codes
+     * along k form a little-endian bit stream, code k at bits [b*k, b*k+b), cut into 32-bit
+     * words; word w of output n at uint32 [w][n] (n contiguous).  A blob in this layout is
+     *   uint32 codes [K*b/32][N] | float scales [K/G][N] | uint32 zeros [ceil(K/G*b/32)][N]
+     * with the zero-points packed by the same rule along the group index (b bits each,
+     * zero-padded to a word).  Needs K*b % 32 == 0. */
+    QG_LAYOUT_CANONICAL = 0,
+    /* The layout qg_gemv and qg_gemm_small read.  Opaque; a pure permutation of the same
+     * codes, scales and zero-points (plus zero padding), fixed by (N, K, bits, group). */
+    QG_LAYOUT_DEVICE = 1
+} qg_layout;
+
+/* Smallest granule of codes the kernels decode at once: 8 codes (one word) at 4 bits, 16
+ * (one word) at 2 bits, 32 (three words, Section 3) at 3 bits.  A group must be a whole
+ * number of cells: G % qg_cell(bits) == 0. */
+int qg_cell(int bits);
+
+const char *qg_status_string(int status);
+
+/* Size in bytes of a packed blob (codes, scales and zero-points) in the given layout;
+ * 0 if the shape is not accepted. */
+size_t qg_packed_bytes(int64_t N, int64_t K, int bits, int group, int layout);
+
+/* Size in bytes of the scratch buffer qg_gemv (M = 1) or qg_gemm_small (M > 1) needs for
+ * this problem: partial sums of the K-split and one counter per 64 outputs.  For a grouped
+ * launch, the sum over its problems.  0 if the shape is not accepted.
+ * The buffer must be zero-filled once before its first use (qg_workspace_init); every call
+ * leaves it zero-filled again where that matters.  Two calls that overlap in time must not
+ * share one workspace. */
+size_t qg_workspace_bytes(int64_t N, int64_t K, int bits, int group, int M);
+int qg_workspace_init(void *workspace, size_t bytes, void *stream);
+
+/* Per-group min-max round-to-nearest quantization (Section 2; the integer-zero form
+ * q = clamp(rint(w/s) + z, 0, 2^b - 1)):
+ *   lo = min(0, min w), hi = max(0, max w) over the group
+ *   s  = (hi - lo) / (2^b - 1)            fp32 division; s = 1, z = 0 if hi == lo
+ *   z  = clamp(rint(-lo / s), 0, 2^b - 1)
+ *   q  = clamp(rint(w / s) + z, 0, 2^b - 1)   ties to even, integer addition of z
+ * every step one IEEE binary32 operation.
+ *   W [N][K] fp32 in;  q [N][K] one code per byte, s [N][K/G] fp32, z [N][K/G] bytes out.
+ * Needs K % G == 0 and G % 4 == 0; W and q 16-byte aligned. */
+int qg_quantize(const float *W, int64_t N, int64_t K, int bits, int group,
+                uint8_t *q, float *s, uint8_t *z, void *stream);
+
+/* Bit-packing of codes, scales and zero-points into one blob of qg_packed_bytes() bytes
+ * (Section 3 "Data format").  q, s, z as produced by qg_quantize.  `packed` 16-byte
+ * aligned.  Codes and zero-points must be < 2^b (not checked). */
+int qg_pack(const uint8_t *q, const float *s, const uint8_t *z, int64_t N, int64_t K,
+            int bits, int group, int layout, void *packed, void *stream);
+
+/* Inverse of qg_pack for either layout: returns q, s, z in the qg_quantize arrangement. */
+int qg_unpack(const void *packed, int64_t N, int64_t K, int bits, int group, int layout,
+              uint8_t *q, float *s, uint8_t *z, void *stream);
+
+/* y[n] = sum_k s[n][k/G] * (q[n][k] - z[n][k/G]) * x[k]   (eq. (2); Algorithm 1)
+ * evaluated per group as s * (sum q x - z * sum x), fp32 throughout, x kept in fp32.
+ *   packed: QG_LAYOUT_DEVICE blob;  x [K] fp32, 64-byte aligned;  y [N] fp32 (overwritten).
+ * workspace: qg_workspace_bytes(N, K, bits, group, 1) bytes, 16-byte aligned. */
+int qg_gemv(const void *packed, int64_t N, int64_t K, int bits, int group,
+            const float *x, float *y, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Several independent products in ONE kernel launch (the seven linear layers of a decoder
+ * block at batch 1 are each only microseconds of memory traffic).  `descs` is a HOST array
+ * of `count` <= QG_MAX_GROUPED problems; they may differ in shape, bits and group (one
+ * launch per distinct (bits, group) pair).  Workspace: the sum of qg_workspace_bytes(). */
+#define QG_MAX_GROUPED 16
+typedef struct qg_gemv_desc {
+    const void *packed; /* QG_LAYOUT_DEVICE blob */
+    int64_t N, K;
+    int bits, group;
+    const float *x;     /* [K], 64-byte aligned */
+    float *y;           /* [N] */
+} qg_gemv_desc;
+int qg_gemv_grouped(const qg_gemv_desc *descs /* HOST */, int count,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* Prompt-phase form for M <= 128 tokens:
+ *   Y[m][n] = sum_k X[m][k] * s[n][k/G] * (q[n][k] - z[n][k/G])
+ * with X and the dequantized weights rounded to bf16 and accumulated in fp32 on the matrix
+ * cores.  X [M][K] fp32 row-major;  Y [M][N] fp32 row-major (overwritten).
+ * workspace: qg_workspace_bytes(N, K, bits, group, M) bytes. */
+int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
+                  const float *X, int M, float *Y,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe).  0 restores the
+ * built-in choice.  waves_per_block in 1..16; bytes_per_wave = packed code bytes one
+ * wavefront streams before the K-split reduction. */
+int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QG_H */

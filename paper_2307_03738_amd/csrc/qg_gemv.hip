@@ -1,0 +1,734 @@
+// qg_gemv / qg_gemv_grouped: y = What x straight from the packed codes (eq. (2), Algorithm 1).
+//
+// Mapping.  One lane per output: lane l of a wavefront owns output n = 64*tile + l and reads
+// its own 128-bit vectors of codes, so each wavefront load is one contiguous 1 KB piece of
+// the blob.  x[k] is the same for all 64 lanes; it is read through the scalar path and used
+// as a scalar operand of the fused multiply-add, so the activation costs no vector
+// register, no LDS bandwidth and no cross-lane traffic.  This is the register picture of the
+// paper's micro-kernel (Algorithm 3: vector accumulators over outputs, x broadcast) at
+// wavefront width.
+//
+// Arithmetic per group g (eq. (2) with the scale kept on the zero term):
+//     y_n += s_{n,g} * ( sum_{k in g} q_{n,k} x_k  -  z_{n,g} * sum_{k in g} x_k )
+// The inner sum runs on raw codes: mask four byte lanes of a word at once, convert a byte
+// lane to float in one instruction, one fused multiply-add per weight.  sum_k x_k per group
+// is the paper's x-hat (Algorithm 1 input), computed once per wavefront with a cross-lane
+// reduction and kept one group per lane.
+//
+// K is split over the wavefronts of a workgroup (LDS reduction in a fixed order) and, when
+// that is not enough parallelism, over workgroups: each writes a partial vector, and the
+// workgroup that arrives last at the tile's counter adds the partials in a fixed order.
+// No floating-point atomics, so results do not depend on timing.
+#include "qg_common.h"
+
+namespace {
+
+struct GemvProblem {
+    const uint4 *codes;
+    const float *scales;
+    const uint32_t *zeros;
+    const float *x;
+    float *y;
+    float *partial;        // [tile][chunk][64]
+    unsigned *counter;     // [tile]
+    int N, K, tiles, steps, ngroups, zwords;
+    int group;             // G
+    int chunks;            // K-split over workgroups
+    int steps_per_wave;
+    int steps_per_group;   // runtime-group kernel only
+    int block_begin;       // first block of this problem in the grid
+};
+
+struct GemvArgs {
+    int count;
+    GemvProblem p[QG_MAX_GROUPED];
+};
+
+template <int BITS> struct Fmt;
+template <> struct Fmt<4> { static constexpr int CELL = 8,  PLANES = 1, STEP_UNITS = 4, ZBITS = 4; };
+template <> struct Fmt<2> { static constexpr int CELL = 16, PLANES = 1, STEP_UNITS = 4, ZBITS = 2; };
+template <> struct Fmt<3> { static constexpr int CELL = 32, PLANES = 3, STEP_UNITS = 2, ZBITS = 4; };
+
+template <int BITS> constexpr int loads_per_step() { return Fmt<BITS>::STEP_UNITS * Fmt<BITS>::PLANES; }
+template <int BITS> constexpr int cells_per_step() { return Fmt<BITS>::STEP_UNITS * 4; }
+template <int BITS> constexpr int codes_per_step() { return cells_per_step<BITS>() * Fmt<BITS>::CELL; }
+
+__device__ inline uint32_t word_of(const uint4 &v, int j)
+{
+    return j == 0 ? v.x : j == 1 ? v.y : j == 2 ? v.z : v.w;
+}
+
+// Keeps a masked word opaque to the optimiser so that the byte-lane conversions below stay
+// "convert byte i of this register" instead of being rewritten as shift-and-mask per code.
+__device__ inline uint32_t opaque(uint32_t v)
+{
+    asm("" : "+v"(v));
+    return v;
+}
+
+// Four byte lanes of m times four x values.  Byte i of m is one code.
+#define QG_B0(m) ((float)((m) & 0xffu))
+#define QG_B1(m) ((float)(((m) >> 8) & 0xffu))
+#define QG_B2(m) ((float)(((m) >> 16) & 0xffu))
+#define QG_B3(m) ((float)((m) >> 24))
+
+// 32 consecutive x values held in scalar registers (x is uniform across the wavefront).
+typedef float xvec16 __attribute__((ext_vector_type(16)));
+struct XBatch {
+    xvec16 lo, hi;
+    __device__ inline float operator[](int i) const { return i < 16 ? lo[i] : hi[i - 16]; }
+};
+__device__ inline XBatch load_x32(const float *__restrict__ p)
+{
+    XBatch b;
+    b.lo = *(const xvec16 *)p;
+    b.hi = *(const xvec16 *)(p + 16);
+    return b;
+}
+
+// Scalar loads return out of order, so the only wait the hardware offers is "all of them".
+// To overlap the load of the next batch with the arithmetic on the current one, the first
+// use of the current batch has to come BEFORE the next load is issued.  The loops below
+// therefore run one octet of the batch, then issue the next load, then run the other three,
+// with scheduling fences so that this order survives instruction scheduling.
+#define QG_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// Octet `o` (0..3) of batch `bt` of a step: eight codes times eight of the 32 x values in xb.
+// 4 bits: an octet is a cell (one word; code i in bits [4i, 4i+4), Algorithm 2).
+// 2 bits: a cell (one word, code i in bits [2i, 2i+2)) is two octets; field set f holds
+//         codes f, 4+f, 8+f, 12+f, and an octet takes two field sets.
+// 3 bits: a cell (words A, B, C, layout in qg_common.h) is four octets, one per source word
+//         A, B, C and the word T gathered from the spare bits.
+template <int BITS>
+__device__ inline float octet_dot(const uint4 *v, int bt, int o, const XBatch &xb, float acc)
+{
+    if constexpr (BITS == 4) {
+        const int cell = bt * 4 + o;
+        const uint32_t w = word_of(v[cell >> 2], cell & 3);
+        const uint32_t lo = opaque(w & 0x0f0f0f0fu);          // even codes
+        const uint32_t hi = opaque((w >> 4) & 0x0f0f0f0fu);   // odd codes
+        const int x0 = 8 * o;
+        acc = fmaf(QG_B0(lo), xb[x0 + 0], acc);  acc = fmaf(QG_B0(hi), xb[x0 + 1], acc);
+        acc = fmaf(QG_B1(lo), xb[x0 + 2], acc);  acc = fmaf(QG_B1(hi), xb[x0 + 3], acc);
+        acc = fmaf(QG_B2(lo), xb[x0 + 4], acc);  acc = fmaf(QG_B2(hi), xb[x0 + 5], acc);
+        acc = fmaf(QG_B3(lo), xb[x0 + 6], acc);  acc = fmaf(QG_B3(hi), xb[x0 + 7], acc);
+    } else if constexpr (BITS == 2) {
+        const int cell = bt * 2 + (o >> 1);
+        const uint32_t w = word_of(v[cell >> 2], cell & 3);
+        const int x0 = 16 * (o >> 1);
+#pragma unroll
+        for (int f = 2 * (o & 1); f < 2 * (o & 1) + 2; ++f) {
+            const uint32_t m = opaque((w >> (2 * f)) & 0x03030303u);
+            acc = fmaf(QG_B0(m), xb[x0 + f], acc);
+            acc = fmaf(QG_B1(m), xb[x0 + 4 + f], acc);
+            acc = fmaf(QG_B2(m), xb[x0 + 8 + f], acc);
+            acc = fmaf(QG_B3(m), xb[x0 + 12 + f], acc);
+        }
+    } else {
+        const int cell = bt;
+        const int u = cell >> 2, j = cell & 3;
+        uint32_t src;
+        if (o < 3) {
+            src = word_of(v[u * 3 + o], j);
+        } else {
+            const uint32_t a = word_of(v[u * 3 + 0], j);
+            const uint32_t b = word_of(v[u * 3 + 1], j);
+            const uint32_t c = word_of(v[u * 3 + 2], j);
+            src = ((a >> 6) & 0x03030303u) | ((b >> 4) & 0x0c0c0c0cu) | ((c >> 2) & 0x30303030u);
+        }
+        const uint32_t m0 = opaque(src & 0x07070707u);
+        const uint32_t m1 = opaque((src >> 3) & 0x07070707u);
+        const int x0 = 8 * o;
+        acc = fmaf(QG_B0(m0), xb[x0 + 0], acc);  acc = fmaf(QG_B1(m0), xb[x0 + 1], acc);
+        acc = fmaf(QG_B2(m0), xb[x0 + 2], acc);  acc = fmaf(QG_B3(m0), xb[x0 + 3], acc);
+        acc = fmaf(QG_B0(m1), xb[x0 + 4], acc);  acc = fmaf(QG_B1(m1), xb[x0 + 5], acc);
+        acc = fmaf(QG_B2(m1), xb[x0 + 6], acc);  acc = fmaf(QG_B3(m1), xb[x0 + 7], acc);
+    }
+    return acc;
+}
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+__device__ inline float lane_value(float v, int src_lane)   // src_lane uniform
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
+}
+
+// x-hat per group: returns, in lane j, sum of x[kbeg + j*G .. + G) for j < ng <= 64.
+// Handles any G >= 64 and G in {8, 16, 32}.
+__device__ inline float group_sums(const float *__restrict__ x, int kbeg, int ng, int G, int lane)
+{
+    float r = 0.0f;
+    if (G >= 64) {
+        for (int j = 0; j < ng; ++j) {
+            float v = 0.0f;
+            for (int i = lane; i < G; i += 64) v += x[kbeg + j * G + i];
+            v = wave_sum(v);
+            if (lane == j) r = v;
+        }
+    } else {
+        const int per = 64 / G;                      // groups per 64-wide window
+        const int windows = (ng + per - 1) / per;
+        for (int w = 0; w < windows; ++w) {
+            const int i = w * 64 + lane;
+            float v = i < ng * G ? x[kbeg + i] : 0.0f;
+            for (int off = 1; off < G; off <<= 1) v += __shfl_xor(v, off);
+            const float t = __shfl(v, (lane % per) * G);
+            if (lane / per == w) r = t;
+        }
+    }
+    return r;
+}
+
+// K-split epilogue.  Every wavefront of the block passes its 64 partial outputs; wavefront
+// 0 adds them in wavefront order and either stores y or hands the block's vector to the
+// tile's last-arriving block.
+__device__ inline void finish_tile(const GemvProblem &P, int tile, int chunk, float yacc,
+                                   float (*red)[QG_WAVE])
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int waves = blockDim.x >> 6;
+    red[wave][lane] = yacc;
+    __syncthreads();
+    if (wave != 0) return;
+    float t = red[0][lane];
+    for (int w = 1; w < waves; ++w) t += red[w][lane];
+    const int n = tile * QG_WAVE + lane;
+    if (P.chunks == 1) {
+        if (n < P.N) P.y[n] = t;
+        return;
+    }
+    float *mine = P.partial + ((size_t)tile * P.chunks + chunk) * QG_WAVE;
+    __hip_atomic_store(mine + lane, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __threadfence();                                   // publish the partial before the count
+    unsigned arrived = 0;
+    if (lane == 0) arrived = atomicAdd(P.counter + tile, 1u);
+    arrived = __builtin_amdgcn_readfirstlane(arrived);
+    if (arrived != (unsigned)P.chunks - 1u) return;
+    __threadfence();                                   // see every other block's partial
+    const float *all = P.partial + (size_t)tile * P.chunks * QG_WAVE;
+    float sum = 0.0f;
+    for (int c = 0; c < P.chunks; ++c)
+        sum += __hip_atomic_load(all + c * QG_WAVE + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (n < P.N) P.y[n] = sum;
+    if (lane == 0) P.counter[tile] = 0u;               // leave the workspace zeroed
+}
+
+__device__ inline int find_problem(const GemvArgs &A, int bid)
+{
+    int p = 0;
+    for (int i = 1; i < A.count; ++i)
+        if (bid >= A.p[i].block_begin) p = i;
+    return p;
+}
+
+template <int BITS>
+__device__ inline void load_step(uint4 *dst, const uint4 *__restrict__ base, int step)
+{
+    constexpr int L = loads_per_step<BITS>();
+#pragma unroll
+    for (int i = 0; i < L; ++i) dst[i] = base[((size_t)step * L + i) * QG_WAVE];
+}
+
+// ---------------------------------------------------------------------------------------
+// Groups no larger than a step: CPG cells per group, GPS = groups per step, all static.
+// ---------------------------------------------------------------------------------------
+template <int BITS, int CPG>
+__global__ __launch_bounds__(1024) void gemv_static(const GemvArgs A)
+{
+    using F = Fmt<BITS>;
+    constexpr int L = loads_per_step<BITS>();
+    constexpr int CPS = cells_per_step<BITS>();
+    constexpr int S = codes_per_step<BITS>();
+    constexpr int GPS = CPS / CPG;
+    constexpr int G = CPG * F::CELL;
+    constexpr int ZPER = 32 / F::ZBITS;
+    constexpr int ZW = GPS > ZPER ? GPS / ZPER : 1;   // zero words touched per step
+    constexpr int NB = S / 32;                        // batches of 32 x values per step
+    __shared__ float red[16][QG_WAVE];
+
+    const int pi = find_problem(A, blockIdx.x);
+    const GemvProblem &P = A.p[pi];
+    const int local = blockIdx.x - P.block_begin;
+    const int tile = local / P.chunks, chunk = local % P.chunks;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int waves = blockDim.x >> 6;
+
+    int s0 = (chunk * waves + wave) * P.steps_per_wave;
+    int s1 = s0 + P.steps_per_wave;
+    if (s1 > P.steps) s1 = P.steps;
+
+    float yacc = 0.0f;
+    if (s0 < s1) {
+        const uint4 *codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
+        const float *sc = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
+        const uint32_t *zr = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+        const float *__restrict__ x = P.x;
+
+        uint4 cur[L], nxt[L] = {};
+        float scur[GPS], snxt[GPS] = {};
+        uint32_t zcur[ZW], znxt[ZW] = {};
+        load_step<BITS>(cur, codes, s0);
+#pragma unroll
+        for (int g = 0; g < GPS; ++g) scur[g] = sc[(size_t)(s0 * GPS + g) * QG_WAVE];
+#pragma unroll
+        for (int w = 0; w < ZW; ++w) zcur[w] = zr[(size_t)((s0 * GPS) / ZPER + w) * QG_WAVE];
+
+        const float xsum = group_sums(x, s0 * S, (s1 - s0) * GPS, G, lane);
+
+        XBatch xb = load_x32(x + (size_t)s0 * S);
+        for (int s = s0; s < s1; ++s) {
+            if (s + 1 < s1) {
+                load_step<BITS>(nxt, codes, s + 1);
+#pragma unroll
+                for (int g = 0; g < GPS; ++g) snxt[g] = sc[(size_t)((s + 1) * GPS + g) * QG_WAVE];
+#pragma unroll
+                for (int w = 0; w < ZW; ++w)
+                    znxt[w] = zr[(size_t)(((s + 1) * GPS) / ZPER + w) * QG_WAVE];
+            }
+            const float *xs = x + (size_t)s * S;
+            float acc = 0.0f;
+#pragma unroll
+            for (int bt = 0; bt < NB; ++bt) {
+                XBatch xn = xb;
+#pragma unroll
+                for (int o = 0; o < 4; ++o) {
+                    if (o == 0) QG_SCHED_FENCE();
+                    acc = octet_dot<BITS>(cur, bt, o, xb, acc);
+                    if (o == 0) {
+                        QG_SCHED_FENCE();
+                        // next batch in flight (it may belong to the next step)
+                        if (bt + 1 < NB || s + 1 < s1) xn = load_x32(xs + 32 * (bt + 1));
+                        QG_SCHED_FENCE();
+                    }
+                    const int done = (bt * 4 + o + 1) * 8;            // codes of the step done so far
+                    if (done % G == 0) {
+                        const int gs = done / G - 1;                  // group within the step
+                        const int gl = (s - s0) * GPS + gs;           // group within the wavefront
+                        const int gabs = s * GPS + gs;
+                        const uint32_t zword = zcur[ZW > 1 ? gs / ZPER : 0];
+                        const float zf = (float)((zword >> (F::ZBITS * (gabs % ZPER))) & ((1u << F::ZBITS) - 1u));
+                        const float sx = lane_value(xsum, gl);
+                        yacc = fmaf(scur[gs], fmaf(-zf, sx, acc), yacc);
+                        acc = 0.0f;
+                    }
+                }
+                xb = xn;
+            }
+#pragma unroll
+            for (int i = 0; i < L; ++i) cur[i] = nxt[i];
+#pragma unroll
+            for (int g = 0; g < GPS; ++g) scur[g] = snxt[g];
+#pragma unroll
+            for (int w = 0; w < ZW; ++w) zcur[w] = znxt[w];
+        }
+    }
+    finish_tile(P, tile, chunk, yacc, red);
+}
+
+// ---------------------------------------------------------------------------------------
+// Groups that are a whole number of steps (G = 256, ..., up to one group per output: the
+// full-column case of eq. (1)).
+// ---------------------------------------------------------------------------------------
+template <int BITS>
+__global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
+{
+    using F = Fmt<BITS>;
+    constexpr int L = loads_per_step<BITS>();
+    constexpr int S = codes_per_step<BITS>();
+    constexpr int ZPER = 32 / F::ZBITS;
+    constexpr int NB = S / 32;
+    __shared__ float red[16][QG_WAVE];
+
+    const int pi = find_problem(A, blockIdx.x);
+    const GemvProblem &P = A.p[pi];
+    const int local = blockIdx.x - P.block_begin;
+    const int tile = local / P.chunks, chunk = local % P.chunks;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int waves = blockDim.x >> 6;
+    const int spg = P.steps_per_group;
+
+    int s0 = (chunk * waves + wave) * P.steps_per_wave;     // a multiple of spg
+    int s1 = s0 + P.steps_per_wave;
+    if (s1 > P.steps) s1 = P.steps;
+
+    float yacc = 0.0f;
+    if (s0 < s1) {
+        const uint4 *codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
+        const float *sc = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
+        const uint32_t *zr = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+        const float *__restrict__ x = P.x;
+        const int g0 = s0 / spg, ng = (s1 - s0) / spg;
+
+        uint4 cur[L], nxt[L] = {};
+        load_step<BITS>(cur, codes, s0);
+        const float xsum = group_sums(x, s0 * S, ng, P.group, lane);
+
+        int s = s0;
+        XBatch xb = load_x32(x + (size_t)s0 * S);
+        for (int gl = 0; gl < ng; ++gl) {
+            const int gabs = g0 + gl;
+            const float scale = sc[(size_t)gabs * QG_WAVE];
+            const uint32_t zword = zr[(size_t)(gabs / ZPER) * QG_WAVE];
+            float acc = 0.0f;
+            for (int i = 0; i < spg; ++i, ++s) {
+                if (s + 1 < s1) load_step<BITS>(nxt, codes, s + 1);
+                const float *xs = x + (size_t)s * S;
+#pragma unroll
+                for (int bt = 0; bt < NB; ++bt) {
+                    XBatch xn = xb;
+#pragma unroll
+                    for (int o = 0; o < 4; ++o) {
+                        if (o == 0) QG_SCHED_FENCE();
+                        acc = octet_dot<BITS>(cur, bt, o, xb, acc);
+                        if (o == 0) {
+                            QG_SCHED_FENCE();
+                            if (bt + 1 < NB || s + 1 < s1) xn = load_x32(xs + 32 * (bt + 1));
+                            QG_SCHED_FENCE();
+                        }
+                    }
+                    xb = xn;
+                }
+#pragma unroll
+                for (int j = 0; j < L; ++j) cur[j] = nxt[j];
+            }
+            const float zf = (float)((zword >> (F::ZBITS * (gabs % ZPER))) & ((1u << F::ZBITS) - 1u));
+            yacc = fmaf(scale, fmaf(-zf, lane_value(xsum, gl), acc), yacc);
+        }
+    }
+    finish_tile(P, tile, chunk, yacc, red);
+}
+
+// ---------------------------------------------------------------------------------------
+// Any other group size (a whole number of cells): one cell at a time, group sums added up
+// serially.  Slow and simple; covers shapes the two kernels above do not.
+// ---------------------------------------------------------------------------------------
+template <int BITS>
+__global__ __launch_bounds__(1024) void gemv_generic(const GemvArgs A)
+{
+    using F = Fmt<BITS>;
+    constexpr int L = loads_per_step<BITS>();
+    constexpr int ZPER = 32 / F::ZBITS;
+    __shared__ float red[16][QG_WAVE];
+
+    const int pi = find_problem(A, blockIdx.x);
+    const GemvProblem &P = A.p[pi];
+    const int local = blockIdx.x - P.block_begin;
+    const int tile = local / P.chunks, chunk = local % P.chunks;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int waves = blockDim.x >> 6;
+    const int cpg = P.group / F::CELL;
+
+    // here steps_per_wave counts groups per wavefront
+    int g0 = (chunk * waves + wave) * P.steps_per_wave;
+    int g1 = g0 + P.steps_per_wave;
+    if (g1 > P.ngroups) g1 = P.ngroups;
+
+    float yacc = 0.0f;
+    const uint4 *codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
+    const float *sc = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
+    const uint32_t *zr = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+    const float *__restrict__ x = P.x;
+    for (int g = g0; g < g1; ++g) {
+        float acc = 0.0f, sx = 0.0f;
+        for (int c = g * cpg; c < (g + 1) * cpg; ++c) {
+            const int unit = c >> 2;
+            uint4 v[3];
+#pragma unroll
+            for (int p = 0; p < F::PLANES; ++p) v[p] = codes[((size_t)unit * F::PLANES + p) * QG_WAVE];
+            const float *xs = x + (size_t)c * F::CELL;
+            // the cell sits at position (c & 3) of its unit; place its x values where
+            // octet_dot expects them inside a batch of 32
+            constexpr int CPB = 32 / F::CELL;                 // cells per batch
+            const int bt = (c & 3) / CPB, pos = (c & 3) % CPB;
+            XBatch xb;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                const int rel = i - pos * F::CELL;
+                const float val = (rel >= 0 && rel < F::CELL) ? xs[rel] : 0.0f;
+                if (i < 16) xb.lo[i] = val; else xb.hi[i - 16] = val;
+            }
+#pragma unroll
+            for (int o = 0; o < 4; ++o)
+                if (o / (4 / CPB) == pos) acc = octet_dot<BITS>(v, bt, o, xb, acc);
+#pragma unroll
+            for (int i = 0; i < F::CELL; ++i) sx += xs[i];
+        }
+        const uint32_t zword = zr[(size_t)(g / ZPER) * QG_WAVE];
+        const float zf = (float)((zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u));
+        yacc = fmaf(sc[(size_t)g * QG_WAVE], fmaf(-zf, sx, acc), yacc);
+    }
+    finish_tile(P, tile, chunk, yacc, red);
+}
+
+__global__ void fill_zero_u32(uint32_t *p, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// ------------------------------------------------------------------ host side
+
+int g_tune_wpb = 0;
+int g_tune_bytes_per_wave = 0;
+
+enum Kind { KIND_STATIC, KIND_RUNTIME, KIND_GENERIC };
+
+// The K-split of one problem: work items along K are steps for the two fast kernels and
+// groups for the generic one; a wavefront takes `spw` consecutive items.
+struct Plan {
+    Kind kind;
+    int64_t items;
+    int64_t quantum;   // spw must be a multiple of this (steps per group, runtime kernel)
+    int64_t max_spw;   // x-hat is kept one group per lane: at most 64 groups per wavefront
+    size_t item_bytes; // packed code bytes one wavefront reads per item
+};
+
+Plan make_plan(const QgLayout &L)
+{
+    Plan pl;
+    const int cpg = L.group / L.cell;
+    const int cps = 4 * L.step_units;
+    const int64_t step_codes = (int64_t)L.unit * L.step_units;
+    const size_t step_bytes = (size_t)L.step_units * L.planes * QG_WAVE * 16;
+    pl.kind = KIND_GENERIC;
+    if (L.K % step_codes == 0) {
+        if (cpg <= cps && (cpg & (cpg - 1)) == 0) pl.kind = KIND_STATIC;
+        else if (L.group % step_codes == 0) pl.kind = KIND_RUNTIME;
+    }
+    if (pl.kind == KIND_STATIC) {
+        pl.items = L.steps;
+        pl.quantum = 1;
+        pl.max_spw = 64 / (cps / cpg);
+        pl.item_bytes = step_bytes;
+    } else if (pl.kind == KIND_RUNTIME) {
+        pl.items = L.steps;
+        pl.quantum = L.group / step_codes;
+        pl.max_spw = 64 * pl.quantum;
+        pl.item_bytes = step_bytes;
+    }
+    // a fast kernel that cannot cover K with 16 wavefronts x QG_MAX_CHUNKS blocks: generic
+    if (pl.kind != KIND_GENERIC &&
+        (pl.items + pl.max_spw - 1) / pl.max_spw > (int64_t)16 * QG_MAX_CHUNKS)
+        pl.kind = KIND_GENERIC;
+    if (pl.kind == KIND_GENERIC) {
+        pl.items = L.ngroups;
+        pl.quantum = 1;
+        pl.max_spw = (int64_t)1 << 30;
+        pl.item_bytes = (size_t)L.group * L.bits / 8 * QG_WAVE;
+    }
+    return pl;
+}
+
+// Items per wavefront for a target of `per_wave` bytes, raised if QG_MAX_CHUNKS blocks of
+// `wpb` wavefronts would not cover K.  Returns 0 if `wpb` wavefronts cannot do it.
+int64_t items_per_wave(const Plan &pl, size_t per_wave, int wpb)
+{
+    int64_t spw = (int64_t)((per_wave + pl.item_bytes / 2) / pl.item_bytes);
+    if (spw < 1) spw = 1;
+    const int64_t floor_spw = (pl.items + (int64_t)wpb * QG_MAX_CHUNKS - 1) / ((int64_t)wpb * QG_MAX_CHUNKS);
+    if (spw < floor_spw) spw = floor_spw;
+    spw = (spw + pl.quantum - 1) / pl.quantum * pl.quantum;
+    if (spw > pl.max_spw) spw = pl.max_spw;
+    if ((pl.items + spw * wpb - 1) / (spw * wpb) > QG_MAX_CHUNKS) return 0;
+    return spw;
+}
+
+size_t workspace_for(const QgLayout &L)
+{
+    const size_t partial = (size_t)L.tiles * QG_MAX_CHUNKS * QG_WAVE * sizeof(float);
+    const size_t counters = qg_round_up((size_t)L.tiles * sizeof(unsigned), QG_SECTION_ALIGN);
+    return partial + counters;
+}
+
+template <int BITS>
+void launch_static(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+{
+    switch (cpg) {
+    case 1: hipLaunchKernelGGL((gemv_static<BITS, 1>), dim3(blocks), dim3(threads), 0, st, A); break;
+    case 2: hipLaunchKernelGGL((gemv_static<BITS, 2>), dim3(blocks), dim3(threads), 0, st, A); break;
+    case 4: hipLaunchKernelGGL((gemv_static<BITS, 4>), dim3(blocks), dim3(threads), 0, st, A); break;
+    case 8: hipLaunchKernelGGL((gemv_static<BITS, 8>), dim3(blocks), dim3(threads), 0, st, A); break;
+    case 16:
+        if constexpr (BITS != 3)
+            hipLaunchKernelGGL((gemv_static<BITS, 16>), dim3(blocks), dim3(threads), 0, st, A);
+        break;
+    }
+}
+
+// One launch for problems that share (bits, group, kernel kind).
+int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const size_t *ws_off,
+                 char *workspace, hipStream_t st)
+{
+    GemvArgs A;
+    A.count = count;
+    QgLayout L[QG_MAX_GROUPED];
+    Plan pl[QG_MAX_GROUPED];
+    size_t code_bytes = 0;
+    for (int i = 0; i < count; ++i) {
+        const qg_gemv_desc &d = descs[idx[i]];
+        qg_make_layout(d.N, d.K, d.bits, d.group, &L[i]);
+        pl[i] = make_plan(L[i]);
+        code_bytes += (size_t)L[i].tiles * L[i].units * L[i].planes * QG_WAVE * 16;
+    }
+    const Kind kind = pl[0].kind;
+
+    // Enough wavefronts to cover the chip about twelve deep, between 4 KB and 16 KB each.
+    size_t per_wave = (size_t)g_tune_bytes_per_wave;
+    if (per_wave == 0) {
+        per_wave = code_bytes / (256 * 12);
+        if (per_wave < 4096) per_wave = 4096;
+        if (per_wave > 16384) per_wave = 16384;
+    }
+    int wpb = g_tune_wpb > 0 ? g_tune_wpb : 4;
+    for (int i = 0; i < count; ++i)
+        while (items_per_wave(pl[i], per_wave, wpb) == 0) {
+            if (wpb == 16) return QG_ERR_UNSUPPORTED;
+            wpb = wpb * 2 > 16 ? 16 : wpb * 2;
+        }
+
+    int blocks = 0;
+    for (int i = 0; i < count; ++i) {
+        const qg_gemv_desc &d = descs[idx[i]];
+        GemvProblem &P = A.p[i];
+        const char *base = (const char *)d.packed;
+        P.codes = (const uint4 *)(base + L[i].codes_off);
+        P.scales = (const float *)(base + L[i].scales_off);
+        P.zeros = (const uint32_t *)(base + L[i].zeros_off);
+        P.x = d.x;
+        P.y = d.y;
+        char *ws = workspace + ws_off[idx[i]];
+        P.partial = (float *)ws;
+        P.counter = (unsigned *)(ws + (size_t)L[i].tiles * QG_MAX_CHUNKS * QG_WAVE * sizeof(float));
+        P.N = (int)L[i].N;
+        P.K = (int)L[i].K;
+        P.tiles = (int)L[i].tiles;
+        P.steps = (int)L[i].steps;
+        P.ngroups = (int)L[i].ngroups;
+        P.zwords = (int)L[i].zwords;
+        P.group = L[i].group;
+        P.steps_per_group = (int)pl[i].quantum;
+        const int64_t spw = items_per_wave(pl[i], per_wave, wpb);
+        P.steps_per_wave = (int)spw;
+        P.chunks = (int)((pl[i].items + spw * wpb - 1) / (spw * wpb));
+        P.block_begin = blocks;
+        const int64_t nb = (int64_t)P.tiles * P.chunks;
+        if (blocks + nb > 0x3fffffff) return QG_ERR_SHAPE;
+        blocks += (int)nb;
+    }
+
+    const unsigned threads = (unsigned)wpb * QG_WAVE;
+    const int bits = L[0].bits;
+    if (kind == KIND_STATIC) {
+        const int cpg = L[0].group / L[0].cell;
+        if (bits == 4) launch_static<4>(cpg, blocks, threads, st, A);
+        else if (bits == 2) launch_static<2>(cpg, blocks, threads, st, A);
+        else launch_static<3>(cpg, blocks, threads, st, A);
+    } else if (kind == KIND_RUNTIME) {
+        if (bits == 4) hipLaunchKernelGGL(gemv_runtime<4>, dim3(blocks), dim3(threads), 0, st, A);
+        else if (bits == 2) hipLaunchKernelGGL(gemv_runtime<2>, dim3(blocks), dim3(threads), 0, st, A);
+        else hipLaunchKernelGGL(gemv_runtime<3>, dim3(blocks), dim3(threads), 0, st, A);
+    } else {
+        if (bits == 4) hipLaunchKernelGGL(gemv_generic<4>, dim3(blocks), dim3(threads), 0, st, A);
+        else if (bits == 2) hipLaunchKernelGGL(gemv_generic<2>, dim3(blocks), dim3(threads), 0, st, A);
+        else hipLaunchKernelGGL(gemv_generic<3>, dim3(blocks), dim3(threads), 0, st, A);
+    }
+    return qg_launch_status();
+}
+
+}  // namespace
+
+extern "C" int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave)
+{
+    if (waves_per_block < 0 || waves_per_block > 16 || bytes_per_wave < 0) return QG_ERR_SHAPE;
+    g_tune_wpb = waves_per_block;
+    g_tune_bytes_per_wave = bytes_per_wave;
+    return QG_OK;
+}
+
+size_t qg_gemm_workspace_bytes(const QgLayout &L, int M);   // qg_gemm_small.hip
+
+extern "C" size_t qg_workspace_bytes(int64_t N, int64_t K, int bits, int group, int M)
+{
+    QgLayout L;
+    if (M <= 0 || qg_make_layout(N, K, bits, group, &L) != QG_OK) return 0;
+    return M == 1 ? workspace_for(L) : qg_gemm_workspace_bytes(L, M);
+}
+
+extern "C" int qg_workspace_init(void *workspace, size_t bytes, void *stream)
+{
+    if (!workspace) return QG_ERR_NULL;
+    if (((uintptr_t)workspace & 3u) || (bytes & 3u)) return QG_ERR_ALIGN;
+    const size_t n = bytes / 4;
+    if (n == 0) return QG_OK;
+    hipLaunchKernelGGL(fill_zero_u32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, (uint32_t *)workspace, n);
+    return qg_launch_status();
+}
+
+extern "C" int qg_gemv_grouped(const qg_gemv_desc *descs, int count, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    if (!descs) return QG_ERR_NULL;
+    if (count <= 0) return QG_ERR_SHAPE;
+    if (count > QG_MAX_GROUPED) return QG_ERR_UNSUPPORTED;
+    size_t ws_off[QG_MAX_GROUPED];
+    size_t need = 0;
+    for (int i = 0; i < count; ++i) {
+        QgLayout L;
+        const int rc = qg_make_layout(descs[i].N, descs[i].K, descs[i].bits, descs[i].group, &L);
+        if (rc != QG_OK) return rc;
+        if (!descs[i].packed || !descs[i].x || !descs[i].y) return QG_ERR_NULL;
+        // x is read with 64-byte scalar loads
+        if (!qg_aligned16(descs[i].packed) || ((uintptr_t)descs[i].x & 63u)) return QG_ERR_ALIGN;
+        ws_off[i] = need;
+        need += workspace_for(L);
+    }
+    if (!workspace || workspace_bytes < need) return QG_ERR_WORKSPACE;
+    if (!qg_aligned16(workspace)) return QG_ERR_ALIGN;
+
+    // one launch per distinct (bits, group, kernel kind)
+    bool done[QG_MAX_GROUPED] = {false};
+    for (int i = 0; i < count; ++i) {
+        if (done[i]) continue;
+        QgLayout Li;
+        qg_make_layout(descs[i].N, descs[i].K, descs[i].bits, descs[i].group, &Li);
+        int idx[QG_MAX_GROUPED], n = 0;
+        for (int j = i; j < count; ++j) {
+            if (done[j]) continue;
+            QgLayout Lj;
+            qg_make_layout(descs[j].N, descs[j].K, descs[j].bits, descs[j].group, &Lj);
+            if (Lj.bits == Li.bits && Lj.group == Li.group && make_plan(Lj).kind == make_plan(Li).kind) {
+                idx[n++] = j;
+                done[j] = true;
+            }
+        }
+        const int rc = launch_class(descs, idx, n, ws_off, (char *)workspace, (hipStream_t)stream);
+        if (rc != QG_OK) return rc;
+    }
+    return QG_OK;
+}
+
+extern "C" int qg_gemv(const void *packed, int64_t N, int64_t K, int bits, int group,
+                       const float *x, float *y, void *workspace, size_t workspace_bytes,
+                       void *stream)
+{
+    qg_gemv_desc d;
+    d.packed = packed;
+    d.N = N;
+    d.K = K;
+    d.bits = bits;
+    d.group = group;
+    d.x = x;
+    d.y = y;
+    return qg_gemv_grouped(&d, 1, workspace, workspace_bytes, stream);
+}

@@ -1,0 +1,248 @@
+"""GPU parity: the HIP library, called through its C-ABI, against the CPU oracle on the same
+seeded inputs.  Quantize, pack and unpack must agree bit for bit; products must agree within
+1e-4 of ||What[n,:]|| ||x|| (fp32 path)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2307_03738_amd import synth
+from tests.util import dev, host, scaled_error
+
+pytestmark = pytest.mark.gpu
+
+TOL_FP32 = 1e-4
+
+
+@pytest.fixture(scope="module")
+def qg():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    from paper_2307_03738_amd import binding
+    binding.lib()
+    return binding
+
+
+def _announce(*what):
+    print("[case]", *what, flush=True)
+
+
+# ------------------------------------------------------------------ quantize (bit-exact)
+
+QUANT_CASES = [  # N, K, bits, group, std, outliers
+    (512, 512, 4, 64, 0.02, False),       # configuration 1
+    (200, 768, 4, 128, 0.02, True),
+    (130, 640, 3, 64, 0.02, False),
+    (77, 512, 2, 32, 0.015, False),
+    (64, 256, 2, 16, 0.02, False),
+    (33, 384, 3, 32, 0.02, True),
+    (16, 1024, 4, 1024, 0.02, True),      # one group per output (full column)
+    (9, 96, 4, 8, 0.02, False),
+    (5, 120, 4, 24, 1.0, False),
+]
+
+
+@pytest.mark.parametrize("N,K,bits,group,std,outliers", QUANT_CASES)
+def test_quantize_bit_exact(qg, oracle, N, K, bits, group, std, outliers):
+    _announce("quantize", N, K, bits, group)
+    W, _ = synth.small_case(N * 7 + K, N, K, std, outliers)
+    q0, s0, z0 = oracle.quantize(W, bits, group)
+    q, s, z = qg.qg_quantize(dev(W), bits, group)
+    assert np.array_equal(host(q), q0)
+    assert np.array_equal(host(s).view(np.uint32), s0.view(np.uint32))
+    assert np.array_equal(host(z), z0)
+
+
+def test_quantize_special_values_bit_exact(qg, oracle):
+    _announce("quantize special values")
+    G = 16
+    rows = [
+        np.array([0.0, 15.0, 0.5, 1.5, 2.5, 3.5, 6.5, 13.5] + [0.0] * 8),      # exact ties, s = 1
+        np.array([-1.0, 14.0, 0.5, 1.5, 2.5, -0.5] + [0.0] * 10),               # ties with odd zero
+        np.zeros(G),                                                            # range 0
+        np.linspace(0.25, 1.0, G),                                              # all positive
+        -np.linspace(0.25, 1.0, G),                                             # all negative
+        np.full(G, 1e-41),                                                      # denormals
+        np.array([-0.0] * 8 + [3e-39] * 8),
+        np.array([1e30, -1e30] + [1.0] * 14),                                   # huge range
+    ]
+    W = np.stack(rows).astype(np.float32)
+    for bits in (2, 3, 4):
+        q0, s0, z0 = oracle.quantize(W, bits, G)
+        q, s, z = qg.qg_quantize(dev(W), bits, G)
+        assert np.array_equal(host(q), q0), bits
+        assert np.array_equal(host(s).view(np.uint32), s0.view(np.uint32)), bits
+        assert np.array_equal(host(z), z0), bits
+
+
+# ------------------------------------------------------------------ pack / unpack (bit-exact)
+
+PACK_CASES = [(512, 512, 4, 64), (200, 768, 4, 128), (130, 640, 3, 64), (77, 512, 2, 32),
+              (64, 256, 2, 16), (33, 384, 3, 32), (1, 96, 3, 96), (65, 160, 4, 32), (3, 64, 2, 64)]
+
+
+@pytest.mark.parametrize("N,K,bits,group", PACK_CASES)
+def test_canonical_pack_matches_oracle_words(qg, oracle, N, K, bits, group):
+    _announce("canonical pack", N, K, bits, group)
+    rng = np.random.default_rng(N + K + bits)
+    q = rng.integers(0, 1 << bits, (N, K), dtype=np.uint8)
+    z = rng.integers(0, 1 << bits, (N, K // group), dtype=np.uint8)
+    s = rng.standard_normal((N, K // group)).astype(np.float32)
+    blob = host(qg.qg_pack(dev(q), dev(s), dev(z), bits, group, qg.QG_LAYOUT_CANONICAL))
+    P, St, Zp = oracle.pack_codes(q, bits), oracle.transpose_scales(s), oracle.pack_zeros(z, bits)
+    ref = np.concatenate([P.ravel().view(np.uint8), St.ravel().view(np.uint8), Zp.ravel().view(np.uint8)])
+    assert blob.size == ref.size == qg.qg_packed_bytes(N, K, bits, group, qg.QG_LAYOUT_CANONICAL)
+    assert np.array_equal(blob, ref)
+    # and back, from the oracle's words
+    q2, s2, z2 = qg.qg_unpack(dev(ref), N, K, bits, group, qg.QG_LAYOUT_CANONICAL)
+    assert np.array_equal(host(q2), q) and np.array_equal(host(z2), z)
+    assert np.array_equal(host(s2).view(np.uint32), s.view(np.uint32))
+
+
+@pytest.mark.parametrize("N,K,bits,group", PACK_CASES)
+def test_device_pack_unpack_identity(qg, N, K, bits, group):
+    _announce("device pack round trip", N, K, bits, group)
+    rng = np.random.default_rng(N * 3 + K + bits)
+    q = rng.integers(0, 1 << bits, (N, K), dtype=np.uint8)
+    z = rng.integers(0, 1 << bits, (N, K // group), dtype=np.uint8)
+    s = rng.standard_normal((N, K // group)).astype(np.float32)
+    blob = qg.qg_pack(dev(q), dev(s), dev(z), bits, group, qg.QG_LAYOUT_DEVICE)
+    q2, s2, z2 = qg.qg_unpack(blob, N, K, bits, group, qg.QG_LAYOUT_DEVICE)
+    assert np.array_equal(host(q2), q) and np.array_equal(host(z2), z)
+    assert np.array_equal(host(s2).view(np.uint32), s.view(np.uint32))
+
+
+# ------------------------------------------------------------------ GEMV (tolerance)
+
+def _gemv_case(qg, oracle, W, x, bits, group, tuning=(0, 0)):
+    N, K = W.shape
+    q0, s0, z0 = oracle.quantize(W, bits, group)
+    y_ref = oracle.matvec(q0, s0, z0, group, x)
+    norms = oracle.row_norms(q0, s0, z0, group)
+    q, s, z = qg.qg_quantize(dev(W), bits, group)
+    assert np.array_equal(host(q), q0) and np.array_equal(host(z), z0)
+    assert np.array_equal(host(s).view(np.uint32), s0.view(np.uint32))
+    blob = qg.qg_pack(q, s, z, bits, group, qg.QG_LAYOUT_DEVICE)
+    qg.qg_set_gemv_tuning(*tuning)
+    try:
+        ws = qg.new_workspace(qg.qg_workspace_bytes(N, K, bits, group, 1))
+        y = torch.full((N + 64,), 7.0, dtype=torch.float32, device="cuda")   # canary behind y
+        qg.qg_gemv(blob, N, K, bits, group, dev(x), y[:N], ws)
+        y2 = torch.empty(N, dtype=torch.float32, device="cuda")
+        qg.qg_gemv(blob, N, K, bits, group, dev(x), y2, ws)                    # workspace reuse
+        torch.cuda.synchronize()
+    finally:
+        qg.qg_set_gemv_tuning(0, 0)
+    yh = host(y)
+    assert np.all(yh[N:] == 7.0), "write past the end of y"
+    assert np.array_equal(yh[:N], host(y2)), "not deterministic / workspace not left clean"
+    assert not host(ws).any(), "workspace not left zeroed"
+    return scaled_error(yh[:N], y_ref, norms, x)
+
+
+GEMV_CASES = [  # N, K, bits, group   -- (kernel flavour)
+    (512, 512, 4, 64),        # configuration 1, static groups
+    (200, 1024, 4, 128),      # ragged N (3 tiles + 8)
+    (130, 512, 4, 32),
+    (70, 256, 4, 16),
+    (64, 128, 4, 8),
+    (257, 1024, 2, 32),
+    (130, 512, 2, 16),
+    (96, 768, 2, 64),
+    (200, 1024, 2, 256),
+    (130, 1536, 3, 64),
+    (77, 512, 3, 32),
+    (64, 1024, 3, 128),
+    (200, 512, 3, 256),
+    (150, 1024, 4, 256),      # group = two steps (runtime-group kernel)
+    (100, 2048, 4, 2048),     # one group per output, eq. (1)
+    (100, 1024, 2, 512),
+    (66, 1536, 3, 768),
+    (90, 480, 4, 24),         # generic kernel: group not a power of two
+    (90, 416, 4, 32),         # generic kernel: K not a whole number of steps
+    (50, 288, 3, 96),
+    (40, 336, 2, 48),
+    (1, 128, 4, 128),         # a single output
+]
+
+
+@pytest.mark.parametrize("N,K,bits,group", GEMV_CASES)
+def test_gemv_matches_oracle(qg, oracle, N, K, bits, group):
+    _announce("gemv", N, K, bits, group)
+    W, x = synth.small_case(N + 3 * K + bits, N, K, 0.02, True)
+    err = _gemv_case(qg, oracle, W, x, bits, group)
+    assert err <= TOL_FP32, err
+
+
+@pytest.mark.parametrize("tuning", [(1, 4096), (2, 4096), (4, 8192), (8, 4096), (16, 4096), (4, 65536)])
+@pytest.mark.parametrize("N,K,bits,group", [(200, 4096, 4, 128), (130, 3072, 3, 64), (130, 4096, 2, 32),
+                                            (70, 4096, 4, 1024)])
+def test_gemv_k_split_shapes(qg, oracle, N, K, bits, group, tuning):
+    # the same product under different wavefront / workgroup splits of K, including the
+    # path where the last-arriving workgroup adds the partial vectors
+    _announce("gemv split", N, K, bits, group, tuning)
+    W, x = synth.small_case(N + K + bits, N, K, 0.02, False)
+    err = _gemv_case(qg, oracle, W, x, bits, group, tuning)
+    assert err <= TOL_FP32, err
+
+
+def test_gemv_zero_input_and_unit_scale(qg, oracle):
+    _announce("gemv x = 0, s = 1 z = 0")
+    rng = np.random.default_rng(5)
+    N, K, bits, group = 130, 512, 4, 64
+    q = rng.integers(0, 16, (N, K), dtype=np.uint8)
+    s = np.ones((N, K // group), np.float32)
+    z = np.zeros((N, K // group), np.uint8)
+    blob = qg.qg_pack(dev(q), dev(s), dev(z), bits, group, qg.QG_LAYOUT_DEVICE)
+    y = qg.qg_gemv(blob, N, K, bits, group, torch.zeros(K, device="cuda"))
+    assert not host(y).any()
+    x = rng.integers(-8, 9, K).astype(np.float32)            # small integers: fp32 sums are exact
+    y = host(qg.qg_gemv(blob, N, K, bits, group, dev(x)))
+    assert np.array_equal(y.astype(np.int64), q.astype(np.int64) @ x.astype(np.int64))
+
+
+def test_gemv_grouped_mixed_problems(qg, oracle):
+    _announce("gemv grouped, mixed shapes and formats")
+    specs = [(200, 1024, 4, 128), (130, 512, 4, 128), (64, 1536, 3, 64), (90, 480, 4, 24),
+             (257, 1024, 2, 32), (512, 512, 4, 128), (100, 2048, 4, 2048)]
+    problems, refs = [], []
+    for i, (N, K, bits, group) in enumerate(specs):
+        W, x = synth.small_case(900 + i, N, K, 0.02, True)
+        q0, s0, z0 = oracle.quantize(W, bits, group)
+        refs.append((oracle.matvec(q0, s0, z0, group, x), oracle.row_norms(q0, s0, z0, group), x))
+        q, s, z = qg.qg_quantize(dev(W), bits, group)
+        problems.append(dict(packed=qg.qg_pack(q, s, z, bits, group), N=N, K=K, bits=bits, group=group,
+                             x=dev(x), y=torch.empty(N, dtype=torch.float32, device="cuda")))
+    ys = qg.qg_gemv_grouped(problems)
+    torch.cuda.synchronize()
+    for y, (y_ref, norms, x) in zip(ys, refs):
+        assert scaled_error(host(y), y_ref, norms, x) <= TOL_FP32
+
+
+# ------------------------------------------------------------------ full benchmark sizes
+
+FULL = [("C2", 0), ("C2", 4), ("C2", 6), ("C3", 0), ("C3", 4), ("C3", 6), ("C4", 0), ("C4", 4), ("C4", 6)]
+
+
+@pytest.mark.parametrize("name,index", FULL)
+def test_full_size_matrix(qg, oracle, name, index):
+    # every distinct shape of the three layer sets, at full size, all outputs compared
+    cfg = synth.CONFIGS[name]
+    N, K = cfg.shapes[index]
+    _announce("full size", name, index, N, K, cfg.bits, cfg.group)
+    W, (x,) = synth.matrix(cfg, index)
+    q0, s0, z0 = oracle.quantize(W, cfg.bits, cfg.group)
+    Wd = dev(W)
+    del W
+    q, s, z = qg.qg_quantize(Wd, cfg.bits, cfg.group)
+    del Wd
+    assert np.array_equal(host(q), q0)
+    assert np.array_equal(host(s).view(np.uint32), s0.view(np.uint32))
+    assert np.array_equal(host(z), z0)
+    blob = qg.qg_pack(q, s, z, cfg.bits, cfg.group)
+    q2, s2, z2 = qg.qg_unpack(blob, N, K, cfg.bits, cfg.group)
+    assert torch.equal(q2, q) and torch.equal(z2, z) and torch.equal(s2.view(torch.int32), s.view(torch.int32))
+    y = host(qg.qg_gemv(blob, N, K, cfg.bits, cfg.group, dev(x)))
+    y_ref = oracle.matvec(q0, s0, z0, cfg.group, x)
+    err = scaled_error(y, y_ref, oracle.row_norms(q0, s0, z0, cfg.group), x)
+    print(f"[full] {name}[{index}] scaled error {err:.3e}", flush=True)
+    assert err <= TOL_FP32, err

@@ -1,0 +1,77 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, sizes blobs as the paper's memory formula says, and rejects bad arguments before
+touching the GPU.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "qg.h")
+
+
+@pytest.fixture(scope="module")
+def qg():
+    from paper_2307_03738_amd import binding
+    binding.lib()
+    return binding
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qg_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(qg):
+    names = _declared_symbols()
+    assert {"qg_quantize", "qg_pack", "qg_unpack", "qg_gemv", "qg_gemv_grouped", "qg_gemm_small",
+            "qg_packed_bytes", "qg_workspace_bytes", "qg_workspace_init", "qg_status_string",
+            "qg_cell", "qg_set_gemv_tuning"} <= set(names)
+    L = qg.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_cells(qg):
+    # Section 3: 8 codes per word at 4 bits, 16 at 2 bits, 32 codes per three words at 3 bits
+    assert [qg.qg_cell(b) for b in (4, 2, 3)] == [8, 16, 32]
+    assert qg.qg_cell(5) == 0
+
+
+@pytest.mark.parametrize("N,K,bits,group", [(512, 512, 4, 64), (4096, 11008, 4, 128),
+                                            (5120, 13824, 3, 64), (8192, 22016, 2, 32), (64, 128, 4, 128)])
+def test_canonical_bytes_follow_the_memory_formula(qg, oracle, N, K, bits, group):
+    # b*N*K + (32 + b)*N*K/G bits, with the zero-point stream padded to whole words per output
+    got = qg.qg_packed_bytes(N, K, bits, group, qg.QG_LAYOUT_CANONICAL)
+    zero_words = (K // group * bits + 31) // 32
+    assert got == N * K * bits // 8 + N * (K // group) * 4 + N * zero_words * 4
+    if (K // group * bits) % 32 == 0:
+        assert got * 8 == oracle.storage_bits(N, K, bits, group)
+    # the device layout holds the same information plus padding only
+    dev = qg.qg_packed_bytes(N, K, bits, group, qg.QG_LAYOUT_DEVICE)
+    assert dev >= N * K * bits // 8 + N * (K // group) * 4
+    assert dev <= got * 1.02 + 3 * 256 + 64 * 3 * 1024
+
+
+def test_bad_shapes_are_rejected_without_a_gpu(qg):
+    assert qg.qg_packed_bytes(64, 100, 4, 32) == 0          # K % G != 0
+    assert qg.qg_packed_bytes(64, 96, 4, 12) == 0           # G not a multiple of the 4-bit cell
+    assert qg.qg_packed_bytes(64, 96, 3, 48) == 0           # G not a multiple of the 3-bit cell
+    assert qg.qg_packed_bytes(64, 96, 5, 32) == 0           # bits
+    assert qg.qg_packed_bytes(0, 96, 4, 32) == 0
+    assert qg.qg_workspace_bytes(64, 96, 4, 32, 0) == 0
+    L = qg.lib()
+    # null pointers and misaligned pointers: an error code, nothing enqueued
+    assert L.qg_gemv(None, 64, 128, 4, 32, None, None, None, 0, None) == 1
+    assert L.qg_quantize(None, 64, 128, 4, 32, None, None, None, None) == 1
+    assert L.qg_quantize(16, 64, 128, 7, 32, 16, 16, 16, None) == 3
+    assert L.qg_quantize(16, 64, 100, 4, 32, 16, 16, 16, None) == 2
+    assert L.qg_quantize(20, 64, 128, 4, 32, 16, 16, 16, None) == 4
+    assert L.qg_pack(16, 16, 16, 64, 128, 4, 32, 9, 16, None) == 3
+    assert L.qg_gemv(16, 64, 128, 4, 32, 16, 16, 16, 0, None) == 5      # workspace too small
+    assert L.qg_gemv_grouped(None, 1, None, 0, None) == 1
+    assert L.qg_set_gemv_tuning(99, 0) == 2
+    assert L.qg_set_gemv_tuning(0, 0) == 0
+    assert b"aligned" in L.qg_status_string(4)
