@@ -41,6 +41,7 @@ struct GemvProblem {
 
 struct GemvArgs {
     int count;
+    int block_begin[QG_MAX_GROUPED];   // first block of problem i; INT_MAX beyond `count`
     GemvProblem p[QG_MAX_GROUPED];
 };
 
@@ -147,42 +148,54 @@ __device__ inline float octet_dot(const uint4 *v, int bt, int o, const XBatch &x
     return acc;
 }
 
-__device__ inline float wave_sum(float v)
+// ---- cross-lane sums on the DPP path (no LDS, no memory) ------------------------------
+// v + (v moved across lanes by the DPP control CTRL); rows that ROW_MASK disables add 0.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ inline float dpp_add(float v)
 {
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false);
+    return v + __int_as_float(moved);
+}
+#define QG_DPP_QUAD_XOR1 0xB1      // quad_perm [1,0,3,2]
+#define QG_DPP_QUAD_XOR2 0x4E      // quad_perm [2,3,0,1]
+#define QG_DPP_HALF_MIRROR 0x141   // lane i <-> 7-i inside each 8 lanes
+#define QG_DPP_ROW_MIRROR 0x140    // lane i <-> 15-i inside each row of 16 lanes
+#define QG_DPP_BCAST15 0x142       // lane 15 of each row to the next row
+#define QG_DPP_BCAST31 0x143       // lane 31 to rows 2 and 3
+
+__device__ inline float uniform_lane(float v, int lane)     // lane is a compile-time constant
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+// Sums of consecutive segments of SEG lanes (SEG = 8, 16, 32 or 64) of v, returned as
+// wavefront-uniform values out[0 .. 64/SEG).  This is x-hat of Algorithm 1 for one group
+// when lane l holds x[k0 + l].
+template <int SEG>
+__device__ inline void segment_sums(float v, float *out)
+{
+    v = dpp_add<QG_DPP_QUAD_XOR1>(v);
+    v = dpp_add<QG_DPP_QUAD_XOR2>(v);
+    v = dpp_add<QG_DPP_HALF_MIRROR>(v);                      // every 8 lanes hold their sum
+    if constexpr (SEG == 8) {
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-    return v;
-}
-
-__device__ inline float lane_value(float v, int src_lane)   // src_lane uniform
-{
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
-}
-
-// x-hat per group: returns, in lane j, sum of x[kbeg + j*G .. + G) for j < ng <= 64.
-// Handles any G >= 64 and G in {8, 16, 32}.
-__device__ inline float group_sums(const float *__restrict__ x, int kbeg, int ng, int G, int lane)
-{
-    float r = 0.0f;
-    if (G >= 64) {
-        for (int j = 0; j < ng; ++j) {
-            float v = 0.0f;
-            for (int i = lane; i < G; i += 64) v += x[kbeg + j * G + i];
-            v = wave_sum(v);
-            if (lane == j) r = v;
-        }
-    } else {
-        const int per = 64 / G;                      // groups per 64-wide window
-        const int windows = (ng + per - 1) / per;
-        for (int w = 0; w < windows; ++w) {
-            const int i = w * 64 + lane;
-            float v = i < ng * G ? x[kbeg + i] : 0.0f;
-            for (int off = 1; off < G; off <<= 1) v += __shfl_xor(v, off);
-            const float t = __shfl(v, (lane % per) * G);
-            if (lane / per == w) r = t;
-        }
+        for (int i = 0; i < 8; ++i) out[i] = uniform_lane(v, 8 * i);
+        return;
     }
-    return r;
+    v = dpp_add<QG_DPP_ROW_MIRROR>(v);                       // every row of 16 holds its sum
+    if constexpr (SEG == 16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[i] = uniform_lane(v, 16 * i + 15);
+        return;
+    }
+    v = dpp_add<QG_DPP_BCAST15, 0xa>(v);                     // rows 1 and 3 += previous row
+    if constexpr (SEG == 32) {
+        out[0] = uniform_lane(v, 31);
+        out[1] = uniform_lane(v, 63);
+        return;
+    }
+    v = dpp_add<QG_DPP_BCAST31, 0xc>(v);                     // row 3 += rows 0 and 1
+    out[0] = uniform_lane(v, 63);
 }
 
 // K-split epilogue.  Every wavefront of the block passes its 64 partial outputs; wavefront
@@ -220,20 +233,118 @@ __device__ inline void finish_tile(const GemvProblem &P, int tile, int chunk, fl
     if (lane == 0) P.counter[tile] = 0u;               // leave the workspace zeroed
 }
 
+// Index of the problem a block belongs to: the last one whose first block is <= bid.
 __device__ inline int find_problem(const GemvArgs &A, int bid)
 {
     int p = 0;
-    for (int i = 1; i < A.count; ++i)
-        if (bid >= A.p[i].block_begin) p = i;
+#pragma unroll
+    for (int i = 1; i < QG_MAX_GROUPED; ++i)
+        if (bid >= A.block_begin[i]) p = i;
     return p;
 }
 
-template <int BITS>
-__device__ inline void load_step(uint4 *dst, const uint4 *__restrict__ base, int step)
+// What one wavefront fetches for one step: the codes, the scale and zero word(s) of the
+// step's groups (GPS = 0: groups span steps, metadata is fetched per group instead) and the
+// step's x values once more, one per lane, for the group sums.
+template <int BITS, int GPS>
+struct StepData {
+    static constexpr int L = loads_per_step<BITS>();
+    static constexpr int NXV = codes_per_step<BITS>() / 64;
+    static constexpr int ZPER = 32 / Fmt<BITS>::ZBITS;
+    static constexpr int ZW = GPS > ZPER ? GPS / ZPER : 1;
+    uint4 v[L];
+    float xv[NXV];
+    float s[GPS > 0 ? GPS : 1];
+    uint32_t zw[ZW];
+};
+
+struct TileView {            // per-lane base pointers of one tile of one problem
+    const uint4 *codes;
+    const float *scales;
+    const uint32_t *zeros;
+    const float *x;
+};
+
+template <int BITS, int GPS>
+__device__ inline void fetch_step(StepData<BITS, GPS> &d, const TileView &T, int step, int lane)
 {
-    constexpr int L = loads_per_step<BITS>();
+    using D = StepData<BITS, GPS>;
 #pragma unroll
-    for (int i = 0; i < L; ++i) dst[i] = base[((size_t)step * L + i) * QG_WAVE];
+    for (int i = 0; i < D::L; ++i) d.v[i] = T.codes[((size_t)step * D::L + i) * QG_WAVE];
+    if constexpr (GPS > 0) {
+#pragma unroll
+        for (int g = 0; g < GPS; ++g) d.s[g] = T.scales[(size_t)(step * GPS + g) * QG_WAVE];
+#pragma unroll
+        for (int w = 0; w < D::ZW; ++w) d.zw[w] = T.zeros[(size_t)((step * GPS) / D::ZPER + w) * QG_WAVE];
+    }
+#pragma unroll
+    for (int i = 0; i < D::NXV; ++i) d.xv[i] = T.x[(size_t)step * codes_per_step<BITS>() + i * 64 + lane];
+}
+
+// The arithmetic of one step on data that has arrived.  xb holds the first 32 x values of
+// the step on entry and the 32 values at `xs_next` on exit (the start of the next step; for
+// the last step of a wavefront the caller passes an address that is valid to read again).
+// GPS > 0: the step's groups are closed here (yacc updated).  GPS == 0: acc and xacc carry
+// the running group across steps.
+template <int BITS, int GPS>
+__device__ inline void compute_step(const StepData<BITS, GPS> &d, const float *__restrict__ xs,
+                                    const float *__restrict__ xs_next, XBatch &xb, int step,
+                                    float &acc, float &xacc, float &yacc)
+{
+    using F = Fmt<BITS>;
+    using D = StepData<BITS, GPS>;
+    constexpr int S = codes_per_step<BITS>();
+    constexpr int NB = S / 32;
+
+    // x-hat of the step's groups (Algorithm 1's sum of x, per group)
+    float xhat[GPS > 0 ? GPS : 1];
+    if constexpr (GPS == 0) {
+#pragma unroll
+        for (int i = 0; i < D::NXV; ++i) xacc += d.xv[i];
+    } else {
+        constexpr int G = S / GPS;
+        if constexpr (G >= 64) {
+#pragma unroll
+            for (int g = 0; g < GPS; ++g) {
+                float v = 0.0f;
+#pragma unroll
+                for (int i = 0; i < G / 64; ++i) v += d.xv[g * (G / 64) + i];
+                segment_sums<64>(v, &xhat[g]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < D::NXV; ++i) segment_sums<G>(d.xv[i], &xhat[i * (64 / G)]);
+        }
+    }
+
+#pragma unroll
+    for (int bt = 0; bt < NB; ++bt) {
+        XBatch xn = xb;
+#pragma unroll
+        for (int o = 0; o < 4; ++o) {
+            if (o == 0) QG_SCHED_FENCE();
+            acc = octet_dot<BITS>(d.v, bt, o, xb, acc);
+            if (o == 0) {
+                QG_SCHED_FENCE();
+                // next batch in flight (it may belong to the next step)
+                xn = load_x32(bt + 1 < NB ? xs + 32 * (bt + 1) : xs_next);
+                QG_SCHED_FENCE();
+            }
+            if constexpr (GPS > 0) {
+                constexpr int G = S / GPS;
+                const int done = (bt * 4 + o + 1) * 8;            // codes of the step done so far
+                if (done % G == 0) {
+                    const int gs = done / G - 1;                  // group within the step
+                    const int gabs = step * GPS + gs;
+                    const uint32_t zword = d.zw[D::ZW > 1 ? gs / D::ZPER : 0];
+                    const float zf = (float)((zword >> (F::ZBITS * (gabs % D::ZPER))) & ((1u << F::ZBITS) - 1u));
+                    yacc = fmaf(d.s[gs], fmaf(-zf, xhat[gs], acc), yacc);
+                    acc = 0.0f;
+                }
+            }
+        }
+        xb = xn;
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -242,15 +353,9 @@ __device__ inline void load_step(uint4 *dst, const uint4 *__restrict__ base, int
 template <int BITS, int CPG>
 __global__ __launch_bounds__(1024) void gemv_static(const GemvArgs A)
 {
-    using F = Fmt<BITS>;
     constexpr int L = loads_per_step<BITS>();
-    constexpr int CPS = cells_per_step<BITS>();
     constexpr int S = codes_per_step<BITS>();
-    constexpr int GPS = CPS / CPG;
-    constexpr int G = CPG * F::CELL;
-    constexpr int ZPER = 32 / F::ZBITS;
-    constexpr int ZW = GPS > ZPER ? GPS / ZPER : 1;   // zero words touched per step
-    constexpr int NB = S / 32;                        // batches of 32 x values per step
+    constexpr int GPS = cells_per_step<BITS>() / CPG;
     __shared__ float red[16][QG_WAVE];
 
     const int pi = find_problem(A, blockIdx.x);
@@ -267,67 +372,25 @@ __global__ __launch_bounds__(1024) void gemv_static(const GemvArgs A)
 
     float yacc = 0.0f;
     if (s0 < s1) {
-        const uint4 *codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
-        const float *sc = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
-        const uint32_t *zr = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+        TileView T;
+        T.codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
+        T.scales = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
+        T.zeros = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+        T.x = P.x;
         const float *__restrict__ x = P.x;
 
-        uint4 cur[L], nxt[L] = {};
-        float scur[GPS], snxt[GPS] = {};
-        uint32_t zcur[ZW], znxt[ZW] = {};
-        load_step<BITS>(cur, codes, s0);
-#pragma unroll
-        for (int g = 0; g < GPS; ++g) scur[g] = sc[(size_t)(s0 * GPS + g) * QG_WAVE];
-#pragma unroll
-        for (int w = 0; w < ZW; ++w) zcur[w] = zr[(size_t)((s0 * GPS) / ZPER + w) * QG_WAVE];
-
-        const float xsum = group_sums(x, s0 * S, (s1 - s0) * GPS, G, lane);
-
+        // The next step is in flight while this one is computed.  The loop body has no
+        // branch: after the last step the "next" fetch simply repeats the last step.
+        StepData<BITS, GPS> cur, nxt;
+        fetch_step(cur, T, s0, lane);
         XBatch xb = load_x32(x + (size_t)s0 * S);
+        float acc = 0.0f, xacc = 0.0f;
+#pragma unroll 2
         for (int s = s0; s < s1; ++s) {
-            if (s + 1 < s1) {
-                load_step<BITS>(nxt, codes, s + 1);
-#pragma unroll
-                for (int g = 0; g < GPS; ++g) snxt[g] = sc[(size_t)((s + 1) * GPS + g) * QG_WAVE];
-#pragma unroll
-                for (int w = 0; w < ZW; ++w)
-                    znxt[w] = zr[(size_t)(((s + 1) * GPS) / ZPER + w) * QG_WAVE];
-            }
-            const float *xs = x + (size_t)s * S;
-            float acc = 0.0f;
-#pragma unroll
-            for (int bt = 0; bt < NB; ++bt) {
-                XBatch xn = xb;
-#pragma unroll
-                for (int o = 0; o < 4; ++o) {
-                    if (o == 0) QG_SCHED_FENCE();
-                    acc = octet_dot<BITS>(cur, bt, o, xb, acc);
-                    if (o == 0) {
-                        QG_SCHED_FENCE();
-                        // next batch in flight (it may belong to the next step)
-                        if (bt + 1 < NB || s + 1 < s1) xn = load_x32(xs + 32 * (bt + 1));
-                        QG_SCHED_FENCE();
-                    }
-                    const int done = (bt * 4 + o + 1) * 8;            // codes of the step done so far
-                    if (done % G == 0) {
-                        const int gs = done / G - 1;                  // group within the step
-                        const int gl = (s - s0) * GPS + gs;           // group within the wavefront
-                        const int gabs = s * GPS + gs;
-                        const uint32_t zword = zcur[ZW > 1 ? gs / ZPER : 0];
-                        const float zf = (float)((zword >> (F::ZBITS * (gabs % ZPER))) & ((1u << F::ZBITS) - 1u));
-                        const float sx = lane_value(xsum, gl);
-                        yacc = fmaf(scur[gs], fmaf(-zf, sx, acc), yacc);
-                        acc = 0.0f;
-                    }
-                }
-                xb = xn;
-            }
-#pragma unroll
-            for (int i = 0; i < L; ++i) cur[i] = nxt[i];
-#pragma unroll
-            for (int g = 0; g < GPS; ++g) scur[g] = snxt[g];
-#pragma unroll
-            for (int w = 0; w < ZW; ++w) zcur[w] = znxt[w];
+            const int sn = s + 1 < s1 ? s + 1 : s;
+            fetch_step(nxt, T, sn, lane);
+            compute_step(cur, x + (size_t)s * S, x + (size_t)sn * S, xb, s, acc, xacc, yacc);
+            cur = nxt;
         }
     }
     finish_tile(P, tile, chunk, yacc, red);
@@ -344,7 +407,6 @@ __global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
     constexpr int L = loads_per_step<BITS>();
     constexpr int S = codes_per_step<BITS>();
     constexpr int ZPER = 32 / F::ZBITS;
-    constexpr int NB = S / 32;
     __shared__ float red[16][QG_WAVE];
 
     const int pi = find_problem(A, blockIdx.x);
@@ -362,46 +424,36 @@ __global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
 
     float yacc = 0.0f;
     if (s0 < s1) {
-        const uint4 *codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
-        const float *sc = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
-        const uint32_t *zr = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+        TileView T;
+        T.codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
+        T.scales = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
+        T.zeros = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+        T.x = P.x;
         const float *__restrict__ x = P.x;
-        const int g0 = s0 / spg, ng = (s1 - s0) / spg;
 
-        uint4 cur[L], nxt[L] = {};
-        load_step<BITS>(cur, codes, s0);
-        const float xsum = group_sums(x, s0 * S, ng, P.group, lane);
-
-        int s = s0;
+        StepData<BITS, 0> da, db;
+        fetch_step(da, T, s0, lane);
         XBatch xb = load_x32(x + (size_t)s0 * S);
-        for (int gl = 0; gl < ng; ++gl) {
-            const int gabs = g0 + gl;
-            const float scale = sc[(size_t)gabs * QG_WAVE];
-            const uint32_t zword = zr[(size_t)(gabs / ZPER) * QG_WAVE];
-            float acc = 0.0f;
-            for (int i = 0; i < spg; ++i, ++s) {
-                if (s + 1 < s1) load_step<BITS>(nxt, codes, s + 1);
-                const float *xs = x + (size_t)s * S;
-#pragma unroll
-                for (int bt = 0; bt < NB; ++bt) {
-                    XBatch xn = xb;
-#pragma unroll
-                    for (int o = 0; o < 4; ++o) {
-                        if (o == 0) QG_SCHED_FENCE();
-                        acc = octet_dot<BITS>(cur, bt, o, xb, acc);
-                        if (o == 0) {
-                            QG_SCHED_FENCE();
-                            if (bt + 1 < NB || s + 1 < s1) xn = load_x32(xs + 32 * (bt + 1));
-                            QG_SCHED_FENCE();
-                        }
-                    }
-                    xb = xn;
-                }
-#pragma unroll
-                for (int j = 0; j < L; ++j) cur[j] = nxt[j];
+        float acc = 0.0f, xacc = 0.0f;
+        int in_group = 0;                                   // steps of the running group done
+#pragma unroll 2
+        for (int s = s0; s < s1; ++s) {
+            const int sn = s + 1 < s1 ? s + 1 : s;
+            fetch_step(db, T, sn, lane);
+            compute_step(da, x + (size_t)s * S, x + (size_t)sn * S, xb, s, acc, xacc, yacc);
+            if (++in_group == spg) {
+                const int g = s / spg;
+                float xhat;
+                segment_sums<64>(xacc, &xhat);
+                const float scale = T.scales[(size_t)g * QG_WAVE];
+                const uint32_t zword = T.zeros[(size_t)(g / ZPER) * QG_WAVE];
+                const float zf = (float)((zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u));
+                yacc = fmaf(scale, fmaf(-zf, xhat, acc), yacc);
+                acc = 0.0f;
+                xacc = 0.0f;
+                in_group = 0;
             }
-            const float zf = (float)((zword >> (F::ZBITS * (gabs % ZPER))) & ((1u << F::ZBITS) - 1u));
-            yacc = fmaf(scale, fmaf(-zf, lane_value(xsum, gl), acc), yacc);
+            da = db;
         }
     }
     finish_tile(P, tile, chunk, yacc, red);
@@ -529,11 +581,14 @@ Plan make_plan(const QgLayout &L)
     return pl;
 }
 
-// Items per wavefront for a target of `per_wave` bytes, raised if QG_MAX_CHUNKS blocks of
-// `wpb` wavefronts would not cover K.  Returns 0 if `wpb` wavefronts cannot do it.
-int64_t items_per_wave(const Plan &pl, size_t per_wave, int wpb)
+// Items per wavefront when K is cut into `split` workgroups of `wpb` wavefronts, or -- with
+// an explicit byte target from the tuning knob -- as close to `per_wave` bytes as allowed.
+// Returns 0 if QG_MAX_CHUNKS workgroups of `wpb` wavefronts cannot cover K.
+int64_t items_per_wave(const Plan &pl, size_t per_wave, int wpb, int split)
 {
-    int64_t spw = (int64_t)((per_wave + pl.item_bytes / 2) / pl.item_bytes);
+    int64_t spw;
+    if (per_wave > 0) spw = (int64_t)((per_wave + pl.item_bytes / 2) / pl.item_bytes);
+    else spw = (pl.items + (int64_t)wpb * split - 1) / ((int64_t)wpb * split);
     if (spw < 1) spw = 1;
     const int64_t floor_spw = (pl.items + (int64_t)wpb * QG_MAX_CHUNKS - 1) / ((int64_t)wpb * QG_MAX_CHUNKS);
     if (spw < floor_spw) spw = floor_spw;
@@ -571,27 +626,40 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
 {
     GemvArgs A;
     A.count = count;
+    for (int i = 0; i < QG_MAX_GROUPED; ++i) A.block_begin[i] = 0x7fffffff;
     QgLayout L[QG_MAX_GROUPED];
     Plan pl[QG_MAX_GROUPED];
-    size_t code_bytes = 0;
     for (int i = 0; i < count; ++i) {
         const qg_gemv_desc &d = descs[idx[i]];
         qg_make_layout(d.N, d.K, d.bits, d.group, &L[i]);
         pl[i] = make_plan(L[i]);
-        code_bytes += (size_t)L[i].tiles * L[i].units * L[i].planes * QG_WAVE * 16;
     }
     const Kind kind = pl[0].kind;
 
-    // Enough wavefronts to cover the chip about twelve deep, between 4 KB and 16 KB each.
-    size_t per_wave = (size_t)g_tune_bytes_per_wave;
-    if (per_wave == 0) {
-        per_wave = code_bytes / (256 * 12);
-        if (per_wave < 4096) per_wave = 4096;
-        if (per_wave > 16384) per_wave = 16384;
+    // Launch shape.  A workgroup owns one tile of 64 outputs and, whenever the launch has
+    // enough tiles to fill the chip, the whole of K: its wavefronts split K and meet in LDS,
+    // and nothing crosses workgroups (the cross-workgroup hand-over needs device-scope
+    // fences, which write back and invalidate L2 and cost more than they save).  Launches
+    // with few tiles split K over workgroups as well, to have about 512 of them.
+    int64_t total_tiles = 0;
+    for (int i = 0; i < count; ++i) total_tiles += L[i].tiles;
+    int split = 1;
+    if (total_tiles < 512) {
+        split = (int)((512 + total_tiles - 1) / total_tiles);
+        if (split > QG_MAX_CHUNKS) split = QG_MAX_CHUNKS;
     }
-    int wpb = g_tune_wpb > 0 ? g_tune_wpb : 4;
+    const size_t per_wave = (size_t)g_tune_bytes_per_wave;   // 0: derive from wpb and split
+    int wpb = g_tune_wpb;
+    if (wpb <= 0) {
+        // about 16 KB of codes per wavefront, between 4 and 16 wavefronts
+        wpb = 4;
+        for (int i = 0; i < count; ++i) {
+            const int64_t want = (int64_t)((pl[i].items * pl[i].item_bytes / split + 16383) / 16384);
+            if (want > wpb) wpb = want > 16 ? 16 : (int)want;
+        }
+    }
     for (int i = 0; i < count; ++i)
-        while (items_per_wave(pl[i], per_wave, wpb) == 0) {
+        while (items_per_wave(pl[i], per_wave, wpb, split) == 0) {
             if (wpb == 16) return QG_ERR_UNSUPPORTED;
             wpb = wpb * 2 > 16 ? 16 : wpb * 2;
         }
@@ -617,10 +685,11 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         P.zwords = (int)L[i].zwords;
         P.group = L[i].group;
         P.steps_per_group = (int)pl[i].quantum;
-        const int64_t spw = items_per_wave(pl[i], per_wave, wpb);
+        const int64_t spw = items_per_wave(pl[i], per_wave, wpb, split);
         P.steps_per_wave = (int)spw;
         P.chunks = (int)((pl[i].items + spw * wpb - 1) / (spw * wpb));
         P.block_begin = blocks;
+        A.block_begin[i] = blocks;
         const int64_t nb = (int64_t)P.tiles * P.chunks;
         if (blocks + nb > 0x3fffffff) return QG_ERR_SHAPE;
         blocks += (int)nb;
