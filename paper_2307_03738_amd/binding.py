@@ -29,7 +29,7 @@ def lib():
     """Load libqg.so, building it first only if no built library is present."""
     global _LIB
     if _LIB is None:
-        path = _build.OUT
+        path = os.environ.get("QG_LIBRARY", _build.OUT)     # override: a library built elsewhere
         if not os.path.exists(path):
             path = _build.build(force=True)
         L = ctypes.CDLL(path)

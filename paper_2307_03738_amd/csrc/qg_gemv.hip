@@ -33,7 +33,9 @@ struct GemvProblem {
     unsigned *counter;     // [tile]
     int N, K, tiles, steps, ngroups, zwords;
     int group;             // G
-    int chunks;            // K-split over workgroups
+    int chunks;            // K-split over workgroups (1: a workgroup covers all of K)
+    int waves_per_tile;    // wavefronts of a workgroup that share one tile
+    int tiles_per_block;   // tiles one workgroup handles (1 if chunks > 1)
     int steps_per_wave;
     int steps_per_group;   // runtime-group kernel only
     int block_begin;       // first block of this problem in the grid
@@ -198,20 +200,56 @@ __device__ inline void segment_sums(float v, float *out)
     out[0] = uniform_lane(v, 63);
 }
 
-// K-split epilogue.  Every wavefront of the block passes its 64 partial outputs; wavefront
-// 0 adds them in wavefront order and either stores y or hands the block's vector to the
-// tile's last-arriving block.
-__device__ inline void finish_tile(const GemvProblem &P, int tile, int chunk, float yacc,
+// What one wavefront does.  A workgroup is a pool of wavefronts; `waves_per_tile` of them
+// share one tile of 64 outputs, each taking `steps_per_wave` consecutive items along K, and
+// a workgroup holds `tiles_per_block` such teams (tiles with a short K pack several teams
+// into a workgroup, tiles with a long K use all of it, so every wavefront of a launch has
+// about the same amount of work).  With chunks > 1 a tile's K is also cut over workgroups.
+struct WaveJob {
+    int tile, chunk;
+    int item0, item1;   // range along K (steps, or groups in the generic kernel)
+    int lead;           // wavefront of the block that leads this tile's team
+    int team;           // wavefronts of the team that have work
+    bool work;
+};
+
+__device__ inline WaveJob locate(const GemvProblem &P, int local_block, int items, int wave)
+{
+    WaveJob j;
+    const int wpt = P.waves_per_tile, spw = P.steps_per_wave;
+    const int slot = wave / wpt, sub = wave - slot * wpt;
+    if (P.chunks > 1) {
+        j.tile = local_block / P.chunks;
+        j.chunk = local_block - j.tile * P.chunks;
+    } else {
+        j.tile = local_block * P.tiles_per_block + slot;
+        j.chunk = 0;
+    }
+    const int first = j.chunk * wpt * spw;
+    j.item0 = first + sub * spw;
+    j.item1 = j.item0 + spw < items ? j.item0 + spw : items;
+    j.lead = slot * wpt;
+    const int left = (items - first + spw - 1) / spw;
+    j.team = left < wpt ? left : wpt;
+    j.work = slot < P.tiles_per_block && j.tile < P.tiles && j.item0 < j.item1;
+    return j;
+}
+
+// K-split epilogue.  The wavefronts of a team pass their 64 partial outputs through LDS
+// (wavefronts without work have already ended; a barrier only waits for wavefronts that are
+// still alive); the team's lead adds them in wavefront order and either stores y or hands
+// the vector to the tile's last-arriving workgroup.
+__device__ inline void finish_tile(const GemvProblem &P, const WaveJob &j, float yacc,
                                    float (*red)[QG_WAVE])
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int waves = blockDim.x >> 6;
     red[wave][lane] = yacc;
     __syncthreads();
-    if (wave != 0) return;
-    float t = red[0][lane];
-    for (int w = 1; w < waves; ++w) t += red[w][lane];
+    if (wave != j.lead) return;
+    float t = red[j.lead][lane];
+    for (int w = 1; w < j.team; ++w) t += red[j.lead + w][lane];
+    const int tile = j.tile, chunk = j.chunk;
     const int n = tile * QG_WAVE + lane;
     if (P.chunks == 1) {
         if (n < P.N) P.y[n] = t;
@@ -289,7 +327,7 @@ __device__ inline void fetch_step(StepData<BITS, GPS> &d, const TileView &T, int
 template <int BITS, int GPS>
 __device__ inline void compute_step(const StepData<BITS, GPS> &d, const float *__restrict__ xs,
                                     const float *__restrict__ xs_next, XBatch &xb, int step,
-                                    float &acc, float &xacc, float &yacc)
+                                    bool valid, float &acc, float &xacc, float &yacc)
 {
     using F = Fmt<BITS>;
     using D = StepData<BITS, GPS>;
@@ -338,7 +376,8 @@ __device__ inline void compute_step(const StepData<BITS, GPS> &d, const float *_
                     const int gabs = step * GPS + gs;
                     const uint32_t zword = d.zw[D::ZW > 1 ? gs / D::ZPER : 0];
                     const float zf = (float)((zword >> (F::ZBITS * (gabs % D::ZPER))) & ((1u << F::ZBITS) - 1u));
-                    yacc = fmaf(d.s[gs], fmaf(-zf, xhat[gs], acc), yacc);
+                    // a step past the end of the wavefront's range counts with scale 0
+                    yacc = fmaf(valid ? d.s[gs] : 0.0f, fmaf(-zf, xhat[gs], acc), yacc);
                     acc = 0.0f;
                 }
             }
@@ -360,40 +399,36 @@ __global__ __launch_bounds__(1024) void gemv_static(const GemvArgs A)
 
     const int pi = find_problem(A, blockIdx.x);
     const GemvProblem &P = A.p[pi];
-    const int local = blockIdx.x - P.block_begin;
-    const int tile = local / P.chunks, chunk = local % P.chunks;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int waves = blockDim.x >> 6;
+    const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.steps, wave);
+    if (!job.work) return;                      // no work: leave before the barrier
+    const int tile = job.tile, s0 = job.item0, s1 = job.item1;
 
-    int s0 = (chunk * waves + wave) * P.steps_per_wave;
-    int s1 = s0 + P.steps_per_wave;
-    if (s1 > P.steps) s1 = P.steps;
+    TileView T;
+    T.codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
+    T.scales = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
+    T.zeros = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+    T.x = P.x;
+    const float *__restrict__ x = P.x;
 
-    float yacc = 0.0f;
-    if (s0 < s1) {
-        TileView T;
-        T.codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
-        T.scales = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
-        T.zeros = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
-        T.x = P.x;
-        const float *__restrict__ x = P.x;
-
-        // The next step is in flight while this one is computed.  The loop body has no
-        // branch: after the last step the "next" fetch simply repeats the last step.
-        StepData<BITS, GPS> cur, nxt;
-        fetch_step(cur, T, s0, lane);
-        XBatch xb = load_x32(x + (size_t)s0 * S);
-        float acc = 0.0f, xacc = 0.0f;
-#pragma unroll 2
-        for (int s = s0; s < s1; ++s) {
-            const int sn = s + 1 < s1 ? s + 1 : s;
-            fetch_step(nxt, T, sn, lane);
-            compute_step(cur, x + (size_t)s * S, x + (size_t)sn * S, xb, s, acc, xacc, yacc);
-            cur = nxt;
-        }
+    // Two buffers used alternately: the next step is in flight while this one is computed.
+    // The loop body has no branch: a fetch past the wavefront's range repeats its last step,
+    // and a second half-iteration past the range is computed with scale 0.
+    const int last = s1 - 1;
+    StepData<BITS, GPS> da, db;
+    fetch_step(da, T, s0, lane);
+    XBatch xb = load_x32(x + (size_t)s0 * S);
+    float yacc = 0.0f, acc = 0.0f, xacc = 0.0f;
+    for (int s = s0; s < s1; s += 2) {
+        const int sb = s + 1 < last ? s + 1 : last;
+        const int sc = s + 2 < last ? s + 2 : last;
+        fetch_step(db, T, sb, lane);
+        compute_step(da, x + (size_t)s * S, x + (size_t)sb * S, xb, s, true, acc, xacc, yacc);
+        fetch_step(da, T, sc, lane);
+        compute_step(db, x + (size_t)sb * S, x + (size_t)sc * S, xb, sb, s + 1 < s1, acc, xacc, yacc);
     }
-    finish_tile(P, tile, chunk, yacc, red);
+    finish_tile(P, job, yacc, red);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -411,52 +446,44 @@ __global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
 
     const int pi = find_problem(A, blockIdx.x);
     const GemvProblem &P = A.p[pi];
-    const int local = blockIdx.x - P.block_begin;
-    const int tile = local / P.chunks, chunk = local % P.chunks;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int waves = blockDim.x >> 6;
     const int spg = P.steps_per_group;
+    const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.steps, wave);
+    if (!job.work) return;                      // no work: leave before the barrier
+    const int tile = job.tile, s0 = job.item0, s1 = job.item1;   // s0 is a multiple of spg
 
-    int s0 = (chunk * waves + wave) * P.steps_per_wave;     // a multiple of spg
-    int s1 = s0 + P.steps_per_wave;
-    if (s1 > P.steps) s1 = P.steps;
+    TileView T;
+    T.codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
+    T.scales = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
+    T.zeros = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+    T.x = P.x;
+    const float *__restrict__ x = P.x;
 
-    float yacc = 0.0f;
-    if (s0 < s1) {
-        TileView T;
-        T.codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
-        T.scales = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
-        T.zeros = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
-        T.x = P.x;
-        const float *__restrict__ x = P.x;
-
-        StepData<BITS, 0> da, db;
-        fetch_step(da, T, s0, lane);
-        XBatch xb = load_x32(x + (size_t)s0 * S);
-        float acc = 0.0f, xacc = 0.0f;
-        int in_group = 0;                                   // steps of the running group done
-#pragma unroll 2
-        for (int s = s0; s < s1; ++s) {
-            const int sn = s + 1 < s1 ? s + 1 : s;
-            fetch_step(db, T, sn, lane);
-            compute_step(da, x + (size_t)s * S, x + (size_t)sn * S, xb, s, acc, xacc, yacc);
-            if (++in_group == spg) {
-                const int g = s / spg;
-                float xhat;
-                segment_sums<64>(xacc, &xhat);
-                const float scale = T.scales[(size_t)g * QG_WAVE];
-                const uint32_t zword = T.zeros[(size_t)(g / ZPER) * QG_WAVE];
-                const float zf = (float)((zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u));
-                yacc = fmaf(scale, fmaf(-zf, xhat, acc), yacc);
-                acc = 0.0f;
-                xacc = 0.0f;
-                in_group = 0;
-            }
-            da = db;
+    StepData<BITS, 0> da, db;
+    fetch_step(da, T, s0, lane);
+    XBatch xb = load_x32(x + (size_t)s0 * S);
+    float yacc = 0.0f, acc = 0.0f, xacc = 0.0f;
+    int in_group = 0;                                   // steps of the running group done
+    for (int s = s0; s < s1; ++s) {
+        const int sn = s + 1 < s1 ? s + 1 : s;
+        fetch_step(db, T, sn, lane);
+        compute_step(da, x + (size_t)s * S, x + (size_t)sn * S, xb, s, true, acc, xacc, yacc);
+        if (++in_group == spg) {
+            const int g = s / spg;
+            float xhat;
+            segment_sums<64>(xacc, &xhat);
+            const float scale = T.scales[(size_t)g * QG_WAVE];
+            const uint32_t zword = T.zeros[(size_t)(g / ZPER) * QG_WAVE];
+            const float zf = (float)((zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u));
+            yacc = fmaf(scale, fmaf(-zf, xhat, acc), yacc);
+            acc = 0.0f;
+            xacc = 0.0f;
+            in_group = 0;
         }
+        da = db;     // a few register moves per step; this kernel is not the hot one
     }
-    finish_tile(P, tile, chunk, yacc, red);
+    finish_tile(P, job, yacc, red);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -473,17 +500,13 @@ __global__ __launch_bounds__(1024) void gemv_generic(const GemvArgs A)
 
     const int pi = find_problem(A, blockIdx.x);
     const GemvProblem &P = A.p[pi];
-    const int local = blockIdx.x - P.block_begin;
-    const int tile = local / P.chunks, chunk = local % P.chunks;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int waves = blockDim.x >> 6;
     const int cpg = P.group / F::CELL;
-
-    // here steps_per_wave counts groups per wavefront
-    int g0 = (chunk * waves + wave) * P.steps_per_wave;
-    int g1 = g0 + P.steps_per_wave;
-    if (g1 > P.ngroups) g1 = P.ngroups;
+    // here the items along K are groups
+    const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.ngroups, wave);
+    if (!job.work) return;                      // no work: leave before the barrier
+    const int tile = job.tile, g0 = job.item0, g1 = job.item1;
 
     float yacc = 0.0f;
     const uint4 *codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
@@ -519,7 +542,7 @@ __global__ __launch_bounds__(1024) void gemv_generic(const GemvArgs A)
         const float zf = (float)((zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u));
         yacc = fmaf(sc[(size_t)g * QG_WAVE], fmaf(-zf, sx, acc), yacc);
     }
-    finish_tile(P, tile, chunk, yacc, red);
+    finish_tile(P, job, yacc, red);
 }
 
 __global__ void fill_zero_u32(uint32_t *p, size_t n)
@@ -532,6 +555,7 @@ __global__ void fill_zero_u32(uint32_t *p, size_t n)
 
 int g_tune_wpb = 0;
 int g_tune_bytes_per_wave = 0;
+bool g_tune_fixed_team = true;
 
 enum Kind { KIND_STATIC, KIND_RUNTIME, KIND_GENERIC };
 
@@ -581,23 +605,6 @@ Plan make_plan(const QgLayout &L)
     return pl;
 }
 
-// Items per wavefront when K is cut into `split` workgroups of `wpb` wavefronts, or -- with
-// an explicit byte target from the tuning knob -- as close to `per_wave` bytes as allowed.
-// Returns 0 if QG_MAX_CHUNKS workgroups of `wpb` wavefronts cannot cover K.
-int64_t items_per_wave(const Plan &pl, size_t per_wave, int wpb, int split)
-{
-    int64_t spw;
-    if (per_wave > 0) spw = (int64_t)((per_wave + pl.item_bytes / 2) / pl.item_bytes);
-    else spw = (pl.items + (int64_t)wpb * split - 1) / ((int64_t)wpb * split);
-    if (spw < 1) spw = 1;
-    const int64_t floor_spw = (pl.items + (int64_t)wpb * QG_MAX_CHUNKS - 1) / ((int64_t)wpb * QG_MAX_CHUNKS);
-    if (spw < floor_spw) spw = floor_spw;
-    spw = (spw + pl.quantum - 1) / pl.quantum * pl.quantum;
-    if (spw > pl.max_spw) spw = pl.max_spw;
-    if ((pl.items + spw * wpb - 1) / (spw * wpb) > QG_MAX_CHUNKS) return 0;
-    return spw;
-}
-
 size_t workspace_for(const QgLayout &L)
 {
     const size_t partial = (size_t)L.tiles * QG_MAX_CHUNKS * QG_WAVE * sizeof(float);
@@ -637,32 +644,57 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     const Kind kind = pl[0].kind;
 
     // Launch shape.  A workgroup owns one tile of 64 outputs and, whenever the launch has
-    // enough tiles to fill the chip, the whole of K: its wavefronts split K and meet in LDS,
-    // and nothing crosses workgroups (the cross-workgroup hand-over needs device-scope
-    // fences, which write back and invalidate L2 and cost more than they save).  Launches
-    // with few tiles split K over workgroups as well, to have about 512 of them.
+    // enough tiles, the whole of K: its wavefronts split K and meet in LDS, and nothing
+    // crosses workgroups (the cross-workgroup hand-over needs device-scope fences, which
+    // write back and invalidate L2 and cost more than they save).  Every wavefront of the
+    // launch gets the same number of items, so that tiles with a long K simply use more
+    // wavefronts of their workgroup; wavefronts without work end at once.  Launches with
+    // few tiles split K over workgroups as well.
     int64_t total_tiles = 0;
-    for (int i = 0; i < count; ++i) total_tiles += L[i].tiles;
+    size_t code_bytes = 0;
+    for (int i = 0; i < count; ++i) {
+        total_tiles += L[i].tiles;
+        code_bytes += (size_t)L[i].tiles * pl[i].items * pl[i].item_bytes;
+    }
     int split = 1;
-    if (total_tiles < 512) {
-        split = (int)((512 + total_tiles - 1) / total_tiles);
+    if (total_tiles < 128) {
+        split = (int)((128 + total_tiles - 1) / total_tiles);
         if (split > QG_MAX_CHUNKS) split = QG_MAX_CHUNKS;
     }
-    const size_t per_wave = (size_t)g_tune_bytes_per_wave;   // 0: derive from wpb and split
-    int wpb = g_tune_wpb;
-    if (wpb <= 0) {
-        // about 16 KB of codes per wavefront, between 4 and 16 wavefronts
-        wpb = 4;
-        for (int i = 0; i < count; ++i) {
-            const int64_t want = (int64_t)((pl[i].items * pl[i].item_bytes / split + 16383) / 16384);
-            if (want > wpb) wpb = want > 16 ? 16 : (int)want;
-        }
+    const int cap = g_tune_wpb > 0 ? g_tune_wpb : 12;        // wavefronts per workgroup, at most
+    size_t target = (size_t)g_tune_bytes_per_wave;           // code bytes per wavefront
+    if (target == 0) {
+        target = code_bytes / (256 * 16);
+        if (target < 4096) target = 4096;
+        if (target > 24576) target = 24576;
     }
-    for (int i = 0; i < count; ++i)
-        while (items_per_wave(pl[i], per_wave, wpb, split) == 0) {
-            if (wpb == 16) return QG_ERR_UNSUPPORTED;
-            wpb = wpb * 2 > 16 ? 16 : wpb * 2;
+    int64_t spw = 1;
+    for (int i = 0; i < count; ++i) {
+        const int64_t per_wg = (pl[i].items + split - 1) / split;
+        int64_t want = (int64_t)((target + pl[i].item_bytes / 2) / pl[i].item_bytes);
+        if (want < 1) want = 1;
+        if ((per_wg + want - 1) / want > cap) want = (per_wg + cap - 1) / cap;
+        if (want > spw) spw = want;
+    }
+
+    int wpb = 1;
+    int64_t spw_of[QG_MAX_GROUPED], team_of[QG_MAX_GROUPED], chunks_of[QG_MAX_GROUPED];
+    for (int i = 0; i < count; ++i) {
+        int64_t w = spw;
+        if (g_tune_fixed_team) {
+            // every tile gets a team of `cap` wavefronts; tiles with a long K take more items each
+            const int64_t per_wg = (pl[i].items + split - 1) / split;
+            w = (per_wg + cap - 1) / cap;
         }
+        w = (w + pl[i].quantum - 1) / pl[i].quantum * pl[i].quantum;
+        if (w > pl[i].max_spw) w = pl[i].max_spw;
+        spw_of[i] = w;
+        const int64_t waves = (pl[i].items + w - 1) / w;
+        chunks_of[i] = (waves + cap - 1) / cap;
+        if (chunks_of[i] > QG_MAX_CHUNKS) return QG_ERR_UNSUPPORTED;   // (cap below 16 set by the knob)
+        team_of[i] = (waves + chunks_of[i] - 1) / chunks_of[i];
+        if (team_of[i] > wpb) wpb = (int)team_of[i];
+    }
 
     int blocks = 0;
     for (int i = 0; i < count; ++i) {
@@ -685,12 +717,14 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         P.zwords = (int)L[i].zwords;
         P.group = L[i].group;
         P.steps_per_group = (int)pl[i].quantum;
-        const int64_t spw = items_per_wave(pl[i], per_wave, wpb, split);
-        P.steps_per_wave = (int)spw;
-        P.chunks = (int)((pl[i].items + spw * wpb - 1) / (spw * wpb));
+        P.steps_per_wave = (int)spw_of[i];
+        P.chunks = (int)chunks_of[i];
+        P.waves_per_tile = (int)team_of[i];
+        P.tiles_per_block = P.chunks > 1 ? 1 : wpb / P.waves_per_tile;
         P.block_begin = blocks;
         A.block_begin[i] = blocks;
-        const int64_t nb = (int64_t)P.tiles * P.chunks;
+        const int64_t nb = P.chunks > 1 ? (int64_t)P.tiles * P.chunks
+                                        : (P.tiles + P.tiles_per_block - 1) / P.tiles_per_block;
         if (blocks + nb > 0x3fffffff) return QG_ERR_SHAPE;
         blocks += (int)nb;
     }
@@ -718,9 +752,10 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
 
 extern "C" int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave)
 {
-    if (waves_per_block < 0 || waves_per_block > 16 || bytes_per_wave < 0) return QG_ERR_SHAPE;
+    if (waves_per_block < 0 || waves_per_block > 16 || bytes_per_wave < -1) return QG_ERR_SHAPE;
     g_tune_wpb = waves_per_block;
-    g_tune_bytes_per_wave = bytes_per_wave;
+    g_tune_fixed_team = bytes_per_wave <= 0;
+    g_tune_bytes_per_wave = bytes_per_wave > 0 ? bytes_per_wave : 0;
     return QG_OK;
 }
 
@@ -781,6 +816,11 @@ extern "C" int qg_gemv_grouped(const qg_gemv_desc *descs, int count, void *works
                 done[j] = true;
             }
         }
+        // longest K first: its wavefronts run longest, so they should start first
+        for (int a = 1; a < n; ++a)
+            for (int b = a; b > 0 && descs[idx[b]].K > descs[idx[b - 1]].K; --b) {
+                const int t = idx[b]; idx[b] = idx[b - 1]; idx[b - 1] = t;
+            }
         const int rc = launch_class(descs, idx, n, ws_off, (char *)workspace, (hipStream_t)stream);
         if (rc != QG_OK) return rc;
     }
