@@ -247,3 +247,79 @@ def test_full_size_matrix(qg, oracle, name, index):
     err = scaled_error(y, y_ref, oracle.row_norms(q0, s0, z0, cfg.group), x)
     print(f"[full] {name}[{index}] scaled error {err:.3e}", flush=True)
     assert err <= TOL_FP32, err
+
+
+# ------------------------------------------------------------------ small-M GEMM (bf16 MFMA path)
+
+TOL_BF16 = 1e-2
+
+
+def _gemm_case(qg, oracle, W, X, bits, group):
+    N, K = W.shape
+    M = X.shape[0]
+    q0, s0, z0 = oracle.quantize(W, bits, group)
+    Y_ref = oracle.matmul_small(q0, s0, z0, group, X)
+    norms = oracle.row_norms(q0, s0, z0, group)
+    q, s, z = qg.qg_quantize(dev(W), bits, group)
+    blob = qg.qg_pack(q, s, z, bits, group, qg.QG_LAYOUT_DEVICE)
+    ws = qg.new_workspace(qg.qg_workspace_bytes(N, K, bits, group, M))
+    Y = torch.full((M * N + 64,), 7.0, dtype=torch.float32, device="cuda")      # canary behind Y
+    qg.qg_gemm_small(blob, N, K, bits, group, dev(X), Y[:M * N].view(M, N), ws)
+    Y2 = qg.qg_gemm_small(blob, N, K, bits, group, dev(X), None, ws)            # workspace reuse
+    torch.cuda.synchronize()
+    Yh = host(Y)
+    assert np.all(Yh[M * N:] == 7.0), "write past the end of Y"
+    assert np.array_equal(Yh[:M * N].reshape(M, N), host(Y2)), "not deterministic"
+    return scaled_error(Yh[:M * N].reshape(M, N), Y_ref, norms, X)
+
+
+GEMM_CASES = [  # N, K, bits, group, M
+    (256, 512, 4, 128, 16),
+    (200, 1024, 4, 128, 5),      # ragged N and M
+    (130, 768, 4, 64, 33),
+    (70, 512, 4, 32, 100),
+    (300, 1024, 4, 256, 64),
+    (128, 2048, 4, 2048, 128),   # one group per output
+    (64, 128, 4, 128, 1),
+    (130, 512, 3, 64, 7),        # other widths: fp32 row-by-row path
+    (96, 512, 2, 32, 4),
+    (90, 480, 4, 24, 3),
+]
+
+
+@pytest.mark.parametrize("N,K,bits,group,M", GEMM_CASES)
+def test_gemm_small_matches_oracle(qg, oracle, N, K, bits, group, M):
+    _announce("gemm_small", N, K, bits, group, M)
+    W, X = synth.small_case(N + K + M, N, K, 0.02, True, m=max(M, 2))
+    X = X[:M]
+    err = _gemm_case(qg, oracle, W, X, bits, group)
+    assert err <= TOL_BF16, err
+
+
+def test_gemm_small_rows_agree_with_gemv(qg, oracle):
+    _announce("gemm_small rows vs gemv")
+    N, K, bits, group, M = 256, 1024, 4, 128, 16
+    W, X = synth.small_case(77, N, K, 0.02, True, m=M)
+    q, s, z = qg.qg_quantize(dev(W), bits, group)
+    blob = qg.qg_pack(q, s, z, bits, group)
+    Y = host(qg.qg_gemm_small(blob, N, K, bits, group, dev(X)))
+    q0, s0, z0 = oracle.quantize(W, bits, group)
+    norms = oracle.row_norms(q0, s0, z0, group)
+    for m in (0, 7, 15):
+        y = host(qg.qg_gemv(blob, N, K, bits, group, dev(X[m])))
+        assert scaled_error(Y[m], y.astype(np.float64), norms, X[m]) <= TOL_BF16
+
+
+@pytest.mark.parametrize("index", [0, 1, 2])
+@pytest.mark.parametrize("mi", [0, 1, 2])
+def test_gemm_small_full_size(qg, oracle, index, mi):
+    # configuration 5: LLaMA-7B shapes, 4-bit group 128, M = 16, 64, 128; all outputs compared
+    cfg = synth.CONFIGS["C5"]
+    N, K = cfg.shapes[index]
+    M = cfg.batch[mi]
+    _announce("gemm full size", N, K, M)
+    W, acts = synth.matrix(cfg, index)
+    X = acts[mi]
+    err = _gemm_case(qg, oracle, W, X, cfg.bits, cfg.group)
+    print(f"[full] C5[{index}] M={M} scaled error {err:.3e}", flush=True)
+    assert err <= TOL_BF16, err
