@@ -12,11 +12,11 @@
 // the raw code words (w0 with w2, w1 with w3) turns one into the other for both 32-output
 // blocks at once, so weights go from HBM to the MFMA operand through registers only:
 // mask, convert, one FMA with the group's (s, -z s), pack to bf16.  Every weight is
-// dequantized exactly once.  The activation rows are converted to bf16 once per 128-k chunk
-// and shared through LDS by the four wavefronts of a workgroup, which work on four
-// neighbouring tiles over the same k range.  K may be cut into `splits` ranges handled by
-// different workgroups; their fp32 partial results are added by a second small kernel in a
-// fixed order.
+// dequantized exactly once.  The activation rows are converted to bf16 once per call and
+// staged chunk by chunk (128 k) through LDS, double-buffered, shared by the four wavefronts
+// of a workgroup, which work on four neighbouring tiles over the same k range.  K may be
+// cut into `splits` ranges handled by different workgroups; their fp32 partial results are
+// added by a second small kernel in a fixed order.
 //
 // Other bit widths and group sizes take the fp32 GEMV kernel once per activation row.
 #include "qg_common.h"
@@ -38,7 +38,7 @@ struct GemmArgs {
     const uint4 *codes;
     const float *scales;
     const uint32_t *zeros;
-    const float *X;
+    const __bf16 *Xb;          // activations as bf16 [M][K]
     float *out;                // Y, or partial results [split][M][N]
     int M, N, K, tiles, steps, ngroups, zwords, group;
     int steps_per_split;
@@ -73,8 +73,9 @@ __device__ inline bf16x8 dequant_word(uint32_t w, float s, float nzs)
     return o.v;
 }
 
-// r0: lanes 0-31 keep a, lanes 32-63 get a's... see below.  v_permlane32_swap(a, b) returns
-// {[a.low half | b.low half], [a.high half | b.high half]} (halves of 32 lanes).
+// v_permlane32_swap(a, b) returns {[a.low half | b.low half], [a.high half | b.high half]}
+// (halves of 32 lanes): `low` is a in lanes 0-31 and b's lanes 0-31 in lanes 32-63; `high` is
+// a's lanes 32-63 in lanes 0-31 and b in lanes 32-63.
 __device__ inline void swap_halves(uint32_t a, uint32_t b, uint32_t &low, uint32_t &high)
 {
     const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
@@ -82,10 +83,26 @@ __device__ inline void swap_halves(uint32_t a, uint32_t b, uint32_t &low, uint32
     high = r[1];
 }
 
+// X fp32 [M][K] -> bf16 [M][K], round to nearest even, done once per call.
+__global__ void convert_x(const float4 *__restrict__ X, size_t count4, uint2 *__restrict__ Xb)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count4) return;
+    const float4 v = X[i];
+    floatx2 a = {v.x, v.y}, b = {v.z, v.w};
+    bf16x2 pa = __builtin_convertvector(a, bf16x2), pb = __builtin_convertvector(b, bf16x2);
+    uint2 packed;
+    packed.x = *(uint32_t *)&pa;
+    packed.y = *(uint32_t *)&pb;
+    Xb[i] = packed;
+}
+
 template <int MB>
 __global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_small_b4(const GemmArgs A)
 {
-    __shared__ __attribute__((aligned(16))) __bf16 Xs[MB * 32 * XPITCH];
+    // two activation buffers: the chunk of the next step is written while this one is read
+    __shared__ __attribute__((aligned(16))) __bf16 Xs[2][MB * 32 * XPITCH];
+    constexpr int XLOADS = MB * 32 * (KC / 8) / (GEMM_WAVES * 64);   // 16-byte loads per thread and chunk
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -113,40 +130,60 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_small_b4(const GemmArgs 
     const int half = lane >> 5;           // which k-octet pair this lane feeds
     const int row = lane & 31;
 
-    for (int step = st0; step < st1; ++step) {
-        // this step's codes are in flight while the activations are staged
-        uint4 v[4];
+    // this thread's share of an activation chunk: XLOADS pieces of 8 bf16, rows past M are zero
+    uint4 xr[XLOADS];
+    auto load_x = [&](int step) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = codes[((size_t)step * 4 + u) * QG_WAVE];
-
-        // stage X[:, step*128 .. +128) as bf16 (rows past M are zero)
-        __syncthreads();                                   // readers of the previous chunk are done
-        for (int i = threadIdx.x; i < MB * 32 * (KC / 4); i += GEMM_WAVES * 64) {
-            const int m = i / (KC / 4), c4 = i % (KC / 4);
-            float4 xv = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (m < A.M) xv = *(const float4 *)(A.X + (size_t)m * A.K + (size_t)step * KC + c4 * 4);
-            floatx2 a = {xv.x, xv.y}, b = {xv.z, xv.w};
-            bf16x2 pa = __builtin_convertvector(a, bf16x2), pb = __builtin_convertvector(b, bf16x2);
-            uint2 packed;
-            packed.x = *(uint32_t *)&pa;
-            packed.y = *(uint32_t *)&pb;
-            *(uint2 *)(Xs + m * XPITCH + c4 * 4) = packed;
+        for (int j = 0; j < XLOADS; ++j) {
+            const int i = j * GEMM_WAVES * 64 + threadIdx.x;
+            const int m = i / (KC / 8), c8 = i % (KC / 8);
+            xr[j] = make_uint4(0u, 0u, 0u, 0u);
+            if (m < A.M) xr[j] = *(const uint4 *)(A.Xb + (size_t)m * A.K + (size_t)step * KC + c8 * 8);
         }
-        __syncthreads();
+    };
+    auto store_x = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < XLOADS; ++j) {
+            const int i = j * GEMM_WAVES * 64 + threadIdx.x;
+            const int m = i / (KC / 8), c8 = i % (KC / 8);
+            *(uint4 *)(&Xs[buf][m * XPITCH + c8 * 8]) = xr[j];
+        }
+    };
 
+    uint4 v[4], vn[4];
+    if (st0 < st1) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = codes[((size_t)st0 * 4 + u) * QG_WAVE];
+        load_x(st0);
+        store_x(0);
+    }
+    __syncthreads();
+
+    int buf = 0;
+    for (int step = st0; step < st1; ++step) {
+        const bool more = step + 1 < st1;
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) vn[u] = codes[((size_t)(step + 1) * 4 + u) * QG_WAVE];
+            load_x(step + 1);
+        }
+        // scale and zero of the step's groups (G is a multiple of 32)
+        float s_u[4], nzs_u[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            // group of these 32 k (G is a multiple of 32)
             const int g = steps_per_group > 1 ? step / steps_per_group
                                               : step * groups_per_step + (u * 32) / A.group;
-            const float s = sc[(size_t)g * QG_WAVE];
+            s_u[u] = sc[(size_t)g * QG_WAVE];
             const uint32_t zword = zr[(size_t)(g / 8) * QG_WAVE];
-            const float zf = (float)((zword >> (4 * (g % 8))) & 15u);
-            const float nzs = -zf * s;
+            nzs_u[u] = -(float)((zword >> (4 * (g % 8))) & 15u) * s_u[u];
+        }
+        const __bf16 *xs = Xs[buf];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
             // outputs 0-31 of the tile in both halves (P), outputs 32-63 in both halves (Q)
             uint32_t sP, sQ, nP, nQ, P0, Q0, P1, Q1;
-            swap_halves(__float_as_uint(s), __float_as_uint(s), sP, sQ);
-            swap_halves(__float_as_uint(nzs), __float_as_uint(nzs), nP, nQ);
+            swap_halves(__float_as_uint(s_u[u]), __float_as_uint(s_u[u]), sP, sQ);
+            swap_halves(__float_as_uint(nzs_u[u]), __float_as_uint(nzs_u[u]), nP, nQ);
             swap_halves(v[u].x, v[u].z, P0, Q0);       // k-octets 0 (low lanes) and 2 (high lanes)
             swap_halves(v[u].y, v[u].w, P1, Q1);       // k-octets 1 and 3
             const bf16x8 bP0 = dequant_word(P0, __uint_as_float(sP), __uint_as_float(nP));
@@ -155,15 +192,22 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_small_b4(const GemmArgs 
             const bf16x8 bQ1 = dequant_word(Q1, __uint_as_float(sQ), __uint_as_float(nQ));
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-                const __bf16 *xr = Xs + (mb * 32 + row) * XPITCH + u * 32 + half * 16;
-                const bf16x8 a0 = *(const bf16x8 *)(xr);          // octet 0 or 2
-                const bf16x8 a1 = *(const bf16x8 *)(xr + 8);      // octet 1 or 3
+                const __bf16 *xp = xs + (mb * 32 + row) * XPITCH + u * 32 + half * 16;
+                const bf16x8 a0 = *(const bf16x8 *)(xp);          // octet 0 or 2
+                const bf16x8 a1 = *(const bf16x8 *)(xp + 8);      // octet 1 or 3
                 acc[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bP0, acc[mb][0], 0, 0, 0);
                 acc[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bP1, acc[mb][0], 0, 0, 0);
                 acc[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bQ0, acc[mb][1], 0, 0, 0);
                 acc[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bQ1, acc[mb][1], 0, 0, 0);
             }
         }
+        if (more) {
+            store_x(buf ^ 1);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = vn[u];
+        }
+        __syncthreads();      // next chunk written, this chunk's readers done
+        buf ^= 1;
     }
 
     if (!have_tile) return;
@@ -203,8 +247,10 @@ int max_splits(int M) { return M <= 32 ? 8 : 4; }
 
 size_t qg_gemm_workspace_bytes(const QgLayout &L, int M)
 {
-    // partial results of the K split, or the GEMV workspace for the row-by-row path
-    const size_t partial = (size_t)max_splits(M) * M * L.N * sizeof(float);
+    // bf16 copy of X and partial results of the K split, or the GEMV workspace for the
+    // row-by-row path
+    const size_t partial = qg_round_up((size_t)M * L.K * 2, QG_SECTION_ALIGN) +
+                           (size_t)max_splits(M) * M * L.N * sizeof(float);
     const size_t gemv = (size_t)L.tiles * QG_MAX_CHUNKS * QG_WAVE * sizeof(float) +
                         qg_round_up((size_t)L.tiles * sizeof(unsigned), QG_SECTION_ALIGN);
     return qg_round_up(fast_path(L) ? partial : gemv, QG_SECTION_ALIGN);
@@ -251,8 +297,13 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     A.codes = (const uint4 *)(base + L.codes_off);
     A.scales = (const float *)(base + L.scales_off);
     A.zeros = (const uint32_t *)(base + L.zeros_off);
-    A.X = X;
-    A.out = splits > 1 ? (float *)workspace : Y;
+    __bf16 *Xb = (__bf16 *)workspace;
+    float *partial = (float *)((char *)workspace + qg_round_up((size_t)M * K * 2, QG_SECTION_ALIGN));
+    const size_t count4 = (size_t)M * K / 4;
+    hipLaunchKernelGGL(convert_x, dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0, st,
+                       (const float4 *)X, count4, (uint2 *)Xb);
+    A.Xb = Xb;
+    A.out = splits > 1 ? partial : Y;
     A.M = M;
     A.N = (int)N;
     A.K = (int)K;
@@ -271,7 +322,7 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     if (splits > 1) {
         const size_t count = (size_t)M * N;
         hipLaunchKernelGGL(add_splits, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st,
-                           (const float *)workspace, splits, count, Y);
+                           (const float *)partial, splits, count, Y);
     }
     return qg_launch_status();
 }
