@@ -26,6 +26,9 @@ import numpy as np
 import torch
 
 HBM_PEAK_GBS = 8000.0          # MI355X public peak
+# HBM bytes of one grouped launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
+# the same counters of a 256 MiB device copy (profiles/gemv_static_b4_g128_C2_layer_set.txt)
+MEASURED_TRAFFIC_BYTES = {"C2": 110.91e6}
 ROTATE_BYTES = 1.3e9           # distinct packed bytes touched between two uses of one copy
 
 
@@ -84,6 +87,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", default="C2", choices=["C2", "C3", "C4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain device copy of 256 MiB (reference for HBM byte counters)")
     ap.add_argument("--wpb", type=int, default=0)
     ap.add_argument("--bytes-per-wave", type=int, default=0)
     args = ap.parse_args()
@@ -105,6 +110,15 @@ def main():
         probs = [dict(p, packed=(p["packed"] if c == 0 else p["packed"].clone())) for p in base]
         launches.append(qg.GroupedGemv(probs))
     torch.cuda.synchronize()
+
+    if args.copy_calibration:
+        # a copy of known size: 256 MiB read + 256 MiB written; profilers' byte counters for this
+        # kernel give the factor between counter units and bytes
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     stream = torch.cuda.current_stream().cuda_stream
     for i in range(args.warmup):
@@ -149,7 +163,8 @@ def main():
         "cache_warm_single_copy_us": round(warm_ms * 1e3, 3),
         "host_wall_ms_per_step": round(wall_ms / args.steps, 6),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None},
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, base)

@@ -323,3 +323,36 @@ def test_gemm_small_full_size(qg, oracle, index, mi):
     err = _gemm_case(qg, oracle, W, X, cfg.bits, cfg.group)
     print(f"[full] C5[{index}] M={M} scaled error {err:.3e}", flush=True)
     assert err <= TOL_BF16, err
+
+
+# ------------------------------------------------------------------ the benchmark's own launch
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4"])
+def test_layer_set_grouped_launch_full_size(qg, oracle, name):
+    # the whole layer set in ONE grouped launch, as bench.py times it; every output of every
+    # matrix is compared with the oracle
+    cfg = synth.CONFIGS[name]
+    _announce("grouped layer set", name)
+    problems, refs = [], []
+    for i, (N, K) in enumerate(cfg.shapes):
+        W, (x,) = synth.matrix(cfg, i)
+        q0, s0, z0 = oracle.quantize(W, cfg.bits, cfg.group)
+        refs.append((oracle.matvec(q0, s0, z0, cfg.group, x), oracle.row_norms(q0, s0, z0, cfg.group), x))
+        q, s, z = qg.qg_quantize(dev(W), cfg.bits, cfg.group)
+        del W
+        assert np.array_equal(host(q), q0) and np.array_equal(host(z), z0)
+        assert np.array_equal(host(s).view(np.uint32), s0.view(np.uint32))
+        problems.append(dict(packed=qg.qg_pack(q, s, z, cfg.bits, cfg.group), N=N, K=K, bits=cfg.bits,
+                             group=cfg.group, x=dev(x), y=torch.empty(N, dtype=torch.float32, device="cuda")))
+        del q, s, z, q0, s0, z0
+    launch = qg.GroupedGemv(problems)
+    launch.launch()
+    first = [host(p["y"]).copy() for p in problems]
+    launch.launch()                                              # same workspace again
+    torch.cuda.synchronize()
+    worst = 0.0
+    for p, y1, (y_ref, norms, x) in zip(problems, first, refs):
+        assert np.array_equal(host(p["y"]), y1), "not deterministic"
+        worst = max(worst, scaled_error(y1, y_ref, norms, x))
+    print(f"[full] {name} grouped launch, worst scaled error {worst:.3e}", flush=True)
+    assert worst <= TOL_FP32, worst
