@@ -102,8 +102,15 @@ __device__ inline XBatch load_x32(const float *__restrict__ p)
 //         codes f, 4+f, 8+f, 12+f, and an octet takes two field sets.
 // 3 bits: a cell (words A, B, C, layout in qg_common.h) is four octets, one per source word
 //         A, B, C and the word T gathered from the spare bits.
+// Two independent accumulation chains per wavefront: a single dependent chain of FMAs can only
+// issue every ~5 cycles, two chains keep the SIMD busy with fewer resident wavefronts.  The
+// two halves are added once per group.
+struct Acc2 {
+    float a, b;
+};
+
 template <int BITS>
-__device__ inline float octet_dot(const uint4 *v, int bt, int o, const XBatch &xb, float acc)
+__device__ inline void octet_dot(const uint4 *v, int bt, int o, const XBatch &xb, Acc2 &acc)
 {
     if constexpr (BITS == 4) {
         const int cell = bt * 4 + o;
@@ -111,22 +118,21 @@ __device__ inline float octet_dot(const uint4 *v, int bt, int o, const XBatch &x
         const uint32_t lo = opaque(w & 0x0f0f0f0fu);          // even codes
         const uint32_t hi = opaque((w >> 4) & 0x0f0f0f0fu);   // odd codes
         const int x0 = 8 * o;
-        acc = fmaf(QG_B0(lo), xb[x0 + 0], acc);  acc = fmaf(QG_B0(hi), xb[x0 + 1], acc);
-        acc = fmaf(QG_B1(lo), xb[x0 + 2], acc);  acc = fmaf(QG_B1(hi), xb[x0 + 3], acc);
-        acc = fmaf(QG_B2(lo), xb[x0 + 4], acc);  acc = fmaf(QG_B2(hi), xb[x0 + 5], acc);
-        acc = fmaf(QG_B3(lo), xb[x0 + 6], acc);  acc = fmaf(QG_B3(hi), xb[x0 + 7], acc);
+        acc.a = fmaf(QG_B0(lo), xb[x0 + 0], acc.a);  acc.b = fmaf(QG_B0(hi), xb[x0 + 1], acc.b);
+        acc.a = fmaf(QG_B1(lo), xb[x0 + 2], acc.a);  acc.b = fmaf(QG_B1(hi), xb[x0 + 3], acc.b);
+        acc.a = fmaf(QG_B2(lo), xb[x0 + 4], acc.a);  acc.b = fmaf(QG_B2(hi), xb[x0 + 5], acc.b);
+        acc.a = fmaf(QG_B3(lo), xb[x0 + 6], acc.a);  acc.b = fmaf(QG_B3(hi), xb[x0 + 7], acc.b);
     } else if constexpr (BITS == 2) {
         const int cell = bt * 2 + (o >> 1);
         const uint32_t w = word_of(v[cell >> 2], cell & 3);
         const int x0 = 16 * (o >> 1);
-#pragma unroll
-        for (int f = 2 * (o & 1); f < 2 * (o & 1) + 2; ++f) {
-            const uint32_t m = opaque((w >> (2 * f)) & 0x03030303u);
-            acc = fmaf(QG_B0(m), xb[x0 + f], acc);
-            acc = fmaf(QG_B1(m), xb[x0 + 4 + f], acc);
-            acc = fmaf(QG_B2(m), xb[x0 + 8 + f], acc);
-            acc = fmaf(QG_B3(m), xb[x0 + 12 + f], acc);
-        }
+        const int f = 2 * (o & 1);
+        const uint32_t m0 = opaque((w >> (2 * f)) & 0x03030303u);
+        const uint32_t m1 = opaque((w >> (2 * f + 2)) & 0x03030303u);
+        acc.a = fmaf(QG_B0(m0), xb[x0 + f], acc.a);       acc.b = fmaf(QG_B0(m1), xb[x0 + f + 1], acc.b);
+        acc.a = fmaf(QG_B1(m0), xb[x0 + 4 + f], acc.a);   acc.b = fmaf(QG_B1(m1), xb[x0 + 4 + f + 1], acc.b);
+        acc.a = fmaf(QG_B2(m0), xb[x0 + 8 + f], acc.a);   acc.b = fmaf(QG_B2(m1), xb[x0 + 8 + f + 1], acc.b);
+        acc.a = fmaf(QG_B3(m0), xb[x0 + 12 + f], acc.a);  acc.b = fmaf(QG_B3(m1), xb[x0 + 12 + f + 1], acc.b);
     } else {
         const int cell = bt;
         const int u = cell >> 2, j = cell & 3;
@@ -142,12 +148,11 @@ __device__ inline float octet_dot(const uint4 *v, int bt, int o, const XBatch &x
         const uint32_t m0 = opaque(src & 0x07070707u);
         const uint32_t m1 = opaque((src >> 3) & 0x07070707u);
         const int x0 = 8 * o;
-        acc = fmaf(QG_B0(m0), xb[x0 + 0], acc);  acc = fmaf(QG_B1(m0), xb[x0 + 1], acc);
-        acc = fmaf(QG_B2(m0), xb[x0 + 2], acc);  acc = fmaf(QG_B3(m0), xb[x0 + 3], acc);
-        acc = fmaf(QG_B0(m1), xb[x0 + 4], acc);  acc = fmaf(QG_B1(m1), xb[x0 + 5], acc);
-        acc = fmaf(QG_B2(m1), xb[x0 + 6], acc);  acc = fmaf(QG_B3(m1), xb[x0 + 7], acc);
+        acc.a = fmaf(QG_B0(m0), xb[x0 + 0], acc.a);  acc.b = fmaf(QG_B0(m1), xb[x0 + 4], acc.b);
+        acc.a = fmaf(QG_B1(m0), xb[x0 + 1], acc.a);  acc.b = fmaf(QG_B1(m1), xb[x0 + 5], acc.b);
+        acc.a = fmaf(QG_B2(m0), xb[x0 + 2], acc.a);  acc.b = fmaf(QG_B2(m1), xb[x0 + 6], acc.b);
+        acc.a = fmaf(QG_B3(m0), xb[x0 + 3], acc.a);  acc.b = fmaf(QG_B3(m1), xb[x0 + 7], acc.b);
     }
-    return acc;
 }
 
 // ---- cross-lane sums on the DPP path (no LDS, no memory) ------------------------------
@@ -327,7 +332,7 @@ __device__ inline void fetch_step(StepData<BITS, GPS> &d, const TileView &T, int
 template <int BITS, int GPS>
 __device__ inline void compute_step(const StepData<BITS, GPS> &d, const float *__restrict__ xs,
                                     const float *__restrict__ xs_next, XBatch &xb, int step,
-                                    bool valid, float &acc, float &xacc, float &yacc)
+                                    bool valid, Acc2 &acc, float &xacc, float &yacc)
 {
     using F = Fmt<BITS>;
     using D = StepData<BITS, GPS>;
@@ -361,7 +366,7 @@ __device__ inline void compute_step(const StepData<BITS, GPS> &d, const float *_
 #pragma unroll
         for (int o = 0; o < 4; ++o) {
             if (o == 0) QG_SCHED_FENCE();
-            acc = octet_dot<BITS>(d.v, bt, o, xb, acc);
+            octet_dot<BITS>(d.v, bt, o, xb, acc);
             if (o == 0) {
                 QG_SCHED_FENCE();
                 // next batch in flight (it may belong to the next step)
@@ -377,8 +382,9 @@ __device__ inline void compute_step(const StepData<BITS, GPS> &d, const float *_
                     const uint32_t zword = d.zw[D::ZW > 1 ? gs / D::ZPER : 0];
                     const float zf = (float)((zword >> (F::ZBITS * (gabs % D::ZPER))) & ((1u << F::ZBITS) - 1u));
                     // a step past the end of the wavefront's range counts with scale 0
-                    yacc = fmaf(valid ? d.s[gs] : 0.0f, fmaf(-zf, xhat[gs], acc), yacc);
-                    acc = 0.0f;
+                    yacc = fmaf(valid ? d.s[gs] : 0.0f, fmaf(-zf, xhat[gs], acc.a + acc.b), yacc);
+                    acc.a = 0.0f;
+                    acc.b = 0.0f;
                 }
             }
         }
@@ -413,20 +419,21 @@ __global__ __launch_bounds__(1024) void gemv_static(const GemvArgs A)
     const float *__restrict__ x = P.x;
 
     // Two buffers used alternately: the next step is in flight while this one is computed.
-    // The loop body has no branch: a fetch past the wavefront's range repeats its last step,
-    // and a second half-iteration past the range is computed with scale 0.
+    // A fetch past the wavefront's range repeats its last step (no branch around the loads).
     const int last = s1 - 1;
     StepData<BITS, GPS> da, db;
     fetch_step(da, T, s0, lane);
     XBatch xb = load_x32(x + (size_t)s0 * S);
-    float yacc = 0.0f, acc = 0.0f, xacc = 0.0f;
+    float yacc = 0.0f, xacc = 0.0f;
+    Acc2 acc = {0.0f, 0.0f};
     for (int s = s0; s < s1; s += 2) {
         const int sb = s + 1 < last ? s + 1 : last;
         const int sc = s + 2 < last ? s + 2 : last;
         fetch_step(db, T, sb, lane);
         compute_step(da, x + (size_t)s * S, x + (size_t)sb * S, xb, s, true, acc, xacc, yacc);
+        if (s + 1 >= s1) break;                       // odd number of steps
         fetch_step(da, T, sc, lane);
-        compute_step(db, x + (size_t)sb * S, x + (size_t)sc * S, xb, sb, s + 1 < s1, acc, xacc, yacc);
+        compute_step(db, x + (size_t)sb * S, x + (size_t)sc * S, xb, sb, true, acc, xacc, yacc);
     }
     finish_tile(P, job, yacc, red);
 }
@@ -463,7 +470,8 @@ __global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
     StepData<BITS, 0> da, db;
     fetch_step(da, T, s0, lane);
     XBatch xb = load_x32(x + (size_t)s0 * S);
-    float yacc = 0.0f, acc = 0.0f, xacc = 0.0f;
+    float yacc = 0.0f, xacc = 0.0f;
+    Acc2 acc = {0.0f, 0.0f};
     int in_group = 0;                                   // steps of the running group done
     for (int s = s0; s < s1; ++s) {
         const int sn = s + 1 < s1 ? s + 1 : s;
@@ -476,8 +484,9 @@ __global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
             const float scale = T.scales[(size_t)g * QG_WAVE];
             const uint32_t zword = T.zeros[(size_t)(g / ZPER) * QG_WAVE];
             const float zf = (float)((zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u));
-            yacc = fmaf(scale, fmaf(-zf, xhat, acc), yacc);
-            acc = 0.0f;
+            yacc = fmaf(scale, fmaf(-zf, xhat, acc.a + acc.b), yacc);
+            acc.a = 0.0f;
+            acc.b = 0.0f;
             xacc = 0.0f;
             in_group = 0;
         }
@@ -514,7 +523,8 @@ __global__ __launch_bounds__(1024) void gemv_generic(const GemvArgs A)
     const uint32_t *zr = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
     const float *__restrict__ x = P.x;
     for (int g = g0; g < g1; ++g) {
-        float acc = 0.0f, sx = 0.0f;
+        Acc2 acc = {0.0f, 0.0f};
+        float sx = 0.0f;
         for (int c = g * cpg; c < (g + 1) * cpg; ++c) {
             const int unit = c >> 2;
             uint4 v[3];
@@ -534,13 +544,13 @@ __global__ __launch_bounds__(1024) void gemv_generic(const GemvArgs A)
             }
 #pragma unroll
             for (int o = 0; o < 4; ++o)
-                if (o / (4 / CPB) == pos) acc = octet_dot<BITS>(v, bt, o, xb, acc);
+                if (o / (4 / CPB) == pos) octet_dot<BITS>(v, bt, o, xb, acc);
 #pragma unroll
             for (int i = 0; i < F::CELL; ++i) sx += xs[i];
         }
         const uint32_t zword = zr[(size_t)(g / ZPER) * QG_WAVE];
         const float zf = (float)((zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u));
-        yacc = fmaf(sc[(size_t)g * QG_WAVE], fmaf(-zf, sx, acc), yacc);
+        yacc = fmaf(sc[(size_t)g * QG_WAVE], fmaf(-zf, sx, acc.a + acc.b), yacc);
     }
     finish_tile(P, job, yacc, red);
 }
