@@ -35,6 +35,8 @@ struct GemvProblem {
     int group;             // G
     int chunks;            // K-split over workgroups (1: a workgroup covers all of K)
     int waves_per_tile;    // wavefronts of a workgroup that share one tile
+    int inv_waves_per_tile;   // ceil(65536 / waves_per_tile): wave / wpt = (wave * inv) >> 16 for wave < 16
+    int team_full;         // wavefronts of a team that have work when a workgroup covers all of K
     int tiles_per_block;   // tiles one workgroup handles (1 if chunks > 1)
     int steps_per_wave;
     int steps_per_group;   // runtime-group kernel only
@@ -222,20 +224,23 @@ __device__ inline WaveJob locate(const GemvProblem &P, int local_block, int item
 {
     WaveJob j;
     const int wpt = P.waves_per_tile, spw = P.steps_per_wave;
-    const int slot = wave / wpt, sub = wave - slot * wpt;
-    if (P.chunks > 1) {
+    const int slot = (wave * P.inv_waves_per_tile) >> 16;     // wave / wpt without a division
+    const int sub = wave - slot * wpt;
+    int first = 0;
+    if (P.chunks > 1) {                                       // rare: K also split over workgroups
         j.tile = local_block / P.chunks;
         j.chunk = local_block - j.tile * P.chunks;
+        first = j.chunk * wpt * spw;
+        const int left = (items - first + spw - 1) / spw;
+        j.team = left < wpt ? left : wpt;
     } else {
         j.tile = local_block * P.tiles_per_block + slot;
         j.chunk = 0;
+        j.team = P.team_full;
     }
-    const int first = j.chunk * wpt * spw;
     j.item0 = first + sub * spw;
     j.item1 = j.item0 + spw < items ? j.item0 + spw : items;
     j.lead = slot * wpt;
-    const int left = (items - first + spw - 1) / spw;
-    j.team = left < wpt ? left : wpt;
     j.work = slot < P.tiles_per_block && j.tile < P.tiles && j.item0 < j.item1;
     return j;
 }
@@ -404,7 +409,7 @@ __global__ __launch_bounds__(1024) void gemv_static(const GemvArgs A)
     __shared__ float red[16][QG_WAVE];
 
     const int pi = find_problem(A, blockIdx.x);
-    const GemvProblem &P = A.p[pi];
+    const GemvProblem P = A.p[pi];                 // one copy: all fields fetched at once
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.steps, wave);
@@ -452,7 +457,7 @@ __global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
     __shared__ float red[16][QG_WAVE];
 
     const int pi = find_problem(A, blockIdx.x);
-    const GemvProblem &P = A.p[pi];
+    const GemvProblem P = A.p[pi];                 // one copy: all fields fetched at once
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int spg = P.steps_per_group;
@@ -508,7 +513,7 @@ __global__ __launch_bounds__(1024) void gemv_generic(const GemvArgs A)
     __shared__ float red[16][QG_WAVE];
 
     const int pi = find_problem(A, blockIdx.x);
-    const GemvProblem &P = A.p[pi];
+    const GemvProblem P = A.p[pi];                 // one copy: all fields fetched at once
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int cpg = P.group / F::CELL;
@@ -730,6 +735,9 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         P.steps_per_wave = (int)spw_of[i];
         P.chunks = (int)chunks_of[i];
         P.waves_per_tile = (int)team_of[i];
+        P.inv_waves_per_tile = (65536 + P.waves_per_tile - 1) / P.waves_per_tile;
+        P.team_full = (int)((pl[i].items + spw_of[i] - 1) / spw_of[i]);
+        if (P.team_full > P.waves_per_tile) P.team_full = P.waves_per_tile;
         P.tiles_per_block = P.chunks > 1 ? 1 : wpb / P.waves_per_tile;
         P.block_begin = blocks;
         A.block_begin[i] = blocks;
