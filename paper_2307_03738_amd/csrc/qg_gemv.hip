@@ -83,11 +83,15 @@ struct XBatch {
     xvec16 lo, hi;
     __device__ inline float operator[](int i) const { return i < 16 ? lo[i] : hi[i - 16]; }
 };
+// x is read-only for the whole launch, so it is read through the constant address space: that
+// keeps these loads on the scalar path whatever else the kernel does.
+typedef __attribute__((address_space(4))) const xvec16 *ConstX16;
 __device__ inline XBatch load_x32(const float *__restrict__ p)
 {
+    const ConstX16 cp = (ConstX16)(unsigned long long)p;
     XBatch b;
-    b.lo = *(const xvec16 *)p;
-    b.hi = *(const xvec16 *)(p + 16);
+    b.lo = cp[0];
+    b.hi = cp[1];
     return b;
 }
 
