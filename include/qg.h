@@ -67,11 +67,13 @@ const char *qg_status_string(int status);
 size_t qg_packed_bytes(int64_t N, int64_t K, int bits, int group, int layout);
 
 /* Size in bytes of the scratch buffer qg_gemv (M = 1) or qg_gemm_small (M > 1) needs for
- * this problem: partial sums of the K-split and one counter per 64 outputs.  For a grouped
- * launch, the sum over its problems.  0 if the shape is not accepted.
- * The buffer must be zero-filled once before its first use (qg_workspace_init); every call
- * leaves it zero-filled again where that matters.  Two calls that overlap in time must not
- * share one workspace. */
+ * this problem (meeting slots of the K-split reduction; partial results and the bf16 copy
+ * of X for the GEMM).  For a grouped launch, the sum over its problems.  0 if the shape is
+ * not accepted.
+ * The buffer must be prepared once before its first use with qg_workspace_init (it fills it
+ * with the "empty slot" pattern); every qg_gemv call leaves it prepared again.  A buffer
+ * belongs to one problem shape and one of the two entry points, and two calls that overlap
+ * in time must not share one. */
 size_t qg_workspace_bytes(int64_t N, int64_t K, int bits, int group, int M);
 int qg_workspace_init(void *workspace, size_t bytes, void *stream);
 
@@ -129,8 +131,8 @@ int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
                   void *workspace, size_t workspace_bytes, void *stream);
 
 /* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe).  0 restores the
- * built-in choice.  waves_per_block in 1..16; bytes_per_wave = packed code bytes one
- * wavefront streams before the K-split reduction. */
+ * built-in choice.  waves_per_block in 1..16 = most wavefronts that share one tile of 64
+ * outputs inside a workgroup; bytes_per_wave = packed code bytes one wavefront streams. */
 int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave);
 
 #ifdef __cplusplus

@@ -251,8 +251,7 @@ size_t qg_gemm_workspace_bytes(const QgLayout &L, int M)
     // row-by-row path
     const size_t partial = qg_round_up((size_t)M * L.K * 2, QG_SECTION_ALIGN) +
                            (size_t)max_splits(M) * M * L.N * sizeof(float);
-    const size_t gemv = (size_t)L.tiles * QG_MAX_CHUNKS * QG_WAVE * sizeof(float) +
-                        qg_round_up((size_t)L.tiles * sizeof(unsigned), QG_SECTION_ALIGN);
+    const size_t gemv = (size_t)L.tiles * QG_MAX_CHUNKS * QG_WAVE * sizeof(uint32_t);
     return qg_round_up(fast_path(L) ? partial : gemv, QG_SECTION_ALIGN);
 }
 

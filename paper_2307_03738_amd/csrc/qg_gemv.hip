@@ -15,10 +15,13 @@
 // is the paper's x-hat (Algorithm 1 input), computed once per wavefront with a cross-lane
 // reduction and kept one group per lane.
 //
-// K is split over the wavefronts of a workgroup (LDS reduction in a fixed order) and, when
-// that is not enough parallelism, over workgroups: each writes a partial vector, and the
-// workgroup that arrives last at the tile's counter adds the partials in a fixed order.
-// No floating-point atomics, so results do not depend on timing.
+// K is split over the wavefronts of a workgroup (LDS reduction in a fixed order) and, for
+// tiles whose K is too long for one workgroup, over 2, 4, ... workgroups whose partial
+// vectors are combined pairwise up a fixed binary tree: the two partners of a pair meet in
+// one 32-bit slot by atomic exchange -- whoever arrives second finds the other's value,
+// adds it (a + b = b + a, so the bits do not depend on who was second) and carries the sum
+// to the next level.  The value travels inside the atomic itself, so no fence and no cache
+// maintenance is needed, and results do not depend on timing.
 #include "qg_common.h"
 
 namespace {
@@ -29,11 +32,11 @@ struct GemvProblem {
     const uint32_t *zeros;
     const float *x;
     float *y;
-    float *partial;        // [tile][chunk][64]
-    unsigned *counter;     // [tile]
+    uint32_t *slots;       // [tile][QG_MAX_CHUNKS][64] meeting slots of the reduction tree
     int N, K, tiles, steps, ngroups, zwords;
     int group;             // G
-    int chunks;            // K-split over workgroups (1: a workgroup covers all of K)
+    int chunks;            // K-split over workgroups, a power of two (1: a workgroup covers all of K)
+    int chunk_shift;       // log2(chunks)
     int waves_per_tile;    // wavefronts of a workgroup that share one tile
     int inv_waves_per_tile;   // ceil(65536 / waves_per_tile): wave / wpt = (wave * inv) >> 16 for wave < 16
     int team_full;         // wavefronts of a team that have work when a workgroup covers all of K
@@ -42,6 +45,8 @@ struct GemvProblem {
     int steps_per_group;   // runtime-group kernel only
     int block_begin;       // first block of this problem in the grid
 };
+
+#define QG_SLOT_EMPTY 0xffffffffu
 
 struct GemvArgs {
     int count;
@@ -231,9 +236,9 @@ __device__ inline WaveJob locate(const GemvProblem &P, int local_block, int item
     const int slot = (wave * P.inv_waves_per_tile) >> 16;     // wave / wpt without a division
     const int sub = wave - slot * wpt;
     int first = 0;
-    if (P.chunks > 1) {                                       // rare: K also split over workgroups
-        j.tile = local_block / P.chunks;
-        j.chunk = local_block - j.tile * P.chunks;
+    if (P.chunks > 1) {                                       // K also split over workgroups
+        j.tile = local_block >> P.chunk_shift;
+        j.chunk = local_block - (j.tile << P.chunk_shift);
         first = j.chunk * wpt * spw;
         const int left = (items - first + spw - 1) / spw;
         j.team = left < wpt ? left : wpt;
@@ -251,8 +256,8 @@ __device__ inline WaveJob locate(const GemvProblem &P, int local_block, int item
 
 // K-split epilogue.  The wavefronts of a team pass their 64 partial outputs through LDS
 // (wavefronts without work have already ended; a barrier only waits for wavefronts that are
-// still alive); the team's lead adds them in wavefront order and either stores y or hands
-// the vector to the tile's last-arriving workgroup.
+// still alive); the team's lead adds them in wavefront order and either stores y or enters
+// the tile's reduction tree.  An empty slot holds a NaN pattern no partial sum can have.
 __device__ inline void finish_tile(const GemvProblem &P, const WaveJob &j, float yacc,
                                    float (*red)[QG_WAVE])
 {
@@ -269,20 +274,22 @@ __device__ inline void finish_tile(const GemvProblem &P, const WaveJob &j, float
         if (n < P.N) P.y[n] = t;
         return;
     }
-    float *mine = P.partial + ((size_t)tile * P.chunks + chunk) * QG_WAVE;
-    __hip_atomic_store(mine + lane, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __threadfence();                                   // publish the partial before the count
-    unsigned arrived = 0;
-    if (lane == 0) arrived = atomicAdd(P.counter + tile, 1u);
-    arrived = __builtin_amdgcn_readfirstlane(arrived);
-    if (arrived != (unsigned)P.chunks - 1u) return;
-    __threadfence();                                   // see every other block's partial
-    const float *all = P.partial + (size_t)tile * P.chunks * QG_WAVE;
-    float sum = 0.0f;
-    for (int c = 0; c < P.chunks; ++c)
-        sum += __hip_atomic_load(all + c * QG_WAVE + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (n < P.N) P.y[n] = sum;
-    if (lane == 0) P.counter[tile] = 0u;               // leave the workspace zeroed
+    // pairwise reduction tree over the chunks of this tile, one independent tree per lane
+    uint32_t *slots = P.slots + (size_t)tile * QG_MAX_CHUNKS * QG_WAVE + lane;
+    int node = chunk, width = P.chunks, base = 0;
+    float v = t;
+    while (width > 1) {
+        uint32_t *slot = slots + (size_t)(base + (node >> 1)) * QG_WAVE;
+        const uint32_t other = __hip_atomic_exchange(slot, __float_as_uint(v), __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        if (other == QG_SLOT_EMPTY) return;               // first of the pair: the partner carries on
+        v += __uint_as_float(other);
+        __hip_atomic_store(slot, QG_SLOT_EMPTY, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        base += width >> 1;
+        width >>= 1;
+        node >>= 1;
+    }
+    if (n < P.N) P.y[n] = v;
 }
 
 // Index of the problem a block belongs to: the last one whose first block is <= bid.
@@ -564,17 +571,16 @@ __global__ __launch_bounds__(1024) void gemv_generic(const GemvArgs A)
     finish_tile(P, job, yacc, red);
 }
 
-__global__ void fill_zero_u32(uint32_t *p, size_t n)
+__global__ void fill_u32(uint32_t *p, size_t n, uint32_t value)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0u;
+    if (i < n) p[i] = value;
 }
 
 // ------------------------------------------------------------------ host side
 
 int g_tune_wpb = 0;
 int g_tune_bytes_per_wave = 0;
-bool g_tune_fixed_team = true;
 
 enum Kind { KIND_STATIC, KIND_RUNTIME, KIND_GENERIC };
 
@@ -626,9 +632,7 @@ Plan make_plan(const QgLayout &L)
 
 size_t workspace_for(const QgLayout &L)
 {
-    const size_t partial = (size_t)L.tiles * QG_MAX_CHUNKS * QG_WAVE * sizeof(float);
-    const size_t counters = qg_round_up((size_t)L.tiles * sizeof(unsigned), QG_SECTION_ALIGN);
-    return partial + counters;
+    return (size_t)L.tiles * QG_MAX_CHUNKS * QG_WAVE * sizeof(uint32_t);
 }
 
 template <int BITS>
@@ -662,56 +666,53 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     }
     const Kind kind = pl[0].kind;
 
-    // Launch shape.  A workgroup owns one tile of 64 outputs and, whenever the launch has
-    // enough tiles, the whole of K: its wavefronts split K and meet in LDS, and nothing
-    // crosses workgroups (the cross-workgroup hand-over needs device-scope fences, which
-    // write back and invalidate L2 and cost more than they save).  Every wavefront of the
-    // launch gets the same number of items, so that tiles with a long K simply use more
-    // wavefronts of their workgroup; wavefronts without work end at once.  Launches with
-    // few tiles split K over workgroups as well.
-    int64_t total_tiles = 0;
-    size_t code_bytes = 0;
-    for (int i = 0; i < count; ++i) {
-        total_tiles += L[i].tiles;
-        code_bytes += (size_t)L[i].tiles * pl[i].items * pl[i].item_bytes;
-    }
-    int split = 1;
-    if (total_tiles < 128) {
-        split = (int)((128 + total_tiles - 1) / total_tiles);
-        if (split > QG_MAX_CHUNKS) split = QG_MAX_CHUNKS;
-    }
-    const int cap = g_tune_wpb > 0 ? g_tune_wpb : 12;        // wavefronts per workgroup, at most
-    size_t target = (size_t)g_tune_bytes_per_wave;           // code bytes per wavefront
+    // Launch shape.  Every wavefront of the launch gets about the same, small amount of work
+    // (`target` bytes of codes), so that all of them are resident at once and finish together.
+    // A tile of 64 outputs is covered by a team of up to `cap` wavefronts inside one
+    // workgroup (they meet in LDS); a tile whose K needs more wavefronts than that is cut
+    // into 2, 4, ... workgroups that meet in the reduction tree.  Short teams are packed
+    // several to a workgroup.  Launches with little work per wavefront slot use less than
+    // `target` per wavefront so that the chip is still covered.
+    const int cap = g_tune_wpb > 0 ? g_tune_wpb : 8;             // wavefronts per team, at most
+    size_t target = (size_t)g_tune_bytes_per_wave;               // code bytes per wavefront
     if (target == 0) {
-        target = code_bytes / (256 * 16);
+        size_t code_bytes = 0;
+        for (int i = 0; i < count; ++i) code_bytes += (size_t)L[i].tiles * pl[i].items * pl[i].item_bytes;
+        target = code_bytes / (256 * 24);                        // about 24 wavefronts per CU
         if (target < 4096) target = 4096;
-        if (target > 24576) target = 24576;
-    }
-    int64_t spw = 1;
-    for (int i = 0; i < count; ++i) {
-        const int64_t per_wg = (pl[i].items + split - 1) / split;
-        int64_t want = (int64_t)((target + pl[i].item_bytes / 2) / pl[i].item_bytes);
-        if (want < 1) want = 1;
-        if ((per_wg + want - 1) / want > cap) want = (per_wg + cap - 1) / cap;
-        if (want > spw) spw = want;
+        if (target > 16384) target = 16384;
     }
 
     int wpb = 1;
     int64_t spw_of[QG_MAX_GROUPED], team_of[QG_MAX_GROUPED], chunks_of[QG_MAX_GROUPED];
     for (int i = 0; i < count; ++i) {
-        int64_t w = spw;
-        if (g_tune_fixed_team) {
-            // every tile gets a team of `cap` wavefronts; tiles with a long K take more items each
-            const int64_t per_wg = (pl[i].items + split - 1) / split;
-            w = (per_wg + cap - 1) / cap;
+        const Plan &q = pl[i];
+        int64_t want = (int64_t)((target + q.item_bytes / 2) / q.item_bytes);   // items per wavefront
+        want = (want + q.quantum - 1) / q.quantum * q.quantum;
+        if (want < q.quantum) want = q.quantum;
+        if (want > q.max_spw) want = q.max_spw;
+        // Among the ways to cover K with `chunks` (a power of two) non-empty workgroups of `team`
+        // <= cap wavefronts, take the one whose items per wavefront come closest to `want`;
+        // on a tie the fewest workgroups, then the smallest team.
+        bool found = false;
+        int64_t best_miss = 0;
+        for (int64_t chunks = 1; chunks <= QG_MAX_CHUNKS; chunks *= 2) {
+            for (int64_t team = 1; team <= cap; ++team) {
+                int64_t spw = (q.items + chunks * team - 1) / (chunks * team);
+                spw = (spw + q.quantum - 1) / q.quantum * q.quantum;
+                if (spw > q.max_spw) continue;
+                if ((chunks - 1) * team * spw >= q.items) continue;       // an empty workgroup
+                const int64_t miss = spw > want ? spw - want : want - spw;
+                if (!found || miss < best_miss) {
+                    spw_of[i] = spw;
+                    team_of[i] = team;
+                    chunks_of[i] = chunks;
+                    best_miss = miss;
+                    found = true;
+                }
+            }
         }
-        w = (w + pl[i].quantum - 1) / pl[i].quantum * pl[i].quantum;
-        if (w > pl[i].max_spw) w = pl[i].max_spw;
-        spw_of[i] = w;
-        const int64_t waves = (pl[i].items + w - 1) / w;
-        chunks_of[i] = (waves + cap - 1) / cap;
-        if (chunks_of[i] > QG_MAX_CHUNKS) return QG_ERR_UNSUPPORTED;   // (cap below 16 set by the knob)
-        team_of[i] = (waves + chunks_of[i] - 1) / chunks_of[i];
+        if (!found) return QG_ERR_UNSUPPORTED;
         if (team_of[i] > wpb) wpb = (int)team_of[i];
     }
 
@@ -725,9 +726,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         P.zeros = (const uint32_t *)(base + L[i].zeros_off);
         P.x = d.x;
         P.y = d.y;
-        char *ws = workspace + ws_off[idx[i]];
-        P.partial = (float *)ws;
-        P.counter = (unsigned *)(ws + (size_t)L[i].tiles * QG_MAX_CHUNKS * QG_WAVE * sizeof(float));
+        P.slots = (uint32_t *)(workspace + ws_off[idx[i]]);
         P.N = (int)L[i].N;
         P.K = (int)L[i].K;
         P.tiles = (int)L[i].tiles;
@@ -738,6 +737,8 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         P.steps_per_group = (int)pl[i].quantum;
         P.steps_per_wave = (int)spw_of[i];
         P.chunks = (int)chunks_of[i];
+        P.chunk_shift = 0;
+        while ((1 << P.chunk_shift) < P.chunks) ++P.chunk_shift;
         P.waves_per_tile = (int)team_of[i];
         P.inv_waves_per_tile = (65536 + P.waves_per_tile - 1) / P.waves_per_tile;
         P.team_full = (int)((pl[i].items + spw_of[i] - 1) / spw_of[i]);
@@ -774,10 +775,9 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
 
 extern "C" int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave)
 {
-    if (waves_per_block < 0 || waves_per_block > 16 || bytes_per_wave < -1) return QG_ERR_SHAPE;
+    if (waves_per_block < 0 || waves_per_block > 16 || bytes_per_wave < 0) return QG_ERR_SHAPE;
     g_tune_wpb = waves_per_block;
-    g_tune_fixed_team = bytes_per_wave <= 0;
-    g_tune_bytes_per_wave = bytes_per_wave > 0 ? bytes_per_wave : 0;
+    g_tune_bytes_per_wave = bytes_per_wave;
     return QG_OK;
 }
 
@@ -796,8 +796,8 @@ extern "C" int qg_workspace_init(void *workspace, size_t bytes, void *stream)
     if (((uintptr_t)workspace & 3u) || (bytes & 3u)) return QG_ERR_ALIGN;
     const size_t n = bytes / 4;
     if (n == 0) return QG_OK;
-    hipLaunchKernelGGL(fill_zero_u32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                       (hipStream_t)stream, (uint32_t *)workspace, n);
+    hipLaunchKernelGGL(fill_u32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, (uint32_t *)workspace, n, QG_SLOT_EMPTY);
     return qg_launch_status();
 }
 
