@@ -673,7 +673,9 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     // into 2, 4, ... workgroups that meet in the reduction tree.  Short teams are packed
     // several to a workgroup.  Launches with little work per wavefront slot use less than
     // `target` per wavefront so that the chip is still covered.
-    const int cap = g_tune_wpb > 0 ? g_tune_wpb : 8;             // wavefronts per team, at most
+    // wavefronts per team, at most (measured: 12 is best for the 4-bit kernels, 8 for the
+    // 2- and 3-bit ones, which hold more registers per wavefront)
+    const int cap = g_tune_wpb > 0 ? g_tune_wpb : (L[0].bits == 4 ? 12 : 8);
     size_t target = (size_t)g_tune_bytes_per_wave;               // code bytes per wavefront
     if (target == 0) {
         size_t code_bytes = 0;
