@@ -186,14 +186,19 @@ __device__ inline float uniform_lane(float v, int lane)     // lane is a compile
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
 
-// Sums of consecutive segments of SEG lanes (SEG = 8, 16, 32 or 64) of v, returned as
+// Sums of consecutive segments of SEG lanes (SEG = 4, 8, 16, 32 or 64) of v, returned as
 // wavefront-uniform values out[0 .. 64/SEG).  This is x-hat of Algorithm 1 for one group
 // when lane l holds x[k0 + l].
 template <int SEG>
 __device__ inline void segment_sums(float v, float *out)
 {
     v = dpp_add<QG_DPP_QUAD_XOR1>(v);
-    v = dpp_add<QG_DPP_QUAD_XOR2>(v);
+    v = dpp_add<QG_DPP_QUAD_XOR2>(v);                        // every 4 lanes hold their sum
+    if constexpr (SEG == 4) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) out[i] = uniform_lane(v, 4 * i);
+        return;
+    }
     v = dpp_add<QG_DPP_HALF_MIRROR>(v);                      // every 8 lanes hold their sum
     if constexpr (SEG == 8) {
 #pragma unroll
@@ -308,11 +313,11 @@ __device__ inline int find_problem(const GemvArgs &A, int bid)
 template <int BITS, int GPS>
 struct StepData {
     static constexpr int L = loads_per_step<BITS>();
-    static constexpr int NXV = codes_per_step<BITS>() / 64;
+    static constexpr int NXV = codes_per_step<BITS>() / 128;   // lane l holds x[128 i + 2l], x[128 i + 2l + 1]
     static constexpr int ZPER = 32 / Fmt<BITS>::ZBITS;
     static constexpr int ZW = GPS > ZPER ? GPS / ZPER : 1;
     uint4 v[L];
-    float xv[NXV];
+    float2 xv[NXV];
     float s[GPS > 0 ? GPS : 1];
     uint32_t zw[ZW];
 };
@@ -337,7 +342,8 @@ __device__ inline void fetch_step(StepData<BITS, GPS> &d, const TileView &T, int
         for (int w = 0; w < D::ZW; ++w) d.zw[w] = T.zeros[(size_t)((step * GPS) / D::ZPER + w) * QG_WAVE];
     }
 #pragma unroll
-    for (int i = 0; i < D::NXV; ++i) d.xv[i] = T.x[(size_t)step * codes_per_step<BITS>() + i * 64 + lane];
+    for (int i = 0; i < D::NXV; ++i)
+        d.xv[i] = *(const float2 *)(T.x + (size_t)step * codes_per_step<BITS>() + i * 128 + 2 * lane);
 }
 
 // The arithmetic of one step on data that has arrived.  xb holds the first 32 x values of
@@ -359,20 +365,21 @@ __device__ inline void compute_step(const StepData<BITS, GPS> &d, const float *_
     float xhat[GPS > 0 ? GPS : 1];
     if constexpr (GPS == 0) {
 #pragma unroll
-        for (int i = 0; i < D::NXV; ++i) xacc += d.xv[i];
+        for (int i = 0; i < D::NXV; ++i) xacc += d.xv[i].x + d.xv[i].y;
     } else {
         constexpr int G = S / GPS;
-        if constexpr (G >= 64) {
+        if constexpr (G >= 128) {
 #pragma unroll
             for (int g = 0; g < GPS; ++g) {
                 float v = 0.0f;
 #pragma unroll
-                for (int i = 0; i < G / 64; ++i) v += d.xv[g * (G / 64) + i];
+                for (int i = 0; i < G / 128; ++i) v += d.xv[g * (G / 128) + i].x + d.xv[g * (G / 128) + i].y;
                 segment_sums<64>(v, &xhat[g]);
             }
         } else {
+            // a group of G codes sits in G/2 neighbouring lanes
 #pragma unroll
-            for (int i = 0; i < D::NXV; ++i) segment_sums<G>(d.xv[i], &xhat[i * (64 / G)]);
+            for (int i = 0; i < D::NXV; ++i) segment_sums<G / 2>(d.xv[i].x + d.xv[i].y, &xhat[i * (128 / G)]);
         }
     }
 
