@@ -12,8 +12,8 @@
 // the raw code words (w0 with w2, w1 with w3) turns one into the other for both 32-output
 // blocks at once, so weights go from HBM to the MFMA operand through registers only:
 // mask, convert, one FMA with the group's (s, -z s), pack to bf16.  Every weight is
-// dequantized exactly once.  The activation rows are converted to bf16 once per call and
-// staged chunk by chunk (128 k) through LDS, double-buffered, shared by the four wavefronts
+// dequantized exactly once.  The activation rows are converted to bf16 on their way into
+// LDS, chunk by chunk (128 k), double-buffered, shared by the four wavefronts
 // of a workgroup, which work on four neighbouring tiles over the same k range.  K may be
 // cut into `splits` ranges handled by different workgroups; their fp32 partial results are
 // added by a second small kernel in a fixed order.
@@ -38,7 +38,7 @@ struct GemmArgs {
     const uint4 *codes;
     const float *scales;
     const uint32_t *zeros;
-    const __bf16 *Xb;          // activations as bf16 [M][K]
+    const float *X;            // activations [M][K] fp32
     float *out;                // Y, or partial results [split][M][N]
     int M, N, K, tiles, steps, ngroups, zwords, group;
     int steps_per_split;
@@ -83,26 +83,12 @@ __device__ inline void swap_halves(uint32_t a, uint32_t b, uint32_t &low, uint32
     high = r[1];
 }
 
-// X fp32 [M][K] -> bf16 [M][K], round to nearest even, done once per call.
-__global__ void convert_x(const float4 *__restrict__ X, size_t count4, uint2 *__restrict__ Xb)
-{
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= count4) return;
-    const float4 v = X[i];
-    floatx2 a = {v.x, v.y}, b = {v.z, v.w};
-    bf16x2 pa = __builtin_convertvector(a, bf16x2), pb = __builtin_convertvector(b, bf16x2);
-    uint2 packed;
-    packed.x = *(uint32_t *)&pa;
-    packed.y = *(uint32_t *)&pb;
-    Xb[i] = packed;
-}
-
 template <int MB>
 __global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_small_b4(const GemmArgs A)
 {
     // two activation buffers: the chunk of the next step is written while this one is read
     __shared__ __attribute__((aligned(16))) __bf16 Xs[2][MB * 32 * XPITCH];
-    constexpr int XLOADS = MB * 32 * (KC / 8) / (GEMM_WAVES * 64);   // 16-byte loads per thread and chunk
+    constexpr int XLOADS = MB * 32 * (KC / 4) / (GEMM_WAVES * 64);   // float4 loads per thread and chunk
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -130,23 +116,29 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_small_b4(const GemmArgs 
     const int half = lane >> 5;           // which k-octet pair this lane feeds
     const int row = lane & 31;
 
-    // this thread's share of an activation chunk: XLOADS pieces of 8 bf16, rows past M are zero
-    uint4 xr[XLOADS];
+    // this thread's share of an activation chunk: XLOADS pieces of 4 consecutive k, converted
+    // to bf16 (round to nearest even) on the way into LDS; rows past M are zero
+    float4 xr[XLOADS];
     auto load_x = [&](int step) {
 #pragma unroll
         for (int j = 0; j < XLOADS; ++j) {
             const int i = j * GEMM_WAVES * 64 + threadIdx.x;
-            const int m = i / (KC / 8), c8 = i % (KC / 8);
-            xr[j] = make_uint4(0u, 0u, 0u, 0u);
-            if (m < A.M) xr[j] = *(const uint4 *)(A.Xb + (size_t)m * A.K + (size_t)step * KC + c8 * 8);
+            const int m = i / (KC / 4), c4 = i % (KC / 4);
+            xr[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (m < A.M) xr[j] = *(const float4 *)(A.X + (size_t)m * A.K + (size_t)step * KC + c4 * 4);
         }
     };
     auto store_x = [&](int buf) {
 #pragma unroll
         for (int j = 0; j < XLOADS; ++j) {
             const int i = j * GEMM_WAVES * 64 + threadIdx.x;
-            const int m = i / (KC / 8), c8 = i % (KC / 8);
-            *(uint4 *)(&Xs[buf][m * XPITCH + c8 * 8]) = xr[j];
+            const int m = i / (KC / 4), c4 = i % (KC / 4);
+            floatx2 a = {xr[j].x, xr[j].y}, b = {xr[j].z, xr[j].w};
+            bf16x2 pa = __builtin_convertvector(a, bf16x2), pb = __builtin_convertvector(b, bf16x2);
+            uint2 packed;
+            packed.x = *(uint32_t *)&pa;
+            packed.y = *(uint32_t *)&pb;
+            *(uint2 *)(&Xs[buf][m * XPITCH + c4 * 4]) = packed;
         }
     };
 
@@ -247,10 +239,8 @@ int max_splits(int M) { return M <= 32 ? 8 : 4; }
 
 size_t qg_gemm_workspace_bytes(const QgLayout &L, int M)
 {
-    // bf16 copy of X and partial results of the K split, or the GEMV workspace for the
-    // row-by-row path
-    const size_t partial = qg_round_up((size_t)M * L.K * 2, QG_SECTION_ALIGN) +
-                           (size_t)max_splits(M) * M * L.N * sizeof(float);
+    // partial results of the K split, or the GEMV workspace for the row-by-row path
+    const size_t partial = (size_t)max_splits(M) * M * L.N * sizeof(float);
     const size_t gemv = (size_t)L.tiles * QG_MAX_CHUNKS * QG_WAVE * sizeof(uint32_t);
     return qg_round_up(fast_path(L) ? partial : gemv, QG_SECTION_ALIGN);
 }
@@ -296,12 +286,8 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     A.codes = (const uint4 *)(base + L.codes_off);
     A.scales = (const float *)(base + L.scales_off);
     A.zeros = (const uint32_t *)(base + L.zeros_off);
-    __bf16 *Xb = (__bf16 *)workspace;
-    float *partial = (float *)((char *)workspace + qg_round_up((size_t)M * K * 2, QG_SECTION_ALIGN));
-    const size_t count4 = (size_t)M * K / 4;
-    hipLaunchKernelGGL(convert_x, dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0, st,
-                       (const float4 *)X, count4, (uint2 *)Xb);
-    A.Xb = Xb;
+    float *partial = (float *)workspace;
+    A.X = X;
     A.out = splits > 1 ? partial : Y;
     A.M = M;
     A.N = (int)N;
