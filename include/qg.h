@@ -67,8 +67,8 @@ const char *qg_status_string(int status);
 size_t qg_packed_bytes(int64_t N, int64_t K, int bits, int group, int layout);
 
 /* Size in bytes of the scratch buffer qg_gemv (M = 1) or qg_gemm_small (M > 1) needs for
- * this problem (meeting slots of the K-split reduction; partial results and the bf16 copy
- * of X for the GEMM).  For a grouped launch, the sum over its problems.  0 if the shape is
+ * this problem (meeting slots of the K-split reduction for the GEMV; partial results of the
+ * K split for the GEMM).  For a grouped launch, the sum over its problems.  0 if the shape is
  * not accepted.
  * The buffer must be prepared once before its first use with qg_workspace_init (it fills it
  * with the "empty slot" pattern); every qg_gemv call leaves it prepared again.  A buffer
@@ -134,6 +134,11 @@ int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
  * built-in choice.  waves_per_block in 1..16 = most wavefronts that share one tile of 64
  * outputs inside a workgroup; bytes_per_wave = packed code bytes one wavefront streams. */
 int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave);
+/* Same for qg_gemm_small: splits in 1..8 = number of K ranges handled by different
+ * workgroups (clamped to what the shape allows); shape in 1..7 = workgroup shape (how many
+ * tiles and K slices the wavefronts of a workgroup cover; ignored if it does not fit M).
+ * 0 restores the built-in choice. */
+int qg_set_gemm_tuning(int splits, int shape);
 
 #ifdef __cplusplus
 }

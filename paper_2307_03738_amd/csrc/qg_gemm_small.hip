@@ -4,19 +4,28 @@
 // eq. (1)) applied to M activation rows at once.  X and the dequantized weights are rounded
 // to bf16, products are accumulated in fp32 by v_mfma_f32_32x32x16_bf16.
 //
-// Mapping (4-bit codes, groups of a multiple of 32).  A wavefront owns one tile of 64
-// outputs -- the same device layout the GEMV reads, lane l holding 32 consecutive k of output
-// 64*tile + l in one 128-bit vector -- and all M rows.  The matrix instruction wants, for a
-// block of 32 outputs, lanes l and l+32 to hold the SAME output with two different k-octets;
-// the layout has them hold two different outputs with the same k.  One v_permlane32_swap of
-// the raw code words (w0 with w2, w1 with w3) turns one into the other for both 32-output
-// blocks at once, so weights go from HBM to the MFMA operand through registers only:
-// mask, convert, one FMA with the group's (s, -z s), pack to bf16.  Every weight is
-// dequantized exactly once.  The activation rows are converted to bf16 on their way into
-// LDS, chunk by chunk (128 k), double-buffered, shared by the four wavefronts
-// of a workgroup, which work on four neighbouring tiles over the same k range.  K may be
-// cut into `splits` ranges handled by different workgroups; their fp32 partial results are
-// added by a second small kernel in a fixed order.
+// Mapping (4-bit codes, groups of 32, 64, 128 or a multiple of 128).  A wavefront owns one
+// tile of 64 outputs -- the same device layout the GEMV reads, lane l holding 32 consecutive
+// k of output 64*tile + l in one 128-bit vector -- and all M rows.  The matrix instruction
+// wants, for a block of 32 outputs, lanes l and l+32 to hold the SAME output with two
+// different k-octets; the layout has them hold two different outputs with the same k.  One
+// v_permlane32_swap of the raw code words (w0 with w2, w1 with w3) turns one into the other
+// for both 32-output blocks at once, so weights go from HBM to the MFMA operand through
+// registers only: mask, convert, one FMA with the group's (s, -z s), pack to bf16.  Every
+// weight is dequantized exactly once.
+//
+// A wavefront holds at most 64 activation rows (64 accumulator registers); more rows run as
+// two row blocks on the grid's z axis.  A workgroup is four wavefronts laid out as TN tiles x
+// KW k-slices (TN * KW = 4): four neighbouring tiles over the same k (KW = 1) when the launch
+// has enough workgroups anyway, otherwise two or four consecutive k-steps of fewer tiles
+// (KW = 2, 4), whose accumulators are added through LDS at the end -- more wavefronts for
+// small problems without more partial results.  The activation rows are converted to bf16
+// on their way into LDS, KW * 128 k at a time, double-buffered, shared by the workgroup; the
+// loads of the next chunk are issued a quarter at a time between the units of the running
+// step, because the path from L2 into a compute unit is what the activations load most.
+// Codes, scales and zero-points of the next step are in flight while the current one is
+// computed.  K may also be cut into `splits` ranges handled by different workgroups; their
+// fp32 partial results are added by a second small kernel in a fixed order.
 //
 // Other bit widths and group sizes take the fp32 GEMV kernel once per activation row.
 #include "qg_common.h"
@@ -30,9 +39,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int KC = 128;            // k per chunk = one step of the 4-bit layout
-constexpr int XPITCH = KC + 8;     // bf16 per LDS row: 272 bytes, conflict-free 128-bit reads
-constexpr int GEMM_WAVES = 4;
+constexpr int KC = 128;            // k per step of the 4-bit layout
 
 struct GemmArgs {
     const uint4 *codes;
@@ -40,8 +47,10 @@ struct GemmArgs {
     const uint32_t *zeros;
     const float *X;            // activations [M][K] fp32
     float *out;                // Y, or partial results [split][M][N]
-    int M, N, K, tiles, steps, ngroups, zwords, group;
-    int steps_per_split;
+    int M, N, K, tiles, steps, ngroups, zwords;
+    int group_shift;           // log2(G) for G <= 128
+    int steps_per_group;       // G / 128 for G > 128, else 1
+    int steps_per_split;       // a multiple of KW and of steps_per_group
 };
 
 __device__ inline uint32_t opaque(uint32_t v)
@@ -83,27 +92,46 @@ __device__ inline void swap_halves(uint32_t a, uint32_t b, uint32_t &low, uint32
     high = r[1];
 }
 
-template <int MB>
-__global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_small_b4(const GemmArgs A)
+// What one wavefront needs for one step (128 k of its tile): four code vectors, the scale of
+// each 32-k unit and the word holding the zero-points of the step's groups.
+struct StepRegs {
+    uint4 v[4];
+    float s[4];
+    uint32_t zw;
+};
+
+template <int MB, int TN, int KW>
+__global__ __launch_bounds__(TN * KW * 64) void gemm_small_b4(const GemmArgs A)
 {
-    // two activation buffers: the chunk of the next step is written while this one is read
-    __shared__ __attribute__((aligned(16))) __bf16 Xs[2][MB * 32 * XPITCH];
-    constexpr int XLOADS = MB * 32 * (KC / 4) / (GEMM_WAVES * 64);   // float4 loads per thread and chunk
+    constexpr int GEMM_THREADS = TN * KW * 64; // TN tiles x KW k-slices, one wavefront each
+    constexpr int ROWS = MB * 32;              // activation rows held (rows past M are zero)
+    constexpr int XK = KW * KC;                // k per workgroup iteration
+    constexpr int XPITCH = XK + 8;             // bf16 per LDS row: conflict-free 128-bit reads
+    constexpr int XLOADS = ROWS * (XK / 4) / GEMM_THREADS;   // float4 loads per thread and chunk
+    constexpr int ACC = MB * 2 * 16;           // accumulator registers per lane
+    // two activation buffers: the chunk of the next iteration is written while this one is
+    // read; reused at the end for the accumulators of the k-slices 1 .. KW-1
+    constexpr int XBYTES = 2 * ROWS * XPITCH * 2;
+    constexpr int RBYTES = (KW - 1) * TN * ACC * 64 * 4;
+    __shared__ __attribute__((aligned(16))) char smem[XBYTES > RBYTES ? XBYTES : RBYTES];
+    __bf16 *Xs = (__bf16 *)smem;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int tile = blockIdx.x * GEMM_WAVES + wave;
+    const int tn = wave % TN, kw = wave / TN;
+    const int tile = blockIdx.x * TN + tn;
     const bool have_tile = tile < A.tiles;
+    const int m0 = blockIdx.z * ROWS;                       // first activation row of this workgroup
+    const int rows = A.M - m0 < ROWS ? A.M - m0 : ROWS;      // real rows among the ROWS held
     const int st0 = blockIdx.y * A.steps_per_split;
     int st1 = st0 + A.steps_per_split;
     if (st1 > A.steps) st1 = A.steps;
+    const int iters = (st1 - st0 + KW - 1) / KW;
 
     const int tclamp = have_tile ? tile : A.tiles - 1;
     const uint4 *codes = A.codes + (size_t)tclamp * A.steps * 4 * QG_WAVE + lane;
     const float *sc = A.scales + (size_t)tclamp * A.ngroups * QG_WAVE + lane;
     const uint32_t *zr = A.zeros + (size_t)tclamp * A.zwords * QG_WAVE + lane;
-    const int groups_per_step = KC / A.group > 0 ? KC / A.group : 1;   // G = 32, 64, 128 -> 4, 2, 1
-    const int steps_per_group = A.group / KC > 0 ? A.group / KC : 1;    // G = 256, ... -> 2, ...
 
     floatx16 acc[MB][2];
 #pragma unroll
@@ -116,90 +144,171 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_small_b4(const GemmArgs 
     const int half = lane >> 5;           // which k-octet pair this lane feeds
     const int row = lane & 31;
 
-    // this thread's share of an activation chunk: XLOADS pieces of 4 consecutive k, converted
-    // to bf16 (round to nearest even) on the way into LDS; rows past M are zero
-    float4 xr[XLOADS];
-    auto load_x = [&](int step) {
+    // group of unit u (32 k) of a step: G <= 128 has 128/G groups per step, G > 128 has
+    // G/128 steps per group (then group_shift is 7 and the unit term vanishes)
+    const int step_shift = 7 - A.group_shift;
+    auto first_group = [&](int step) { return (step / A.steps_per_group) << step_shift; };
+    auto unit_group = [&](int g0, int u) { return g0 + ((u * 32) >> A.group_shift); };
+    auto fetch = [&](int step, StepRegs &r) {
 #pragma unroll
-        for (int j = 0; j < XLOADS; ++j) {
-            const int i = j * GEMM_WAVES * 64 + threadIdx.x;
-            const int m = i / (KC / 4), c4 = i % (KC / 4);
-            xr[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (m < A.M) xr[j] = *(const float4 *)(A.X + (size_t)m * A.K + (size_t)step * KC + c4 * 4);
+        for (int u = 0; u < 4; ++u) r.v[u] = codes[((size_t)step * 4 + u) * QG_WAVE];
+        const int g0 = first_group(step);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) r.s[u] = sc[(size_t)unit_group(g0, u) * QG_WAVE];
+        r.zw = zr[(size_t)(g0 >> 3) * QG_WAVE];      // a step's groups share one zero word
+    };
+
+    // this thread's share of an activation chunk: XLOADS pieces of 4 consecutive k, RPP rows
+    // apart, converted to bf16 (round to nearest even) on the way into LDS.  Pieces with no
+    // real row are skipped (their LDS rows keep whatever they held), other rows past M repeat
+    // the last real row, and k past K repeats the last piece: a row of the A operand only
+    // reaches the same row of the result, and rows past M are never stored; k past K belongs
+    // to steps no wavefront runs.  Offsets are rebuilt at every use (two operations per piece) rather
+    // than kept in registers across the loop.
+    constexpr int RPP = GEMM_THREADS / (XK / 4);
+    constexpr int XPART = XLOADS / 4;          // pieces issued per 32-k unit of the running step
+    const int xrow = threadIdx.x / (XK / 4), xcol = (threadIdx.x % (XK / 4)) * 4;
+    float4 xr[XLOADS];
+    auto load_x_part = [&](int k0, int part) {
+        const float *base = A.X + (size_t)m0 * A.K + k0;     // uniform
+        const uint32_t r = opaque((uint32_t)xrow);
+        const uint32_t last = (uint32_t)(A.K - 4 - k0);
+        const uint32_t col = (uint32_t)xcol < last ? (uint32_t)xcol : last;
+#pragma unroll
+        for (int j = part * XPART; j < (part + 1) * XPART; ++j) {
+            if (j * RPP >= rows) continue;                   // uniform: no real row in this piece
+            uint32_t m = r + j * RPP;
+            m = m < (uint32_t)rows ? m : (uint32_t)(rows - 1);
+            xr[j] = *(const float4 *)(base + (m * (uint32_t)A.K + col));
         }
     };
     auto store_x = [&](int buf) {
+        __bf16 *dst = Xs + (size_t)(buf * ROWS + xrow) * XPITCH + xcol;
 #pragma unroll
         for (int j = 0; j < XLOADS; ++j) {
-            const int i = j * GEMM_WAVES * 64 + threadIdx.x;
-            const int m = i / (KC / 4), c4 = i % (KC / 4);
+            if (j * RPP >= rows) continue;
             floatx2 a = {xr[j].x, xr[j].y}, b = {xr[j].z, xr[j].w};
             bf16x2 pa = __builtin_convertvector(a, bf16x2), pb = __builtin_convertvector(b, bf16x2);
             uint2 packed;
             packed.x = *(uint32_t *)&pa;
             packed.y = *(uint32_t *)&pb;
-            *(uint2 *)(&Xs[buf][m * XPITCH + c4 * 4]) = packed;
+            *(uint2 *)(dst + j * RPP * XPITCH) = packed;
         }
     };
 
-    uint4 v[4], vn[4];
-    if (st0 < st1) {
+    // One step of this wavefront: dequantize 64 outputs x 128 k, multiply with all rows.  The
+    // A operands of unit u + 1 are read from LDS while unit u is multiplied; with `xk0` >= 0 a
+    // quarter of the next activation chunk is requested at the start of every unit, so the
+    // memory pipeline works alongside the arithmetic instead of ahead of it.
+    auto compute = [&](const StepRegs &r, int step, int buf, int xk0) {
+        const int g0 = first_group(step);
+        const __bf16 *xs = Xs + (size_t)buf * ROWS * XPITCH + kw * KC + row * XPITCH + half * 16;
+        bf16x8 a0[MB], a1[MB], n0[MB], n1[MB];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = codes[((size_t)st0 * 4 + u) * QG_WAVE];
-        load_x(st0);
+        for (int mb = 0; mb < MB; ++mb) {
+            a0[mb] = *(const bf16x8 *)(xs + mb * 32 * XPITCH);          // octet 0 or 2
+            a1[mb] = *(const bf16x8 *)(xs + mb * 32 * XPITCH + 8);      // octet 1 or 3
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (xk0 >= 0) load_x_part(xk0, u);
+            if (u < 3) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    n0[mb] = *(const bf16x8 *)(xs + mb * 32 * XPITCH + (u + 1) * 32);
+                    n1[mb] = *(const bf16x8 *)(xs + mb * 32 * XPITCH + (u + 1) * 32 + 8);
+                }
+            }
+            const float s = r.s[u];
+            const int g = unit_group(g0, u);
+            const float nzs = -(float)((r.zw >> (4 * (g & 7))) & 15u) * s;
+            // outputs 0-31 of the tile in both halves (P), outputs 32-63 in both halves (Q)
+            uint32_t sP, sQ, nP, nQ, P0, Q0, P1, Q1;
+            swap_halves(__float_as_uint(s), __float_as_uint(s), sP, sQ);
+            swap_halves(__float_as_uint(nzs), __float_as_uint(nzs), nP, nQ);
+            swap_halves(r.v[u].x, r.v[u].z, P0, Q0);   // k-octets 0 (low lanes) and 2 (high lanes)
+            swap_halves(r.v[u].y, r.v[u].w, P1, Q1);   // k-octets 1 and 3
+            const bf16x8 bP0 = dequant_word(P0, __uint_as_float(sP), __uint_as_float(nP));
+            const bf16x8 bQ0 = dequant_word(Q0, __uint_as_float(sQ), __uint_as_float(nQ));
+            const bf16x8 bP1 = dequant_word(P1, __uint_as_float(sP), __uint_as_float(nP));
+            const bf16x8 bQ1 = dequant_word(Q1, __uint_as_float(sQ), __uint_as_float(nQ));
+            // consecutive matrix instructions write different accumulators
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                acc[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mb], bP0, acc[mb][0], 0, 0, 0);
+                acc[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mb], bQ0, acc[mb][1], 0, 0, 0);
+            }
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                acc[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[mb], bP1, acc[mb][0], 0, 0, 0);
+                acc[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[mb], bQ1, acc[mb][1], 0, 0, 0);
+            }
+            if (u < 3) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    a0[mb] = n0[mb];
+                    a1[mb] = n1[mb];
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);     // units stay in order
+        }
+    };
+    // Every iteration but the last has all KW steps inside the split, so the loop body is
+    // straight-line code: issue the loads of iteration it + 1, compute iteration it from
+    // registers and LDS filled one iteration earlier, then move the new data into place.
+    StepRegs cur, nxt;
+    if (iters > 0) {
+        const int step = st0 + kw;
+        fetch(step < st1 ? step : st1 - 1, cur);
+#pragma unroll
+        for (int part = 0; part < 4; ++part) load_x_part(st0 * KC, part);
         store_x(0);
     }
     __syncthreads();
-
     int buf = 0;
-    for (int step = st0; step < st1; ++step) {
-        const bool more = step + 1 < st1;
-        if (more) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) vn[u] = codes[((size_t)(step + 1) * 4 + u) * QG_WAVE];
-            load_x(step + 1);
-        }
-        // scale and zero of the step's groups (G is a multiple of 32)
-        float s_u[4], nzs_u[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int g = steps_per_group > 1 ? step / steps_per_group
-                                              : step * groups_per_step + (u * 32) / A.group;
-            s_u[u] = sc[(size_t)g * QG_WAVE];
-            const uint32_t zword = zr[(size_t)(g / 8) * QG_WAVE];
-            nzs_u[u] = -(float)((zword >> (4 * (g % 8))) & 15u) * s_u[u];
-        }
-        const __bf16 *xs = Xs[buf];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            // outputs 0-31 of the tile in both halves (P), outputs 32-63 in both halves (Q)
-            uint32_t sP, sQ, nP, nQ, P0, Q0, P1, Q1;
-            swap_halves(__float_as_uint(s_u[u]), __float_as_uint(s_u[u]), sP, sQ);
-            swap_halves(__float_as_uint(nzs_u[u]), __float_as_uint(nzs_u[u]), nP, nQ);
-            swap_halves(v[u].x, v[u].z, P0, Q0);       // k-octets 0 (low lanes) and 2 (high lanes)
-            swap_halves(v[u].y, v[u].w, P1, Q1);       // k-octets 1 and 3
-            const bf16x8 bP0 = dequant_word(P0, __uint_as_float(sP), __uint_as_float(nP));
-            const bf16x8 bP1 = dequant_word(P1, __uint_as_float(sP), __uint_as_float(nP));
-            const bf16x8 bQ0 = dequant_word(Q0, __uint_as_float(sQ), __uint_as_float(nQ));
-            const bf16x8 bQ1 = dequant_word(Q1, __uint_as_float(sQ), __uint_as_float(nQ));
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                const __bf16 *xp = xs + (mb * 32 + row) * XPITCH + u * 32 + half * 16;
-                const bf16x8 a0 = *(const bf16x8 *)(xp);          // octet 0 or 2
-                const bf16x8 a1 = *(const bf16x8 *)(xp + 8);      // octet 1 or 3
-                acc[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bP0, acc[mb][0], 0, 0, 0);
-                acc[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bP1, acc[mb][0], 0, 0, 0);
-                acc[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bQ0, acc[mb][1], 0, 0, 0);
-                acc[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bQ1, acc[mb][1], 0, 0, 0);
-            }
-        }
-        if (more) {
-            store_x(buf ^ 1);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = vn[u];
-        }
+    for (int it = 0; it + 1 < iters; ++it) {
+        const int step = st0 + it * KW + kw;
+        const int ns = step + KW;
+        fetch(ns < st1 ? ns : st1 - 1, nxt);
+        __builtin_amdgcn_sched_barrier(0);     // weight loads first ...
+        compute(cur, step, buf, (st0 + (it + 1) * KW) * KC);
+        __builtin_amdgcn_sched_barrier(0);     // ... and nothing that waits for them before the arithmetic is done
+        store_x(buf ^ 1);
+        cur = nxt;
         __syncthreads();      // next chunk written, this chunk's readers done
         buf ^= 1;
+    }
+    if (iters > 0) {
+        const int step = st0 + (iters - 1) * KW + kw;
+        if (step < st1) compute(cur, step, buf, -1);
+    }
+
+    if constexpr (KW > 1) {
+        // k-slices 1 .. KW-1 hand their accumulators to slice 0 of the same tile, which adds
+        // them in slice order; the buffers of X are reused once every reader is done
+        float *red = (float *)smem;
+        __syncthreads();
+        if (kw > 0) {
+            float *dst = red + ((size_t)((kw - 1) * TN + tn) * ACC) * 64 + lane;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) dst[((mb * 2 + nb) * 16 + i) * 64] = acc[mb][nb][i];
+        }
+        __syncthreads();
+        if (kw > 0) return;
+#pragma unroll
+        for (int k = 1; k < KW; ++k) {
+            const float *src = red + ((size_t)((k - 1) * TN + tn) * ACC) * 64 + lane;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[mb][nb][i] += src[((mb * 2 + nb) * 16 + i) * 64];
+        }
     }
 
     if (!have_tile) return;
@@ -211,7 +320,7 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_small_b4(const GemmArgs 
             const int n = tile * QG_WAVE + nb * 32 + row;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int m = mb * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+                const int m = m0 + mb * 32 + 8 * (i / 4) + 4 * half + (i % 4);
                 if (m < A.M && n < A.N) out[(size_t)m * A.N + n] = acc[mb][nb][i];
             }
         }
@@ -229,20 +338,61 @@ __global__ void add_splits(const float *__restrict__ partial, int splits, size_t
 
 bool fast_path(const QgLayout &L)
 {
-    return L.bits == 4 && L.group % 32 == 0 && L.K % KC == 0 &&
+    return L.bits == 4 && L.group % 32 == 0 && L.K % KC == 0 && L.K <= (1 << 20) &&
            (L.group <= KC ? KC % L.group == 0 : L.group % KC == 0);
 }
 
-int max_splits(int M) { return M <= 32 ? 8 : 4; }
+constexpr int MAX_SPLITS = 8;
+int g_tune_splits = 0;      // measurement knobs: 0 = built-in choice
+int g_tune_shape = 0;       // 1 + index into SHAPES
+
+int gcd(int a, int b) { return b == 0 ? a : gcd(b, a % b); }
+
+template <int MB, int TN, int KW>
+void launch(const GemmArgs &A, dim3 grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((gemm_small_b4<MB, TN, KW>), grid, dim3(TN * KW * 64), 0, st, A);
+}
+
+// Workgroup shapes: {rows / 32, tiles, k-slices}
+struct Shape {
+    int mb, tn, kw;
+};
+constexpr Shape SHAPES[] = {
+    {1, 1, 4}, {1, 2, 4}, {1, 4, 2},                 // up to 32 rows
+    {2, 2, 2}, {2, 4, 1}, {2, 4, 2}, {2, 8, 1},      // blocks of 64 rows
+};
+constexpr int NSHAPES = sizeof(SHAPES) / sizeof(SHAPES[0]);
+
+void launch_shape(int i, const GemmArgs &A, dim3 grid, hipStream_t st)
+{
+    switch (i) {
+    case 0: launch<1, 1, 4>(A, grid, st); break;
+    case 1: launch<1, 2, 4>(A, grid, st); break;
+    case 2: launch<1, 4, 2>(A, grid, st); break;
+    case 3: launch<2, 2, 2>(A, grid, st); break;
+    case 4: launch<2, 4, 1>(A, grid, st); break;
+    case 5: launch<2, 4, 2>(A, grid, st); break;
+    default: launch<2, 8, 1>(A, grid, st); break;
+    }
+}
 
 }  // namespace
 
 size_t qg_gemm_workspace_bytes(const QgLayout &L, int M)
 {
     // partial results of the K split, or the GEMV workspace for the row-by-row path
-    const size_t partial = (size_t)max_splits(M) * M * L.N * sizeof(float);
+    const size_t partial = (size_t)MAX_SPLITS * M * L.N * sizeof(float);
     const size_t gemv = (size_t)L.tiles * QG_MAX_CHUNKS * QG_WAVE * sizeof(uint32_t);
     return qg_round_up(fast_path(L) ? partial : gemv, QG_SECTION_ALIGN);
+}
+
+extern "C" int qg_set_gemm_tuning(int splits, int shape)
+{
+    if (splits < 0 || splits > MAX_SPLITS || shape < 0 || shape > NSHAPES) return QG_ERR_SHAPE;
+    g_tune_splits = splits;
+    g_tune_shape = shape;
+    return QG_OK;
 }
 
 extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
@@ -270,15 +420,25 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
         return QG_OK;
     }
 
-    // enough wavefronts for about one per SIMD, within the workspace's split budget
-    int splits = (int)((1024 + L.tiles - 1) / L.tiles);
-    if (splits > max_splits(M)) splits = max_splits(M);
-    if (splits > L.steps) splits = (int)L.steps;
-    int sps = (int)((L.steps + splits - 1) / splits);
-    if (L.group > KC) {                                   // keep whole groups inside a split
-        const int q = L.group / KC;
-        sps = (sps + q - 1) / q * q;
-    }
+    // Workgroup shape.  Up to 32 rows: one block of rows, two tiles x four k-slices.  More:
+    // blocks of 64 rows on the grid's z axis (two blocks double the wavefronts of a launch at
+    // the price of dequantizing twice, which pays as long as the launch cannot fill the chip),
+    // four tiles x two k-slices.  Eight wavefronts per workgroup: one workgroup per compute unit.
+    int shape = M <= 32 ? 1 : 5;
+    if (g_tune_shape && (SHAPES[g_tune_shape - 1].mb == 1) == (M <= 32)) shape = g_tune_shape - 1;
+    const int rows_per_block = SHAPES[shape].mb * 32;
+    const int zblocks = (M + rows_per_block - 1) / rows_per_block;
+    const int kw = SHAPES[shape].kw, tn = SHAPES[shape].tn;
+    const int blocks_x = (int)((L.tiles + tn - 1) / tn);
+    const int steps_per_group = group > KC ? group / KC : 1;
+    // a split is a whole number of workgroup iterations and of groups
+    const int quantum = kw / gcd(kw, steps_per_group) * steps_per_group;
+    const int quanta = (int)((L.steps + quantum - 1) / quantum);
+    // about one workgroup per compute unit, each with at least one quantum of work
+    int splits = g_tune_splits ? g_tune_splits : (256 + blocks_x * zblocks - 1) / (blocks_x * zblocks);
+    if (splits > MAX_SPLITS) splits = MAX_SPLITS;
+    if (splits > quanta) splits = quanta;
+    const int sps = (quanta + splits - 1) / splits * quantum;
     splits = (int)((L.steps + sps - 1) / sps);
 
     GemmArgs A;
@@ -296,13 +456,11 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     A.steps = (int)L.steps;
     A.ngroups = (int)L.ngroups;
     A.zwords = (int)L.zwords;
-    A.group = group;
+    A.group_shift = group == 32 ? 5 : group == 64 ? 6 : 7;
+    A.steps_per_group = steps_per_group;
     A.steps_per_split = sps;
-    const dim3 grid((unsigned)((L.tiles + GEMM_WAVES - 1) / GEMM_WAVES), (unsigned)splits);
-    const dim3 block(GEMM_WAVES * 64);
-    if (M <= 32) hipLaunchKernelGGL(gemm_small_b4<1>, grid, block, 0, st, A);
-    else if (M <= 64) hipLaunchKernelGGL(gemm_small_b4<2>, grid, block, 0, st, A);
-    else hipLaunchKernelGGL(gemm_small_b4<4>, grid, block, 0, st, A);
+    const dim3 grid((unsigned)blocks_x, (unsigned)splits, (unsigned)zblocks);
+    launch_shape(shape, A, grid, st);
     if (qg_launch_status() != QG_OK) return QG_ERR_DEVICE;
     if (splits > 1) {
         const size_t count = (size_t)M * N;

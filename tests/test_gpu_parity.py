@@ -280,6 +280,12 @@ GEMM_CASES = [  # N, K, bits, group, M
     (300, 1024, 4, 256, 64),
     (128, 2048, 4, 2048, 128),   # one group per output
     (64, 128, 4, 128, 1),
+    (200, 640, 4, 128, 16),      # 5 steps: ragged last iteration of four k-slices
+    (330, 1152, 4, 384, 20),     # group of three steps against four k-slices
+    (190, 1408, 4, 64, 40),      # 11 steps against two k-slices, odd number of tiles
+    (190, 1408, 4, 128, 128),
+    (200, 1024, 4, 128, 65),     # second block of rows holds a single row
+    (1100, 256, 4, 128, 72),     # enough tiles for the four-tile workgroup shape
     (130, 512, 3, 64, 7),        # other widths: fp32 row-by-row path
     (96, 512, 2, 32, 4),
     (90, 480, 4, 24, 3),
@@ -307,6 +313,36 @@ def test_gemm_small_rows_agree_with_gemv(qg, oracle):
     for m in (0, 7, 15):
         y = host(qg.qg_gemv(blob, N, K, bits, group, dev(X[m])))
         assert scaled_error(Y[m], y.astype(np.float64), norms, X[m]) <= TOL_BF16
+
+
+@pytest.mark.parametrize("splits", [1, 2, 3, 8])
+@pytest.mark.parametrize("M", [8, 48, 96])
+def test_gemm_small_every_split_count(qg, oracle, splits, M):
+    _announce("gemm_small splits", splits, M)
+    N, K, bits, group = 200, 2304, 4, 128          # 18 steps
+    W, X = synth.small_case(500 + M, N, K, 0.02, True, m=M)
+    qg.qg_set_gemm_tuning(splits, 0)
+    try:
+        err = _gemm_case(qg, oracle, W, X, bits, group)
+    finally:
+        qg.qg_set_gemm_tuning(0, 0)
+    assert err <= TOL_BF16, err
+
+
+@pytest.mark.parametrize("shape", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("N,K,group", [(610, 1408, 64), (130, 1152, 384)])
+def test_gemm_small_every_workgroup_shape(qg, oracle, shape, N, K, group):
+    # shapes 1-3 hold up to 32 rows, 4-7 blocks of 64 rows; ragged tiles, steps and rows
+    M = 23 if shape <= 3 else 77
+    _announce("gemm_small shape", shape, N, K, group, M)
+    W, X = synth.small_case(900 + shape, N, K, 0.02, True, m=M)
+    for splits in (0, 2):
+        qg.qg_set_gemm_tuning(splits, shape)
+        try:
+            err = _gemm_case(qg, oracle, W, X, 4, group)
+        finally:
+            qg.qg_set_gemm_tuning(0, 0)
+        assert err <= TOL_BF16, (splits, err)
 
 
 @pytest.mark.parametrize("index", [0, 1, 2])
