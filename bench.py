@@ -80,12 +80,66 @@ def cpu_baseline(cfg, problems, passes=5):
             "sample": f"full {cfg.name} layer set from the canonical packed format, median of {passes} passes"}
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X public dense bf16 peak
+
+
+def bench_gemm(cfg, qg, args):
+    """Prompt-phase form (configuration 5): every (shape, M) problem timed on its own, packed
+    copies rotated like the GEMV's.  A step is one pass over the nine problems."""
+    from paper_2307_03738_amd import synth
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    stream_steps, warm = max(1, args.steps // 10), max(1, args.warmup // 10)
+    rows, total_us = [], 0.0
+    for idx, (N, K) in enumerate(cfg.shapes):
+        W, acts = synth.matrix(cfg, idx)
+        q, s, z = qg.qg_quantize(torch.from_numpy(W).cuda(), cfg.bits, cfg.group)
+        blob = qg.qg_pack(q, s, z, cfg.bits, cfg.group)
+        del q, s, z
+        copies = max(2, int(np.ceil(ROTATE_BYTES / blob.numel())))
+        blobs = [blob] + [blob.clone() for _ in range(copies - 1)]
+        for M, X in zip(cfg.batch, acts):
+            Xd = torch.from_numpy(X).cuda()
+            Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+            ws = qg.new_workspace(qg.qg_workspace_bytes(N, K, cfg.bits, cfg.group, M))
+            for i in range(warm):
+                qg.qg_gemm_small(blobs[i % copies], N, K, cfg.bits, cfg.group, Xd, Y, ws)
+            torch.cuda.synchronize()
+            start.record()
+            for i in range(stream_steps):
+                qg.qg_gemm_small(blobs[i % copies], N, K, cfg.bits, cfg.group, Xd, Y, ws)
+            stop.record()
+            torch.cuda.synchronize()
+            us = start.elapsed_time(stop) / stream_steps * 1e3
+            flops = 2.0 * M * N * K
+            byts = (cfg.bits * N * K + (32 + cfg.bits) * N * (K // cfg.group)) // 8 + 4 * M * K + 4 * M * N
+            rows.append({"N": N, "K": K, "M": M, "us": round(us, 2),
+                         "TFLOPs": round(flops / us / 1e6, 1),
+                         "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
+                         "GBps": round(byts / us / 1e3, 1),
+                         "frac_of_hbm_peak": round(byts / us / 1e3 / HBM_PEAK_GBS, 4)})
+            total_us += us
+        del blobs, blob
+    top = max(rows, key=lambda r: r["TFLOPs"])
+    return {
+        "metric": "us per pass over the small-M GEMM problems (3 LLaMA-7B shapes x M = 16, 64, 128), 4-bit g128",
+        "value": round(total_us, 2), "unit": "us", "n_gpus": 1, "steps": stream_steps, "warmup": warm,
+        "ms_per_step": round(total_us / 1e3, 6), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: Y = X What^T, shapes {list(cfg.shapes)}, M in {list(cfg.batch)}, "
+                               f"{cfg.bits}-bit, group {cfg.group}, bf16 MFMA with fp32 accumulation"},
+        "problems": rows,
+        "roofline": {"bound": "mfma", "achieved": top["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": top["frac_of_bf16_mfma_peak"], "traffic": None,
+                     "problem": {k: top[k] for k in ("N", "K", "M")}},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--config", default="C2", choices=["C2", "C3", "C4"])
+    ap.add_argument("--config", default="C2", choices=["C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of 256 MiB (reference for HBM byte counters)")
@@ -100,6 +154,9 @@ def main():
     from paper_2307_03738_amd import binding as qg, synth
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
+    if args.config == "C5":
+        print(json.dumps(bench_gemm(cfg, qg, args)))
+        return
     qg.qg_set_gemv_tuning(args.wpb, args.bytes_per_wave)
 
     base = prepare_set(cfg, qg)
