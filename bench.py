@@ -134,6 +134,61 @@ def bench_gemm(cfg, qg, args):
     }
 
 
+def bench_sweep(qg, args):
+    """Group size x bit width on the three LLaMA-shaped layer sets (timing only; weights are
+    seeded Gaussian noise drawn on the GPU, since the kernels have no data-dependent control
+    flow).  Group 0 stands for one group per output (G = K, the full-column form of eq. (1))."""
+    from paper_2307_03738_amd import synth
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    stream = torch.cuda.current_stream().cuda_stream
+    steps, warm = max(1, args.steps // 10), max(1, args.warmup // 10)
+    rows = []
+    for name in ("C2", "C3", "C4"):
+        shapes = synth.CONFIGS[name].shapes
+        gen = torch.Generator(device="cuda").manual_seed(100 + synth.CONFIGS[name].seed)
+        Ws = {}
+        for n, k in set(shapes):
+            Ws[(n, k)] = torch.randn((n, k), device="cuda", generator=gen) * 0.02
+        xs = {k: torch.randn((k,), device="cuda", generator=gen) for k in {k for _, k in shapes}}
+        for bits in (4, 3, 2):
+            for group in args.sweep_groups:
+                if group and group % qg.qg_cell(bits):
+                    continue
+                packed = {}
+                for (n, k), W in Ws.items():
+                    g = group or k
+                    q, s, z = qg.qg_quantize(W, bits, g)
+                    packed[(n, k)] = qg.qg_pack(q, s, z, bits, g)
+                    del q, s, z
+                set_bytes = sum(packed[s_].numel() for s_ in shapes)
+                copies = max(2, int(np.ceil(ROTATE_BYTES / set_bytes)))
+                launches = []
+                for c in range(copies):
+                    probs = [dict(packed=(packed[(n, k)] if c == 0 else packed[(n, k)].clone()), N=n, K=k,
+                                  bits=bits, group=group or k, x=xs[k],
+                                  y=torch.empty(n, dtype=torch.float32, device="cuda")) for n, k in shapes]
+                    launches.append(qg.GroupedGemv(probs))
+                for i in range(warm):
+                    launches[i % copies].launch(stream)
+                torch.cuda.synchronize()
+                start.record()
+                for i in range(steps):
+                    launches[i % copies].launch(stream)
+                stop.record()
+                torch.cuda.synchronize()
+                us = start.elapsed_time(stop) / steps * 1e3
+                alg = sum((bits * n * k + (32 + bits) * n * (k // (group or k))) // 8 + 4 * k + 4 * n for n, k in shapes)
+                rows.append({"shapes": name, "bits": bits, "group": group or "K", "us": round(us, 2),
+                             "GBps": round(alg / us / 1e3, 1), "frac_of_hbm_peak": round(alg / us / 1e3 / HBM_PEAK_GBS, 4)})
+                print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
+                del launches, packed
+        del Ws
+    return {"metric": "us per GEMV layer set over group size x bit width", "unit": "us", "n_gpus": 1,
+            "steps": steps, "warmup": warm, "dtype": "f32", "data": "synthetic (timing only)",
+            "config": {"workload": "layer sets with the shapes of C2, C3, C4; bits in {4,3,2}; group in {16,32,64,128,K}"},
+            "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -141,6 +196,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", default="C2", choices=["C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep-groups", type=lambda s: [int(v) for v in s.split(",")], default=[16, 32, 64, 128, 0],
+                    help="group sizes of --sweep; 0 = one group per output")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time every group size x bit width on the three layer-set shapes instead")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of 256 MiB (reference for HBM byte counters)")
     ap.add_argument("--wpb", type=int, default=0)
@@ -154,6 +213,9 @@ def main():
     from paper_2307_03738_amd import binding as qg, synth
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
+    if args.sweep:
+        print(json.dumps(bench_sweep(qg, args)))
+        return
     if args.config == "C5":
         print(json.dumps(bench_gemm(cfg, qg, args)))
         return

@@ -109,7 +109,9 @@ int qg_gemv(const void *packed, int64_t N, int64_t K, int bits, int group,
 /* Several independent products in ONE kernel launch (the seven linear layers of a decoder
  * block at batch 1 are each only microseconds of memory traffic).  `descs` is a HOST array
  * of `count` <= QG_MAX_GROUPED problems; they may differ in shape, bits and group (one
- * launch per distinct (bits, group) pair).  Workspace: the sum of qg_workspace_bytes(). */
+ * launch per distinct (bits, group) pair with groups up to one step of the kernel -- 128
+ * codes at 4 bits, 256 at 2 and 3 bits; problems with longer groups, up to one group per
+ * output, share one launch per bit width).  Workspace: the sum of qg_workspace_bytes(). */
 #define QG_MAX_GROUPED 16
 typedef struct qg_gemv_desc {
     const void *packed; /* QG_LAYOUT_DEVICE blob */

@@ -463,7 +463,10 @@ __global__ __launch_bounds__(1024) void gemv_static(const GemvArgs A)
 
 // ---------------------------------------------------------------------------------------
 // Groups that are a whole number of steps (G = 256, ..., up to one group per output: the
-// full-column case of eq. (1)).
+// full-column case of eq. (1)).  A wavefront's range of steps need not begin or end at a group
+// boundary: s (sum q x - z sum x) is linear in the two sums, so the pieces of a group that
+// different wavefronts hold are closed separately, each with the group's s and z, and add up
+// in the team's reduction.
 // ---------------------------------------------------------------------------------------
 template <int BITS>
 __global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
@@ -481,7 +484,7 @@ __global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
     const int spg = P.steps_per_group;
     const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.steps, wave);
     if (!job.work) return;                      // no work: leave before the barrier
-    const int tile = job.tile, s0 = job.item0, s1 = job.item1;   // s0 is a multiple of spg
+    const int tile = job.tile, s0 = job.item0, s1 = job.item1;
 
     TileView T;
     T.codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
@@ -490,30 +493,41 @@ __global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
     T.x = P.x;
     const float *__restrict__ x = P.x;
 
+    float yacc = 0.0f, xacc = 0.0f;
+    Acc2 acc = {0.0f, 0.0f};
+    int g = s0 / spg;                                   // running group
+    int left = (g + 1) * spg - s0;                      // its steps still to come
+    // closes the piece of group g this wavefront has seen, if step s ends the group or the range
+    auto close_group = [&](int s) {
+        if (--left != 0 && s + 1 != s1) return;
+        float xhat;
+        segment_sums<64>(xacc, &xhat);
+        const float scale = T.scales[(size_t)g * QG_WAVE];
+        const uint32_t zword = T.zeros[(size_t)(g / ZPER) * QG_WAVE];
+        const float zf = (float)((zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u));
+        yacc = fmaf(scale, fmaf(-zf, xhat, acc.a + acc.b), yacc);
+        acc.a = 0.0f;
+        acc.b = 0.0f;
+        xacc = 0.0f;
+        ++g;
+        left = spg;
+    };
+
+    // two buffers used alternately, as in gemv_static
+    const int last = s1 - 1;
     StepData<BITS, 0> da, db;
     fetch_step(da, T, s0, lane);
     XBatch xb = load_x32(x + (size_t)s0 * S);
-    float yacc = 0.0f, xacc = 0.0f;
-    Acc2 acc = {0.0f, 0.0f};
-    int in_group = 0;                                   // steps of the running group done
-    for (int s = s0; s < s1; ++s) {
-        const int sn = s + 1 < s1 ? s + 1 : s;
-        fetch_step(db, T, sn, lane);
-        compute_step(da, x + (size_t)s * S, x + (size_t)sn * S, xb, s, true, acc, xacc, yacc);
-        if (++in_group == spg) {
-            const int g = s / spg;
-            float xhat;
-            segment_sums<64>(xacc, &xhat);
-            const float scale = T.scales[(size_t)g * QG_WAVE];
-            const uint32_t zword = T.zeros[(size_t)(g / ZPER) * QG_WAVE];
-            const float zf = (float)((zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u));
-            yacc = fmaf(scale, fmaf(-zf, xhat, acc.a + acc.b), yacc);
-            acc.a = 0.0f;
-            acc.b = 0.0f;
-            xacc = 0.0f;
-            in_group = 0;
-        }
-        da = db;     // a few register moves per step; this kernel is not the hot one
+    for (int s = s0; s < s1; s += 2) {
+        const int sb = s + 1 < last ? s + 1 : last;
+        const int sc = s + 2 < last ? s + 2 : last;
+        fetch_step(db, T, sb, lane);
+        compute_step(da, x + (size_t)s * S, x + (size_t)sb * S, xb, s, true, acc, xacc, yacc);
+        close_group(s);
+        if (s + 1 >= s1) break;                       // odd number of steps
+        fetch_step(da, T, sc, lane);
+        compute_step(db, x + (size_t)sb * S, x + (size_t)sc * S, xb, sb, true, acc, xacc, yacc);
+        close_group(sb);
     }
     finish_tile(P, job, yacc, red);
 }
@@ -596,7 +610,7 @@ enum Kind { KIND_STATIC, KIND_RUNTIME, KIND_GENERIC };
 struct Plan {
     Kind kind;
     int64_t items;
-    int64_t quantum;   // spw must be a multiple of this (steps per group, runtime kernel)
+    int64_t steps_per_group;   // runtime kernel: steps one group spans
     int64_t max_spw;   // x-hat is kept one group per lane: at most 64 groups per wavefront
     size_t item_bytes; // packed code bytes one wavefront reads per item
 };
@@ -615,13 +629,13 @@ Plan make_plan(const QgLayout &L)
     }
     if (pl.kind == KIND_STATIC) {
         pl.items = L.steps;
-        pl.quantum = 1;
+        pl.steps_per_group = 1;
         pl.max_spw = 64 / (cps / cpg);
         pl.item_bytes = step_bytes;
     } else if (pl.kind == KIND_RUNTIME) {
         pl.items = L.steps;
-        pl.quantum = L.group / step_codes;
-        pl.max_spw = 64 * pl.quantum;
+        pl.steps_per_group = L.group / step_codes;
+        pl.max_spw = (int64_t)1 << 30;               // the running group is one scalar
         pl.item_bytes = step_bytes;
     }
     // a fast kernel that cannot cover K with 16 wavefronts x QG_MAX_CHUNKS blocks: generic
@@ -630,7 +644,7 @@ Plan make_plan(const QgLayout &L)
         pl.kind = KIND_GENERIC;
     if (pl.kind == KIND_GENERIC) {
         pl.items = L.ngroups;
-        pl.quantum = 1;
+        pl.steps_per_group = 1;
         pl.max_spw = (int64_t)1 << 30;
         pl.item_bytes = (size_t)L.group * L.bits / 8 * QG_WAVE;
     }
@@ -697,8 +711,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     for (int i = 0; i < count; ++i) {
         const Plan &q = pl[i];
         int64_t want = (int64_t)((target + q.item_bytes / 2) / q.item_bytes);   // items per wavefront
-        want = (want + q.quantum - 1) / q.quantum * q.quantum;
-        if (want < q.quantum) want = q.quantum;
+        if (want < 1) want = 1;
         if (want > q.max_spw) want = q.max_spw;
         // Among the ways to cover K with `chunks` (a power of two) non-empty workgroups of `team`
         // <= cap wavefronts, take the one whose items per wavefront come closest to `want`;
@@ -707,8 +720,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         int64_t best_miss = 0;
         for (int64_t chunks = 1; chunks <= QG_MAX_CHUNKS; chunks *= 2) {
             for (int64_t team = 1; team <= cap; ++team) {
-                int64_t spw = (q.items + chunks * team - 1) / (chunks * team);
-                spw = (spw + q.quantum - 1) / q.quantum * q.quantum;
+                const int64_t spw = (q.items + chunks * team - 1) / (chunks * team);
                 if (spw > q.max_spw) continue;
                 if ((chunks - 1) * team * spw >= q.items) continue;       // an empty workgroup
                 const int64_t miss = spw > want ? spw - want : want - spw;
@@ -743,7 +755,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         P.ngroups = (int)L[i].ngroups;
         P.zwords = (int)L[i].zwords;
         P.group = L[i].group;
-        P.steps_per_group = (int)pl[i].quantum;
+        P.steps_per_group = (int)pl[i].steps_per_group;
         P.steps_per_wave = (int)spw_of[i];
         P.chunks = (int)chunks_of[i];
         P.chunk_shift = 0;
@@ -831,7 +843,8 @@ extern "C" int qg_gemv_grouped(const qg_gemv_desc *descs, int count, void *works
     if (!workspace || workspace_bytes < need) return QG_ERR_WORKSPACE;
     if (!qg_aligned16(workspace)) return QG_ERR_ALIGN;
 
-    // one launch per distinct (bits, group, kernel kind)
+    // one launch per distinct (bits, kernel kind), and per group size where the kernel has it
+    // as a compile-time constant
     bool done[QG_MAX_GROUPED] = {false};
     for (int i = 0; i < count; ++i) {
         if (done[i]) continue;
@@ -842,7 +855,8 @@ extern "C" int qg_gemv_grouped(const qg_gemv_desc *descs, int count, void *works
             if (done[j]) continue;
             QgLayout Lj;
             qg_make_layout(descs[j].N, descs[j].K, descs[j].bits, descs[j].group, &Lj);
-            if (Lj.bits == Li.bits && Lj.group == Li.group && make_plan(Lj).kind == make_plan(Li).kind) {
+            const Kind ki = make_plan(Li).kind;
+            if (Lj.bits == Li.bits && make_plan(Lj).kind == ki && (ki != KIND_STATIC || Lj.group == Li.group)) {
                 idx[n++] = j;
                 done[j] = true;
             }

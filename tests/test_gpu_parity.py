@@ -157,6 +157,10 @@ GEMV_CASES = [  # N, K, bits, group   -- (kernel flavour)
     (100, 2048, 4, 2048),     # one group per output, eq. (1)
     (100, 1024, 2, 512),
     (66, 1536, 3, 768),
+    (130, 11008, 4, 11008),   # full column, K long enough to be cut over wavefronts and workgroups
+    (70, 5120, 3, 5120),
+    (70, 8192, 2, 8192),
+    (200, 2304, 4, 768),      # three groups of six steps: wavefront ranges end inside groups
     (90, 480, 4, 24),         # generic kernel: group not a power of two
     (90, 416, 4, 32),         # generic kernel: K not a whole number of steps
     (50, 288, 3, 96),
@@ -175,7 +179,7 @@ def test_gemv_matches_oracle(qg, oracle, N, K, bits, group):
 
 @pytest.mark.parametrize("tuning", [(1, 4096), (2, 4096), (4, 8192), (8, 4096), (16, 4096), (4, 65536)])
 @pytest.mark.parametrize("N,K,bits,group", [(200, 4096, 4, 128), (130, 3072, 3, 64), (130, 4096, 2, 32),
-                                            (70, 4096, 4, 1024)])
+                                            (70, 4096, 4, 1024), (70, 5632, 4, 5632), (70, 3840, 3, 1280)])
 def test_gemv_k_split_shapes(qg, oracle, N, K, bits, group, tuning):
     # the same product under different wavefront / workgroup splits of K, including the
     # path where the last-arriving workgroup adds the partial vectors
