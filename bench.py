@@ -204,6 +204,7 @@ def main():
                     help="also run one plain device copy of 256 MiB (reference for HBM byte counters)")
     ap.add_argument("--wpb", type=int, default=0)
     ap.add_argument("--bytes-per-wave", type=int, default=0)
+    ap.add_argument("--kernel", type=int, default=0, help="0 built-in choice, 1 vector-ALU GEMV, 2 matrix-core GEMV")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: the path has no multi-GPU part (run with --gpus 1)",
@@ -219,7 +220,7 @@ def main():
     if args.config == "C5":
         print(json.dumps(bench_gemm(cfg, qg, args)))
         return
-    qg.qg_set_gemv_tuning(args.wpb, args.bytes_per_wave)
+    qg.qg_set_gemv_tuning(args.wpb, args.bytes_per_wave, args.kernel)
 
     base = prepare_set(cfg, qg)
     set_bytes = sum(p["packed"].numel() for p in base)

@@ -134,8 +134,10 @@ int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
 
 /* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe).  0 restores the
  * built-in choice.  waves_per_block in 1..16 = most wavefronts that share one tile of 64
- * outputs inside a workgroup; bytes_per_wave = packed code bytes one wavefront streams. */
-int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave);
+ * outputs inside a workgroup; bytes_per_wave = packed code bytes one wavefront streams;
+ * kernel = 1: multiply-adds on the vector ALU, 2: on the matrix cores (where that kernel
+ * exists: groups of at least two cells and at most one step). */
+int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel);
 /* Same for qg_gemm_small: splits in 1..8 = number of K ranges handled by different
  * workgroups (clamped to what the shape allows); shape in 1..7 = workgroup shape (how many
  * tiles and K slices the wavefronts of a workgroup cover; ignored if it does not fit M).

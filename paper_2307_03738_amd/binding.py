@@ -57,7 +57,7 @@ def lib():
         L.qg_gemm_small.restype = i32
         L.qg_gemm_small.argtypes = [vp, i64, i64, i32, i32, vp, i32, vp, vp, sz, vp]
         L.qg_set_gemv_tuning.restype = i32
-        L.qg_set_gemv_tuning.argtypes = [i32, i32]
+        L.qg_set_gemv_tuning.argtypes = [i32, i32, i32]
         L.qg_set_gemm_tuning.restype = i32
         L.qg_set_gemm_tuning.argtypes = [i32, i32]
         _LIB = L
@@ -203,8 +203,8 @@ def qg_gemm_small(packed: torch.Tensor, N: int, K: int, bits: int, group: int, X
     return Y
 
 
-def qg_set_gemv_tuning(waves_per_block: int = 0, bytes_per_wave: int = 0):
-    _check(lib().qg_set_gemv_tuning(waves_per_block, bytes_per_wave), "qg_set_gemv_tuning")
+def qg_set_gemv_tuning(waves_per_block: int = 0, bytes_per_wave: int = 0, kernel: int = 0):
+    _check(lib().qg_set_gemv_tuning(waves_per_block, bytes_per_wave, kernel), "qg_set_gemv_tuning")
 
 
 def qg_set_gemm_tuning(splits: int = 0, shape: int = 0):

@@ -462,6 +462,272 @@ __global__ __launch_bounds__(1024) void gemv_static(const GemvArgs A)
 }
 
 // ---------------------------------------------------------------------------------------
+// The same product with the multiply-adds on the matrix cores.
+//
+// The 2- and 3-bit kernels above are bound by vector-ALU issue (mask, convert and multiply-add
+// are three instructions per code), not by memory.  Here a code costs about one vector
+// instruction: two codes are masked into the mantissas of two bf16 numbers 128 + q with one
+// shift and one and-or (0x4300 is 128.0 in bf16, and 128 + q needs 8 significant bits), and
+// v_mfma_f32_32x32x16_bf16 multiplies 32 outputs x 16 k of them with x and accumulates in fp32.
+// x stays exact: every fp32 value is the sum of three bf16 numbers (8 + 8 + 8 significant bits),
+// which occupy three rows of the instruction's A operand; the other 29 rows are zero.  The
+// products are exact in fp32, the sums are fp32, and per group
+//     y_n += s (T - (128 + z) xhat),   T = sum_k x_k (128 + q_k)
+// which is eq. (2) again with the offset of the code folded into the zero-point.
+//
+// Data movement.  A wavefront still owns 64 outputs, one per lane.  The matrix instruction
+// wants lanes l and l + 32 to hold two different k-octets of the SAME output, so two
+// neighbouring cells of a lane (c, c + 1) are exchanged between the wavefront's halves with
+// v_permlane32_swap: afterwards lanes 0-31 hold cell c and lanes 32-63 cell c + 1 of outputs
+// 0-31 (P), and likewise for outputs 32-63 (Q).  The wavefront keeps its x values of the step
+// in LDS, split into the three parts and stored in the order the unpacked codes have inside
+// an operand; each wavefront has its own region (no barriers), double-buffered over steps.
+// ---------------------------------------------------------------------------------------
+typedef __bf16 mma_bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 mma_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float mma_floatx2 __attribute__((ext_vector_type(2)));
+typedef float mma_floatx16 __attribute__((ext_vector_type(16)));
+
+union MmaOperand {
+    mma_bf16x8 v;
+    uint32_t r[4];
+    uint4 q;
+};
+// LDS holds the parts of x as 16-bit patterns written one by one and read eight at a time:
+// both accesses go through types that may alias anything, so that they stay in program order
+typedef uint16_t __attribute__((may_alias)) lds_u16;
+typedef uint4 __attribute__((may_alias)) lds_u128;
+
+#define QG_MMA_MAGIC 0x43004300u       // two bf16 128.0
+
+// (v & mask) | magic.  Mask and magic reach this as register values the optimiser cannot see
+// through (MmaConst), which is what makes it one v_and_or_b32 instead of an AND and an OR with
+// literal operands.
+__device__ inline uint32_t and_or(uint32_t v, uint32_t mask, uint32_t magic)
+{
+    return (v & mask) | magic;
+}
+
+struct MmaConst {
+    uint32_t mask, magic;
+};
+
+template <int BITS>
+__device__ inline MmaConst mma_constants()
+{
+    MmaConst c;
+    c.mask = BITS == 4 ? 0x000f000fu : BITS == 2 ? 0x00030003u : 0x00070007u;
+    c.magic = QG_MMA_MAGIC;
+    asm("" : "+s"(c.mask));
+    asm("" : "+v"(c.magic));
+    return c;
+}
+
+// Codes per matrix-instruction operand: 8 per lane.  A cell unpacks into OPS operands.
+template <int BITS> constexpr int mma_ops() { return Fmt<BITS>::CELL / 8; }
+
+// Position (operand, element) of code i of a cell after unpacking; the x values are stored
+// in the same order.
+template <int BITS>
+__device__ inline int mma_slot(int i)
+{
+    if constexpr (BITS == 4) {
+        return i < 4 ? 2 * i : 2 * (i - 4) + 1;                 // register j = codes j, j + 4
+    } else if constexpr (BITS == 2) {
+        const int j = i & 7;                                     // register j = codes j, j + 8
+        return (j >> 2) * 8 + 2 * (j & 3) + (i >> 3);
+    } else {
+        // word A, B, C or T holds codes 8 w + {0..7}: byte b has code b (low field) and
+        // 4 + b (high field); registers take bytes (0, 2) low, (0, 2) high, (1, 3) low, (1, 3) high
+        const int w = i >> 3, r = i & 7;
+        const int b = r & 3, high = r >> 2;
+        return w * 8 + ((b & 1) * 2 + high) * 2 + (b >> 1);
+    }
+}
+
+// Unpacks the word(s) of one cell (already exchanged between the halves) into OPS operands.
+template <int BITS>
+__device__ inline void mma_unpack(const uint32_t *w, const MmaConst &c, MmaOperand *op)
+{
+    const uint32_t mask = c.mask, magic = c.magic;
+    if constexpr (BITS == 4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) op[0].r[j] = and_or(w[0] >> (4 * j), mask, magic);
+    } else if constexpr (BITS == 2) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) op[j >> 2].r[j & 3] = and_or(w[0] >> (2 * j), mask, magic);
+    } else {
+        const uint32_t t = ((w[0] >> 6) & 0x03030303u) | ((w[1] >> 4) & 0x0c0c0c0cu) | ((w[2] >> 2) & 0x30303030u);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t src = k < 3 ? w[k] : t;
+            op[k].r[0] = and_or(src, mask, magic);
+            op[k].r[1] = and_or(src >> 3, mask, magic);
+            op[k].r[2] = and_or(src >> 8, mask, magic);
+            op[k].r[3] = and_or(src >> 11, mask, magic);
+        }
+    }
+}
+
+// x-hat of the groups of a step from the per-lane x values (Algorithm 1's sum of x)
+template <int BITS, int GPS>
+__device__ inline void step_group_sums(const StepData<BITS, GPS> &d, float *xhat)
+{
+    using D = StepData<BITS, GPS>;
+    constexpr int G = codes_per_step<BITS>() / GPS;
+    if constexpr (G >= 128) {
+#pragma unroll
+        for (int g = 0; g < GPS; ++g) {
+            float v = 0.0f;
+#pragma unroll
+            for (int i = 0; i < G / 128; ++i) v += d.xv[g * (G / 128) + i].x + d.xv[g * (G / 128) + i].y;
+            segment_sums<64>(v, &xhat[g]);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < D::NXV; ++i) segment_sums<G / 2>(d.xv[i].x + d.xv[i].y, &xhat[i * (128 / G)]);
+    }
+}
+
+template <int BITS, int CPG>
+__global__ __launch_bounds__(512) void gemv_mma(const GemvArgs A)
+{
+    using F = Fmt<BITS>;
+    constexpr int L = loads_per_step<BITS>();
+    constexpr int S = codes_per_step<BITS>();
+    constexpr int CELLS = cells_per_step<BITS>();
+    constexpr int GPS = CELLS / CPG;
+    constexpr int OPS = mma_ops<BITS>();
+    constexpr int NXV = S / 128;
+    using D = StepData<BITS, GPS>;
+    static_assert(CPG >= 2 && CPG % 2 == 0, "a group must hold whole pairs of cells");
+    __shared__ float red[16][QG_WAVE];
+    // one block of zeros for the unused rows of the A operand, shared by everybody; per
+    // wavefront and buffer three parts of x in operand order (dynamic: sized by the launch for
+    // the wavefronts a workgroup really has, so that more workgroups fit a compute unit)
+    __shared__ __attribute__((aligned(16))) lds_u16 zeros[S];
+    extern __shared__ __attribute__((aligned(16))) lds_u16 xs_raw[];
+    lds_u16(*xs)[2][3][S] = (lds_u16(*)[2][3][S])xs_raw;
+
+    const int pi = find_problem(A, blockIdx.x);
+    const GemvProblem P = A.p[pi];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.steps, wave);
+    if (!job.work) return;                      // no work: leave before the barrier
+    const int tile = job.tile, s0 = job.item0, s1 = job.item1;
+
+    TileView T;
+    T.codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
+    T.scales = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
+    T.zeros = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+    T.x = P.x;
+
+    // every wavefront clears the zero block itself before it reads it (same values from all)
+#pragma unroll
+    for (int i = lane; i < S; i += QG_WAVE) zeros[i] = 0;
+
+    // where this lane's x values go: x[128 i + 2 lane + e] of the step is code (k % CELL) of
+    // cell k / CELL; cells pair up as (2 cp, 2 cp + 1) = the two halves of an operand
+    int xpos[NXV][2];
+#pragma unroll
+    for (int i = 0; i < NXV; ++i)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int k = 128 * i + 2 * lane + e;
+            const int cell = k / F::CELL, slot = mma_slot<BITS>(k % F::CELL);
+            xpos[i][e] = (((cell >> 1) * OPS + (slot >> 3)) * 2 + (cell & 1)) * 8 + (slot & 7);
+        }
+    // A operand: row = lane % 32 (rows 0-2 = the parts of x, the others zero), half = lane / 32
+    const int row = lane & 31, half = lane >> 5;
+    const lds_u16 *abase[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) abase[b] = row < 3 ? &xs[wave][b][row][half * 8] : &zeros[half * 8];
+
+    // splits the step's x values into three bf16 parts and stores them for the A operands
+    auto stage_x = [&](const D &d, int buf) {
+#pragma unroll
+        for (int i = 0; i < NXV; ++i) {
+            mma_floatx2 r = {d.xv[i].x, d.xv[i].y};
+#pragma unroll
+            for (int part = 0; part < 3; ++part) {
+                const mma_bf16x2 h = __builtin_convertvector(r, mma_bf16x2);     // round to nearest even
+                const uint32_t bits = *(const uint32_t *)&h;
+                xs[wave][buf][part][xpos[i][0]] = (uint16_t)bits;
+                xs[wave][buf][part][xpos[i][1]] = (uint16_t)(bits >> 16);
+                r[0] -= __uint_as_float(bits << 16);                             // exact
+                r[1] -= __uint_as_float(bits & 0xffff0000u);
+            }
+        }
+    };
+
+    const MmaConst mc = mma_constants<BITS>();
+    float yacc = 0.0f;
+
+    auto compute = [&](const D &d, int step, int buf) {
+        float xhat[GPS];
+        step_group_sums<BITS, GPS>(d, xhat);
+        mma_floatx16 accP, accQ;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accQ[i] = 0.0f; }
+#pragma unroll
+        for (int cp = 0; cp < CELLS / 2; ++cp) {
+            // words of cells 2 cp and 2 cp + 1, exchanged between the halves
+            uint32_t wp[F::PLANES], wq[F::PLANES];
+            const int c0 = 2 * cp, u = c0 >> 2, j = c0 & 3;
+#pragma unroll
+            for (int pl = 0; pl < F::PLANES; ++pl) {
+                const auto sw = __builtin_amdgcn_permlane32_swap(word_of(d.v[u * F::PLANES + pl], j),
+                                                                 word_of(d.v[u * F::PLANES + pl], j + 1), false, false);
+                wp[pl] = sw[0];       // outputs 0-31: cell 2 cp in lanes 0-31, cell 2 cp + 1 in lanes 32-63
+                wq[pl] = sw[1];       // outputs 32-63
+            }
+            MmaOperand bp[OPS], bq[OPS];
+            mma_unpack<BITS>(wp, mc, bp);
+            mma_unpack<BITS>(wq, mc, bq);
+#pragma unroll
+            for (int op = 0; op < OPS; ++op) {
+                MmaOperand a;
+                a.q = *(const lds_u128 *)(abase[buf] + (cp * OPS + op) * 16);
+                accP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bp[op].v, accP, 0, 0, 0);
+                accQ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bq[op].v, accQ, 0, 0, 0);
+            }
+            if ((2 * cp + 2) % CPG == 0) {
+                // a group is complete: rows 0-2 of the result (lanes 0-31) are the three parts
+                const int gs = (2 * cp + 2) / CPG - 1;
+                const int gabs = step * GPS + gs;
+                const float tp = accP[0] + accP[1] + accP[2], tq = accQ[0] + accQ[1] + accQ[2];
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tp), __float_as_uint(tq), false, false);
+                const float tsum = __uint_as_float(sw[0]);           // lane l: output l of the tile
+                const uint32_t zword = d.zw[D::ZW > 1 ? gs / D::ZPER : 0];
+                const float zf = (float)(((zword >> (F::ZBITS * (gabs % D::ZPER))) & ((1u << F::ZBITS) - 1u)) + 128u);
+                yacc = fmaf(d.s[gs], fmaf(-zf, xhat[gs], tsum), yacc);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accQ[i] = 0.0f; }
+            }
+        }
+    };
+
+    // two register buffers and two LDS buffers used alternately, as in gemv_static
+    const int last = s1 - 1;
+    D da, db;
+    fetch_step(da, T, s0, lane);
+    stage_x(da, 0);
+    for (int s = s0; s < s1; s += 2) {
+        const int sb = s + 1 < last ? s + 1 : last;
+        const int sc = s + 2 < last ? s + 2 : last;
+        fetch_step(db, T, sb, lane);
+        compute(da, s, 0);
+        if (s + 1 >= s1) break;                       // odd number of steps
+        stage_x(db, 1);
+        fetch_step(da, T, sc, lane);
+        compute(db, sb, 1);
+        stage_x(da, 0);
+    }
+    finish_tile(P, job, yacc, red);
+}
+
+// ---------------------------------------------------------------------------------------
 // Groups that are a whole number of steps (G = 256, ..., up to one group per output: the
 // full-column case of eq. (1)).  A wavefront's range of steps need not begin or end at a group
 // boundary: s (sum q x - z sum x) is linear in the two sums, so the pieces of a group that
@@ -602,6 +868,7 @@ __global__ void fill_u32(uint32_t *p, size_t n, uint32_t value)
 
 int g_tune_wpb = 0;
 int g_tune_bytes_per_wave = 0;
+int g_tune_kernel = 0;       // 0 = built-in choice, 1 = vector-ALU kernels, 2 = matrix-core kernel where it exists
 
 enum Kind { KIND_STATIC, KIND_RUNTIME, KIND_GENERIC };
 
@@ -671,6 +938,32 @@ void launch_static(int cpg, unsigned blocks, unsigned threads, hipStream_t st, c
     }
 }
 
+template <int BITS>
+void launch_mma(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+{
+    // x of one step in three bf16 parts, two buffers, per wavefront
+    const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 3 * codes_per_step<BITS>() * sizeof(uint16_t);
+    switch (cpg) {
+    case 2: hipLaunchKernelGGL((gemv_mma<BITS, 2>), dim3(blocks), dim3(threads), lds, st, A); break;
+    case 4: hipLaunchKernelGGL((gemv_mma<BITS, 4>), dim3(blocks), dim3(threads), lds, st, A); break;
+    case 8: hipLaunchKernelGGL((gemv_mma<BITS, 8>), dim3(blocks), dim3(threads), lds, st, A); break;
+    case 16:
+        if constexpr (BITS != 3)
+            hipLaunchKernelGGL((gemv_mma<BITS, 16>), dim3(blocks), dim3(threads), lds, st, A);
+        break;
+    }
+}
+
+// Whether a static-group problem runs on the matrix cores.  That kernel needs a group of at
+// least two cells.  Measured on the layer sets: ahead at 3 bits (by 8 %), level at 2 bits,
+// behind at 4 bits, where the vector-ALU kernel is bound by memory anyway.
+bool use_mma(int bits, int cpg)
+{
+    if (cpg < 2) return false;
+    if (g_tune_kernel) return g_tune_kernel == 2;
+    return bits == 3;
+}
+
 // One launch for problems that share (bits, group, kernel kind).
 int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const size_t *ws_off,
                  char *workspace, hipStream_t st)
@@ -696,7 +989,12 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     // `target` per wavefront so that the chip is still covered.
     // wavefronts per team, at most (measured: 12 is best for the 4-bit kernels, 8 for the
     // 2- and 3-bit ones, which hold more registers per wavefront)
-    const int cap = g_tune_wpb > 0 ? g_tune_wpb : (L[0].bits == 4 ? 12 : 8);
+    const bool mma = kind == KIND_STATIC && use_mma(L[0].bits, L[0].group / L[0].cell);
+    int cap = g_tune_wpb > 0 ? g_tune_wpb : (L[0].bits == 4 ? 12 : 8);
+    if (mma) {                                 // the matrix-core kernel is built for at most 8 wavefronts;
+        if (cap > 8) cap = 8;                  // measured: teams of 4 are best for it
+        if (g_tune_wpb == 0) cap = 4;
+    }
     size_t target = (size_t)g_tune_bytes_per_wave;               // code bytes per wavefront
     if (target == 0) {
         size_t code_bytes = 0;
@@ -777,7 +1075,11 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     const int bits = L[0].bits;
     if (kind == KIND_STATIC) {
         const int cpg = L[0].group / L[0].cell;
-        if (bits == 4) launch_static<4>(cpg, blocks, threads, st, A);
+        if (mma) {
+            if (bits == 4) launch_mma<4>(cpg, blocks, threads, st, A);
+            else if (bits == 2) launch_mma<2>(cpg, blocks, threads, st, A);
+            else launch_mma<3>(cpg, blocks, threads, st, A);
+        } else if (bits == 4) launch_static<4>(cpg, blocks, threads, st, A);
         else if (bits == 2) launch_static<2>(cpg, blocks, threads, st, A);
         else launch_static<3>(cpg, blocks, threads, st, A);
     } else if (kind == KIND_RUNTIME) {
@@ -794,11 +1096,13 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
 
 }  // namespace
 
-extern "C" int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave)
+extern "C" int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel)
 {
-    if (waves_per_block < 0 || waves_per_block > 16 || bytes_per_wave < 0) return QG_ERR_SHAPE;
+    if (waves_per_block < 0 || waves_per_block > 16 || bytes_per_wave < 0 || kernel < 0 || kernel > 2)
+        return QG_ERR_SHAPE;
     g_tune_wpb = waves_per_block;
     g_tune_bytes_per_wave = bytes_per_wave;
+    g_tune_kernel = kernel;
     return QG_OK;
 }
 

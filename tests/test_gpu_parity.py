@@ -113,7 +113,7 @@ def test_device_pack_unpack_identity(qg, N, K, bits, group):
 
 # ------------------------------------------------------------------ GEMV (tolerance)
 
-def _gemv_case(qg, oracle, W, x, bits, group, tuning=(0, 0)):
+def _gemv_case(qg, oracle, W, x, bits, group, tuning=(0, 0, 0)):
     N, K = W.shape
     q0, s0, z0 = oracle.quantize(W, bits, group)
     y_ref = oracle.matvec(q0, s0, z0, group, x)
@@ -131,7 +131,7 @@ def _gemv_case(qg, oracle, W, x, bits, group, tuning=(0, 0)):
         qg.qg_gemv(blob, N, K, bits, group, dev(x), y2, ws)                    # workspace reuse
         torch.cuda.synchronize()
     finally:
-        qg.qg_set_gemv_tuning(0, 0)
+        qg.qg_set_gemv_tuning(0, 0, 0)
     yh = host(y)
     assert np.all(yh[N:] == 7.0), "write past the end of y"
     assert np.array_equal(yh[:N], host(y2)), "not deterministic / workspace not left clean"
@@ -169,15 +169,29 @@ GEMV_CASES = [  # N, K, bits, group   -- (kernel flavour)
 ]
 
 
+@pytest.mark.parametrize("kernel", [1, 2])       # multiply-adds on the vector ALU / on the matrix cores
 @pytest.mark.parametrize("N,K,bits,group", GEMV_CASES)
-def test_gemv_matches_oracle(qg, oracle, N, K, bits, group):
-    _announce("gemv", N, K, bits, group)
+def test_gemv_matches_oracle(qg, oracle, N, K, bits, group, kernel):
+    _announce("gemv", N, K, bits, group, kernel)
     W, x = synth.small_case(N + 3 * K + bits, N, K, 0.02, True)
-    err = _gemv_case(qg, oracle, W, x, bits, group)
+    err = _gemv_case(qg, oracle, W, x, bits, group, (0, 0, kernel))
     assert err <= TOL_FP32, err
 
 
-@pytest.mark.parametrize("tuning", [(1, 4096), (2, 4096), (4, 8192), (8, 4096), (16, 4096), (4, 65536)])
+@pytest.mark.parametrize("bits,group", [(4, 16), (4, 32), (4, 64), (4, 128), (2, 32), (2, 64), (2, 128), (2, 256),
+                                        (3, 64), (3, 128), (3, 256)])
+def test_gemv_matrix_core_kernel_every_group_size(qg, oracle, bits, group):
+    # x with a wide range of magnitudes and both signs: its split into three bf16 parts must be exact
+    _announce("gemv matrix cores", bits, group)
+    N, K = 200, 2048
+    W, x = synth.small_case(40 + bits + group, N, K, 0.02, True)
+    x = (x * np.exp2(np.arange(K) % 40 - 20)).astype(np.float32)
+    err = _gemv_case(qg, oracle, W, x, bits, group, (0, 0, 2))
+    assert err <= TOL_FP32, err
+
+
+@pytest.mark.parametrize("tuning", [(1, 4096, 1), (2, 4096, 1), (4, 8192, 1), (8, 4096, 1), (16, 4096, 1), (4, 65536, 1),
+                                    (1, 4096, 2), (3, 8192, 2), (8, 4096, 2), (16, 4096, 2), (4, 65536, 2)])
 @pytest.mark.parametrize("N,K,bits,group", [(200, 4096, 4, 128), (130, 3072, 3, 64), (130, 4096, 2, 32),
                                             (70, 4096, 4, 1024), (70, 5632, 4, 5632), (70, 3840, 3, 1280)])
 def test_gemv_k_split_shapes(qg, oracle, N, K, bits, group, tuning):

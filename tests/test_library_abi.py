@@ -73,6 +73,6 @@ def test_bad_shapes_are_rejected_without_a_gpu(qg):
     assert L.qg_gemv(16, 64, 128, 4, 32, 64, 16, 16, 0, None) == 5      # workspace too small
     assert L.qg_gemv(16, 64, 128, 4, 32, 16, 16, 16, 0, None) == 4      # x not 64-byte aligned
     assert L.qg_gemv_grouped(None, 1, None, 0, None) == 1
-    assert L.qg_set_gemv_tuning(99, 0) == 2
-    assert L.qg_set_gemv_tuning(0, 0) == 0
+    assert L.qg_set_gemv_tuning(99, 0, 0) == 2
+    assert L.qg_set_gemv_tuning(0, 0, 0) == 0
     assert b"aligned" in L.qg_status_string(4)
