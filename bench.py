@@ -69,15 +69,20 @@ def cpu_baseline(cfg, problems, passes=5):
         q, s, z, x = p["host"]
         packed.append((oracle.pack_codes(q, cfg.bits), oracle.transpose_scales(s),
                        oracle.pack_zeros(z, cfg.bits), p["K"], x))
-    times = []
-    for _ in range(passes):
+    def one_pass():
         t0 = time.perf_counter()
         for P, St, Zp, K, x in packed:
             oracle.matvec_packed(P, St, Zp, K, cfg.bits, cfg.group, x)
-        times.append(time.perf_counter() - t0)
+        return time.perf_counter() - t0
+    cores = oracle.threads()
+    times = [one_pass() for _ in range(passes)]
+    oracle.set_threads(1)
+    single = [one_pass() for _ in range(2)]
+    oracle.set_threads(cores)
     return {"value": round(float(np.median(times)) * 1e6, 1), "unit": "us per layer set",
-            "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"full {cfg.name} layer set from the canonical packed format, median of {passes} passes"}
+            "cores": cores, "kind": "oracle",
+            "sample": f"full {cfg.name} layer set from the canonical packed format, median of {passes} passes",
+            "single_thread_us": round(float(min(single)) * 1e6, 1)}
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X public dense bf16 peak
@@ -253,6 +258,15 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ms_per_step = start.elapsed_time(stop) / args.steps
+    # the same timed loop four more times: spread of the measurement (the first one is `value`)
+    repeats = [ms_per_step * 1e3]
+    for _ in range(4):
+        start.record()
+        for i in range(args.steps):
+            launches[i % copies].launch(stream)
+        stop.record()
+        torch.cuda.synchronize()
+        repeats.append(start.elapsed_time(stop) / args.steps * 1e3)
 
     # the same launches on a single copy: weights served largely by the last-level cache
     for i in range(20):
@@ -280,6 +294,8 @@ def main():
                    "algorithmic_bytes_per_set": alg},
         "effective_weight_GBps": round(achieved, 1),
         "pct_of_hbm_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
+        "repeats_us": [round(r, 3) for r in repeats],
+        "repeats_median_us": round(float(np.median(repeats)), 3), "repeats_min_us": round(min(repeats), 3),
         "cache_warm_single_copy_us": round(warm_ms * 1e3, 3),
         "host_wall_ms_per_step": round(wall_ms / args.steps, 6),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -23,6 +23,8 @@ def lib():
         L = ctypes.CDLL(path)
         i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
         L.qgo_threads.restype = i32
+        L.qgo_set_threads.restype = None
+        L.qgo_set_threads.argtypes = [i32]
         L.qgo_code_words.restype = i64
         L.qgo_code_words.argtypes = [i64, i32]
         L.qgo_storage_bits.restype = i64
@@ -65,6 +67,10 @@ def _check(rc, what):
 
 def threads():
     return int(lib().qgo_threads())
+
+
+def set_threads(n: int):
+    lib().qgo_set_threads(int(n))
 
 
 def quantize(W, bits, group):

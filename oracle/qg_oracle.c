@@ -44,6 +44,17 @@ int qgo_threads(void)
 #endif
 }
 
+/* Number of threads the loops over outputs use from now on (timing only; results do not
+ * depend on it: every output is summed by one thread in index order). */
+void qgo_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 /* ---------------------------------------------------------------------------------------
  * Quantization (Section 2, "Quantization": Q(x,b) maps to integers in [0, 2^b); D(x_q) =
  * s (x_q - z) as fixed by eq. (1)).  Reading used here, stated in the task as
