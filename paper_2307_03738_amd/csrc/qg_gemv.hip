@@ -22,6 +22,11 @@
 // adds it (a + b = b + a, so the bits do not depend on who was second) and carries the sum
 // to the next level.  The value travels inside the atomic itself, so no fence and no cache
 // maintenance is needed, and results do not depend on timing.
+//
+// Kernels: gemv_static (groups up to one step, the arithmetic above on the vector ALU),
+// gemv_mma (the same groups with the multiply-adds on the matrix cores, see there),
+// gemv_runtime (groups of whole steps up to one group per output, eq. (1)) and gemv_generic
+// (anything else).  All share the work distribution and the reductions.
 #include "qg_common.h"
 
 namespace {

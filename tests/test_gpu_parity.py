@@ -221,7 +221,9 @@ def test_gemv_zero_input_and_unit_scale(qg, oracle):
 def test_gemv_grouped_mixed_problems(qg, oracle):
     _announce("gemv grouped, mixed shapes and formats")
     specs = [(200, 1024, 4, 128), (130, 512, 4, 128), (64, 1536, 3, 64), (90, 480, 4, 24),
-             (257, 1024, 2, 32), (512, 512, 4, 128), (100, 2048, 4, 2048)]
+             (257, 1024, 2, 32), (512, 512, 4, 128), (100, 2048, 4, 2048),
+             (70, 2304, 4, 768), (130, 5632, 4, 5632),       # long groups of different sizes share a launch
+             (66, 1536, 3, 768), (77, 1024, 3, 64)]
     problems, refs = [], []
     for i, (N, K, bits, group) in enumerate(specs):
         W, x = synth.small_case(900 + i, N, K, 0.02, True)
