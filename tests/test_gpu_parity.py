@@ -203,6 +203,17 @@ def test_gemv_k_split_shapes(qg, oracle, N, K, bits, group, tuning):
     assert err <= TOL_FP32, err
 
 
+@pytest.mark.parametrize("N,K,bits,group", [(70, 1 << 20, 4, 128),      # a very long K: 32 workgroups x 12 wavefronts per tile
+                                            (70, 1 << 19, 2, 1 << 19),   # ... as one group per output
+                                            (1 << 20, 128, 4, 128),      # a very long N: one step per tile
+                                            (300000, 256, 3, 64)])
+def test_gemv_extreme_shapes(qg, oracle, N, K, bits, group):
+    _announce("gemv extreme", N, K, bits, group)
+    W, x = synth.small_case(7 + bits, N, K, 0.02, False)
+    err = _gemv_case(qg, oracle, W, x, bits, group)
+    assert err <= TOL_FP32, err
+
+
 def test_gemv_zero_input_and_unit_scale(qg, oracle):
     _announce("gemv x = 0, s = 1 z = 0")
     rng = np.random.default_rng(5)
@@ -317,6 +328,14 @@ def test_gemm_small_matches_oracle(qg, oracle, N, K, bits, group, M):
     _announce("gemm_small", N, K, bits, group, M)
     W, X = synth.small_case(N + K + M, N, K, 0.02, True, m=max(M, 2))
     X = X[:M]
+    err = _gemm_case(qg, oracle, W, X, bits, group)
+    assert err <= TOL_BF16, err
+
+
+def test_gemm_small_longest_k_of_the_matrix_core_path(qg, oracle):
+    _announce("gemm_small K = 2^20")
+    N, K, bits, group, M = 70, 1 << 20, 4, 128, 9
+    W, X = synth.small_case(31, N, K, 0.02, False, m=M)
     err = _gemm_case(qg, oracle, W, X, bits, group)
     assert err <= TOL_BF16, err
 
