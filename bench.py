@@ -201,6 +201,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", default="C2", choices=["C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--autotune", action="store_true",
+                    help="let qg_gemv_autotune pick the launch shape (timed over the rotated copies) before the run")
     ap.add_argument("--sweep-groups", type=lambda s: [int(v) for v in s.split(",")], default=[16, 32, 64, 128, 0],
                     help="group sizes of --sweep; 0 = one group per output")
     ap.add_argument("--sweep", action="store_true",
@@ -245,6 +247,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    tuned = None
+    if args.autotune:
+        tuned = qg.qg_gemv_autotune(launches, repeats=2 * copies)
     stream = torch.cuda.current_stream().cuda_stream
     for i in range(args.warmup):
         launches[i % copies].launch(stream)
@@ -302,6 +307,9 @@ def main():
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name)},
     }
+    if tuned is not None:
+        out["autotuned"] = {"waves_per_block": tuned[0], "bytes_per_wave": tuned[1], "kernel": tuned[2],
+                            "us_while_tuning": round(tuned[3], 3)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, base)
     print(json.dumps(out))

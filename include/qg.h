@@ -138,6 +138,19 @@ int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
  * kernel = 1: multiply-adds on the vector ALU, 2: on the matrix cores (where that kernel
  * exists: groups of at least two cells and at most one step). */
 int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel);
+/* Search for the fastest launch shape of one grouped launch by timing -- this machine's
+ * counterpart of the paper's parameter search (Section 3, Algorithm 4).  `descs` holds `sets`
+ * copies of the launch back to back (set i at descs + i * count; same shapes, normally
+ * different packed buffers, so that a cache cannot serve the weights; sets = 1 times one set
+ * again and again).  Runs the launch `repeats` times, rotating over the sets, for each of 50
+ * candidates (team size x bytes per wavefront x vector-ALU or matrix-core kernel), WAITS for
+ * the GPU (the only call that does), leaves the fastest installed as qg_set_gemv_tuning would,
+ * and reports it (HOST pointers, each may be NULL; best_us = microseconds per launch).  The
+ * outputs y are overwritten as by qg_gemv_grouped; all sets share the workspace. */
+int qg_gemv_autotune(const qg_gemv_desc *descs /* HOST */, int count, int sets,
+                     void *workspace, size_t workspace_bytes, void *stream, int repeats,
+                     int *waves_per_block, int *bytes_per_wave, int *kernel, float *best_us);
+
 /* Same for qg_gemm_small: splits in 1..8 = number of K ranges handled by different
  * workgroups (clamped to what the shape allows); shape in 1..7 = workgroup shape (how many
  * tiles and K slices the wavefronts of a workgroup cover; ignored if it does not fit M).

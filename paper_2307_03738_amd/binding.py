@@ -58,6 +58,10 @@ def lib():
         L.qg_gemm_small.argtypes = [vp, i64, i64, i32, i32, vp, i32, vp, vp, sz, vp]
         L.qg_set_gemv_tuning.restype = i32
         L.qg_set_gemv_tuning.argtypes = [i32, i32, i32]
+        L.qg_gemv_autotune.restype = i32
+        L.qg_gemv_autotune.argtypes = [ctypes.POINTER(_Desc), i32, i32, vp, sz, vp, i32,
+                                       ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32),
+                                       ctypes.POINTER(ctypes.c_float)]
         L.qg_set_gemm_tuning.restype = i32
         L.qg_set_gemm_tuning.argtypes = [i32, i32]
         _LIB = L
@@ -205,6 +209,28 @@ def qg_gemm_small(packed: torch.Tensor, N: int, K: int, bits: int, group: int, X
 
 def qg_set_gemv_tuning(waves_per_block: int = 0, bytes_per_wave: int = 0, kernel: int = 0):
     _check(lib().qg_set_gemv_tuning(waves_per_block, bytes_per_wave, kernel), "qg_set_gemv_tuning")
+
+
+def qg_gemv_autotune(launches, repeats: int = 20):
+    """Times the candidates on the prepared launch(es) -- a GroupedGemv or a list of them with the
+    same shapes, rotated -- and leaves the fastest installed; returns (waves_per_block,
+    bytes_per_wave, kernel, microseconds per launch)."""
+    if isinstance(launches, GroupedGemv):
+        launches = [launches]
+    count = launches[0].count
+    if any(l.count != count for l in launches):
+        _check(2, "qg_gemv_autotune")
+    descs = (_Desc * (count * len(launches)))()
+    for s, l in enumerate(launches):
+        for i in range(count):
+            descs[s * count + i] = l.descs[i]
+    ws = launches[0].workspace
+    w, b, k = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    us = ctypes.c_float()
+    _check(lib().qg_gemv_autotune(descs, count, len(launches), ws.data_ptr(), ws.numel(), _stream(), repeats,
+                                  ctypes.byref(w), ctypes.byref(b), ctypes.byref(k), ctypes.byref(us)),
+           "qg_gemv_autotune")
+    return w.value, b.value, k.value, us.value
 
 
 def qg_set_gemm_tuning(splits: int = 0, shape: int = 0):

@@ -1206,3 +1206,66 @@ extern "C" int qg_gemv(const void *packed, int64_t N, int64_t K, int bits, int g
     d.y = y;
     return qg_gemv_grouped(&d, 1, workspace, workspace_bytes, stream);
 }
+
+// Empirical choice of the launch shape for one grouped launch: the counterpart of the paper's
+// parameter search (Section 3, Algorithm 4 with the model of eqs. (3)-(5)), done by timing
+// instead of by a cache model.  Every candidate (team size, bytes per wavefront, vector-ALU or
+// matrix-core kernel) runs the launch a few times between two events; the fastest is left
+// installed as with qg_set_gemv_tuning.  Unlike every other call this one waits for the GPU.
+extern "C" int qg_gemv_autotune(const qg_gemv_desc *descs, int count, int sets, void *workspace,
+                                size_t workspace_bytes, void *stream, int repeats,
+                                int *waves_per_block, int *bytes_per_wave, int *kernel,
+                                float *best_us)
+{
+    if (repeats <= 0 || sets <= 0) return QG_ERR_SHAPE;
+    if (!descs) return QG_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    const int saved[3] = {g_tune_wpb, g_tune_bytes_per_wave, g_tune_kernel};
+    int rc = QG_OK;
+    for (int s = 0; s < sets && rc == QG_OK; ++s)                                  // argument checks
+        rc = qg_gemv_grouped(descs + (size_t)s * count, count, workspace, workspace_bytes, stream);
+    if (rc != QG_OK) return rc;
+    int turn = 0;
+    auto run = [&]() {
+        const qg_gemv_desc *d = descs + (size_t)(turn++ % sets) * count;
+        return qg_gemv_grouped(d, count, workspace, workspace_bytes, stream);
+    };
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return QG_ERR_DEVICE;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return QG_ERR_DEVICE; }
+    static const int teams[] = {0, 4, 8, 12, 16};
+    static const int sizes[] = {0, 4096, 8192, 16384, 32768};
+    int best[3] = {0, 0, 0};
+    float best_ms = -1.0f;
+    for (int k = 1; k <= 2 && rc == QG_OK; ++k)
+        for (int a = 0; a < 5 && rc == QG_OK; ++a)
+            for (int b = 0; b < 5 && rc == QG_OK; ++b) {
+                g_tune_wpb = teams[a];
+                g_tune_bytes_per_wave = sizes[b];
+                g_tune_kernel = k;
+                for (int i = 0; i < 2 && rc == QG_OK; ++i) rc = run();
+                if (rc != QG_OK) break;
+                if (hipEventRecord(e0, st) != hipSuccess) { rc = QG_ERR_DEVICE; break; }
+                for (int i = 0; i < repeats && rc == QG_OK; ++i) rc = run();
+                if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) rc = QG_ERR_DEVICE;
+                float ms = 0.0f;
+                if (rc == QG_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = QG_ERR_DEVICE;
+                if (rc == QG_OK && (best_ms < 0.0f || ms < best_ms)) {
+                    best_ms = ms;
+                    best[0] = teams[a]; best[1] = sizes[b]; best[2] = k;
+                }
+            }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != QG_OK) {
+        g_tune_wpb = saved[0]; g_tune_bytes_per_wave = saved[1]; g_tune_kernel = saved[2];
+        return rc;
+    }
+    g_tune_wpb = best[0]; g_tune_bytes_per_wave = best[1]; g_tune_kernel = best[2];
+    if (waves_per_block) *waves_per_block = best[0];
+    if (bytes_per_wave) *bytes_per_wave = best[1];
+    if (kernel) *kernel = best[2];
+    if (best_us) *best_us = best_ms * 1e3f / (float)repeats;
+    return QG_OK;
+}
+

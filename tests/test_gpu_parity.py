@@ -249,6 +249,33 @@ def test_gemv_grouped_mixed_problems(qg, oracle):
         assert scaled_error(host(y), y_ref, norms, x) <= TOL_FP32
 
 
+def test_gemv_autotune_leaves_a_working_choice(qg, oracle):
+    _announce("gemv autotune")
+    specs = [(300, 2048, 4, 128), (200, 1024, 4, 128), (130, 4096, 4, 128)]
+    problems, refs = [], []
+    for i, (N, K, bits, group) in enumerate(specs):
+        W, x = synth.small_case(1200 + i, N, K, 0.02, True)
+        q0, s0, z0 = oracle.quantize(W, bits, group)
+        refs.append((oracle.matvec(q0, s0, z0, group, x), oracle.row_norms(q0, s0, z0, group), x))
+        q, s, z = qg.qg_quantize(dev(W), bits, group)
+        problems.append(dict(packed=qg.qg_pack(q, s, z, bits, group), N=N, K=K, bits=bits, group=group,
+                             x=dev(x), y=torch.empty(N, dtype=torch.float32, device="cuda")))
+    launch = qg.GroupedGemv(problems)
+    twin = qg.GroupedGemv([dict(p, packed=p["packed"].clone()) for p in problems], launch.workspace)
+    try:
+        wpb, bpw, kernel, us = qg.qg_gemv_autotune([launch, twin], repeats=6)
+        assert wpb in (0, 4, 8, 12, 16) and bpw in (0, 4096, 8192, 16384, 32768) and kernel in (1, 2) and us > 0
+        for p in problems:
+            p["y"].fill_(7.0)
+        launch.launch()
+        torch.cuda.synchronize()
+        for p, (y_ref, norms, x) in zip(problems, refs):
+            assert scaled_error(host(p["y"]), y_ref, norms, x) <= TOL_FP32
+        assert np.all(host(launch.workspace) == 0xFF)
+    finally:
+        qg.qg_set_gemv_tuning(0, 0, 0)
+
+
 # ------------------------------------------------------------------ full benchmark sizes
 
 FULL = [("C2", 0), ("C2", 4), ("C2", 6), ("C3", 0), ("C3", 4), ("C3", 6), ("C4", 0), ("C4", 4), ("C4", 6)]
