@@ -123,6 +123,18 @@ typedef struct qg_gemv_desc {
 int qg_gemv_grouped(const qg_gemv_desc *descs /* HOST */, int count,
                     void *workspace, size_t workspace_bytes, void *stream);
 
+/* The gated MLP input of a LLaMA block in one launch: the packed matrix holds two projections
+ * of the same x, "gate" in outputs [0, I) and "up" in outputs [I, 2I) (a QG_LAYOUT_DEVICE blob
+ * of 2I x K), and
+ *   h[n] = silu(y[n]) * y[I + n],   y = What x as in qg_gemv,   silu(t) = t / (1 + exp(-t))
+ * The two products are the linear layers of Section 3 "Computation" as they sit side by side
+ * in a LLaMA block; the elementwise step that follows them there is folded into the kernel's
+ * epilogue.  I must be a multiple of 64.
+ *   x [K] fp32, 64-byte aligned;  h [I] fp32 (overwritten);
+ * workspace: qg_workspace_bytes(2 I, K, bits, group, 1) bytes, prepared by qg_workspace_init. */
+int qg_gemv_swiglu(const void *packed, int64_t I, int64_t K, int bits, int group,
+                   const float *x, float *h, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Prompt-phase form for M <= 128 tokens:
  *   Y[m][n] = sum_k X[m][k] * s[n][k/G] * (q[n][k] - z[n][k/G])
  * with X and the dequantized weights rounded to bf16 and accumulated in fp32 on the matrix

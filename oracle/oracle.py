@@ -43,6 +43,8 @@ def lib():
             "qgo_matmul_small": [vp, vp, vp, i64, i64, i32, vp, i64, vp],
             "qgo_row_norms": [vp, vp, vp, i64, i64, i32, vp],
         }
+        L.qgo_swiglu.restype = None
+        L.qgo_swiglu.argtypes = [vp, vp, i64, vp]
         for name, args in sigs.items():
             fn = getattr(L, name)
             fn.restype = i32
@@ -179,3 +181,12 @@ def row_norms(q, s, z, group):
     out = np.empty(N, np.float64)
     _check(lib().qgo_row_norms(_p(q), _p(s), _p(z), N, K, group, _p(out)), "row_norms")
     return out
+
+
+def swiglu(g, u):
+    """h = silu(g) * u in fp64 (the gated combination after the "gate" and "up" products)."""
+    g, u = _c(g, np.float64), _c(u, np.float64)
+    h = np.empty_like(g)
+    lib().qgo_swiglu(_p(g), _p(u), g.size, _p(h))
+    return h
+

@@ -342,3 +342,11 @@ int qgo_row_norms(const uint8_t *q, const float *s, const uint8_t *z, int64_t N,
     }
     return 0;
 }
+
+/* The gated combination of two products that a LLaMA block applies after its "gate" and "up"
+ * projections: h[i] = silu(g[i]) * u[i], silu(t) = t / (1 + exp(-t)), in fp64. */
+void qgo_swiglu(const double *g, const double *u, int64_t n, double *h)
+{
+    for (int64_t i = 0; i < n; ++i) h[i] = g[i] / (1.0 + exp(-g[i])) * u[i];
+}
+

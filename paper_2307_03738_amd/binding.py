@@ -54,6 +54,8 @@ def lib():
         L.qg_gemv.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, sz, vp]
         L.qg_gemv_grouped.restype = i32
         L.qg_gemv_grouped.argtypes = [ctypes.POINTER(_Desc), i32, vp, sz, vp]
+        L.qg_gemv_swiglu.restype = i32
+        L.qg_gemv_swiglu.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, sz, vp]
         L.qg_gemm_small.restype = i32
         L.qg_gemm_small.argtypes = [vp, i64, i64, i32, i32, vp, i32, vp, vp, sz, vp]
         L.qg_set_gemv_tuning.restype = i32
@@ -190,6 +192,20 @@ class GroupedGemv:
 def qg_gemv_grouped(problems: Sequence[dict], workspace: Optional[torch.Tensor] = None):
     GroupedGemv(problems, workspace).launch()
     return [p["y"] for p in problems]
+
+
+def qg_gemv_swiglu(packed: torch.Tensor, I: int, K: int, bits: int, group: int, x: torch.Tensor,
+                   h: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(packed, torch.uint8, "packed"); _dev(x, torch.float32, "x")
+    if x.numel() != K or packed.numel() < qg_packed_bytes(2 * I, K, bits, group, QG_LAYOUT_DEVICE):
+        _check(2, "qg_gemv_swiglu")
+    if h is None:
+        h = torch.empty(I, dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = new_workspace(qg_workspace_bytes(2 * I, K, bits, group, 1), x.device)
+    _check(lib().qg_gemv_swiglu(packed.data_ptr(), I, K, bits, group, x.data_ptr(), h.data_ptr(),
+                                workspace.data_ptr(), workspace.numel(), _stream()), "qg_gemv_swiglu")
+    return h
 
 
 def qg_gemm_small(packed: torch.Tensor, N: int, K: int, bits: int, group: int, X: torch.Tensor,

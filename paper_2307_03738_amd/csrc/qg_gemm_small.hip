@@ -383,7 +383,7 @@ size_t qg_gemm_workspace_bytes(const QgLayout &L, int M)
 {
     // partial results of the K split, or the GEMV workspace for the row-by-row path
     const size_t partial = (size_t)MAX_SPLITS * M * L.N * sizeof(float);
-    const size_t gemv = (size_t)L.tiles * QG_MAX_CHUNKS * QG_WAVE * sizeof(uint32_t);
+    const size_t gemv = (size_t)L.tiles * (QG_MAX_CHUNKS + 1) * QG_WAVE * sizeof(uint32_t);   // as qg_gemv asks
     return qg_round_up(fast_path(L) ? partial : gemv, QG_SECTION_ALIGN);
 }
 

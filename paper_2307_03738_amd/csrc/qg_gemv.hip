@@ -49,6 +49,8 @@ struct GemvProblem {
     int steps_per_wave;
     int steps_per_group;   // runtime-group kernel only
     int block_begin;       // first block of this problem in the grid
+    int pair_tiles;        // > 0: outputs [0, 64 pair_tiles) gate outputs [64 pair_tiles, ...), see emit_output
+    float *h;              // gated result (pair_tiles > 0)
 };
 
 #define QG_SLOT_EMPTY 0xffffffffu
@@ -264,6 +266,31 @@ __device__ inline WaveJob locate(const GemvProblem &P, int local_block, int item
     return j;
 }
 
+// Where a finished output goes.  Plain product: y[n].  Gated pair (the MLP of a LLaMA block:
+// the packed matrix holds the "gate" projection in its first 64 * pair_tiles outputs and the
+// "up" projection in the rest, same x): tile t and tile t + pair_tiles meet in one slot per
+// lane exactly like two partners of the reduction tree, and the second to arrive writes
+// h = silu(gate) * up -- the elementwise step that follows the two products, without a launch.
+__device__ inline void emit_output(const GemvProblem &P, int tile, int lane, float v)
+{
+    if (P.pair_tiles == 0) {
+        const int n = tile * QG_WAVE + lane;
+        if (n < P.N) P.y[n] = v;
+        return;
+    }
+    const bool is_up = tile >= P.pair_tiles;
+    const int t = is_up ? tile - P.pair_tiles : tile;
+    // the pair slots follow the tree slots of all tiles
+    uint32_t *slot = P.slots + (size_t)P.tiles * QG_MAX_CHUNKS * QG_WAVE + (size_t)t * QG_WAVE + lane;
+    const uint32_t other = __hip_atomic_exchange(slot, __float_as_uint(v), __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+    if (other == QG_SLOT_EMPTY) return;
+    __hip_atomic_store(slot, QG_SLOT_EMPTY, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const float g = is_up ? __uint_as_float(other) : v;
+    const float u = is_up ? v : __uint_as_float(other);
+    P.h[t * QG_WAVE + lane] = g / (1.0f + expf(-g)) * u;
+}
+
 // K-split epilogue.  The wavefronts of a team pass their 64 partial outputs through LDS
 // (wavefronts without work have already ended; a barrier only waits for wavefronts that are
 // still alive); the team's lead adds them in wavefront order and either stores y or enters
@@ -279,9 +306,8 @@ __device__ inline void finish_tile(const GemvProblem &P, const WaveJob &j, float
     float t = red[j.lead][lane];
     for (int w = 1; w < j.team; ++w) t += red[j.lead + w][lane];
     const int tile = j.tile, chunk = j.chunk;
-    const int n = tile * QG_WAVE + lane;
     if (P.chunks == 1) {
-        if (n < P.N) P.y[n] = t;
+        emit_output(P, tile, lane, t);
         return;
     }
     // pairwise reduction tree over the chunks of this tile, one independent tree per lane
@@ -299,7 +325,7 @@ __device__ inline void finish_tile(const GemvProblem &P, const WaveJob &j, float
         width >>= 1;
         node >>= 1;
     }
-    if (n < P.N) P.y[n] = v;
+    emit_output(P, tile, lane, v);
 }
 
 // Index of the problem a block belongs to: the last one whose first block is <= bid.
@@ -936,7 +962,8 @@ Plan make_plan(const QgLayout &L)
 
 size_t workspace_for(const QgLayout &L)
 {
-    return (size_t)L.tiles * QG_MAX_CHUNKS * QG_WAVE * sizeof(uint32_t);
+    // meeting slots of the reduction tree, then one more row of slots for gated pairs
+    return (size_t)L.tiles * (QG_MAX_CHUNKS + 1) * QG_WAVE * sizeof(uint32_t);
 }
 
 template <int BITS>
@@ -982,7 +1009,7 @@ bool use_mma(int bits, int cpg)
 
 // One launch for problems that share (bits, group, kernel kind).
 int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const size_t *ws_off,
-                 char *workspace, hipStream_t st)
+                 char *workspace, hipStream_t st, const int64_t *gate_rows, float *const *gated)
 {
     GemvArgs A;
     A.count = count;
@@ -1079,6 +1106,8 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         P.team_full = (int)((pl[i].items + spw_of[i] - 1) / spw_of[i]);
         if (P.team_full > P.waves_per_tile) P.team_full = P.waves_per_tile;
         P.tiles_per_block = P.chunks > 1 ? 1 : wpb / P.waves_per_tile;
+        P.pair_tiles = gate_rows ? (int)(gate_rows[idx[i]] / QG_WAVE) : 0;
+        P.h = gated ? gated[idx[i]] : nullptr;
         P.block_begin = blocks;
         A.block_begin[i] = blocks;
         const int64_t nb = P.chunks > 1 ? (int64_t)P.tiles * P.chunks
@@ -1142,8 +1171,10 @@ extern "C" int qg_workspace_init(void *workspace, size_t bytes, void *stream)
     return qg_launch_status();
 }
 
-extern "C" int qg_gemv_grouped(const qg_gemv_desc *descs, int count, void *workspace,
-                               size_t workspace_bytes, void *stream)
+// gate_rows / gated: per problem, the number of gate outputs and the result vector of a gated
+// pair (0 / unused for a plain product); both NULL for plain launches.
+static int gemv_grouped(const qg_gemv_desc *descs, int count, void *workspace, size_t workspace_bytes,
+                        void *stream, const int64_t *gate_rows, float *const *gated)
 {
     if (!descs) return QG_ERR_NULL;
     if (count <= 0) return QG_ERR_SHAPE;
@@ -1154,7 +1185,9 @@ extern "C" int qg_gemv_grouped(const qg_gemv_desc *descs, int count, void *works
         QgLayout L;
         const int rc = qg_make_layout(descs[i].N, descs[i].K, descs[i].bits, descs[i].group, &L);
         if (rc != QG_OK) return rc;
-        if (!descs[i].packed || !descs[i].x || !descs[i].y) return QG_ERR_NULL;
+        const bool pair = gate_rows && gate_rows[i] > 0;
+        if (!descs[i].packed || !descs[i].x || !(pair ? (const void *)gated[i] : (const void *)descs[i].y))
+            return QG_ERR_NULL;
         // x is read with 64-byte scalar loads
         if (!qg_aligned16(descs[i].packed) || ((uintptr_t)descs[i].x & 63u)) return QG_ERR_ALIGN;
         ws_off[i] = need;
@@ -1186,10 +1219,35 @@ extern "C" int qg_gemv_grouped(const qg_gemv_desc *descs, int count, void *works
             for (int b = a; b > 0 && descs[idx[b]].K > descs[idx[b - 1]].K; --b) {
                 const int t = idx[b]; idx[b] = idx[b - 1]; idx[b - 1] = t;
             }
-        const int rc = launch_class(descs, idx, n, ws_off, (char *)workspace, (hipStream_t)stream);
+        const int rc = launch_class(descs, idx, n, ws_off, (char *)workspace, (hipStream_t)stream,
+                                    gate_rows, gated);
         if (rc != QG_OK) return rc;
     }
     return QG_OK;
+}
+
+extern "C" int qg_gemv_grouped(const qg_gemv_desc *descs, int count, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    return gemv_grouped(descs, count, workspace, workspace_bytes, stream, nullptr, nullptr);
+}
+
+extern "C" int qg_gemv_swiglu(const void *packed, int64_t I, int64_t K, int bits, int group,
+                              const float *x, float *h, void *workspace, size_t workspace_bytes,
+                              void *stream)
+{
+    if (I <= 0 || I % QG_WAVE != 0) return QG_ERR_SHAPE;
+    qg_gemv_desc d;
+    d.packed = packed;
+    d.N = 2 * I;
+    d.K = K;
+    d.bits = bits;
+    d.group = group;
+    d.x = x;
+    d.y = nullptr;
+    const int64_t gate_rows = I;
+    float *const gated = h;
+    return gemv_grouped(&d, 1, workspace, workspace_bytes, stream, &gate_rows, &gated);
 }
 
 extern "C" int qg_gemv(const void *packed, int64_t N, int64_t K, int bits, int group,

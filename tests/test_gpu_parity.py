@@ -249,6 +249,44 @@ def test_gemv_grouped_mixed_problems(qg, oracle):
         assert scaled_error(host(y), y_ref, norms, x) <= TOL_FP32
 
 
+@pytest.mark.parametrize("I,K,bits,group,tuning", [(128, 512, 4, 128, (0, 0, 0)), (320, 1024, 4, 64, (0, 0, 0)),
+                                                   (192, 4096, 4, 128, (2, 4096, 1)),      # K cut over workgroups
+                                                   (256, 1536, 3, 64, (0, 0, 0)), (256, 1536, 3, 64, (0, 0, 1)),
+                                                   (128, 2048, 2, 32, (0, 0, 0)), (64, 2048, 4, 2048, (0, 0, 0)),
+                                                   (11008, 4096, 4, 128, (0, 0, 0))])     # LLaMA-7B gate/up
+def test_gemv_swiglu_matches_oracle(qg, oracle, I, K, bits, group, tuning):
+    _announce("gemv swiglu", I, K, bits, group, tuning)
+    std = 0.02 if K < 4096 else 0.02
+    W, x = synth.small_case(2000 + I + bits, 2 * I, K, std, True)
+    q0, s0, z0 = oracle.quantize(W, bits, group)
+    y_ref = oracle.matvec(q0, s0, z0, group, x)
+    g, u = y_ref[:I], y_ref[I:]
+    h_ref = oracle.swiglu(g, u)
+    # what an error of TOL_FP32 * |row| * |x| in each product may do to h (|silu'| <= 1.1, |silu(g)| <= |g|)
+    e = TOL_FP32 * oracle.row_norms(q0, s0, z0, group) * np.linalg.norm(x.astype(np.float64))
+    tol = 1.1 * e[:I] * (np.abs(u) + e[I:]) + np.abs(g) * e[I:] + 1e-6 * np.abs(h_ref)
+    q, s, z = qg.qg_quantize(dev(W), bits, group)
+    blob = qg.qg_pack(q, s, z, bits, group)
+    ws = qg.new_workspace(qg.qg_workspace_bytes(2 * I, K, bits, group, 1))
+    qg.qg_set_gemv_tuning(*tuning)
+    try:
+        h = torch.full((I + 64,), 7.0, dtype=torch.float32, device="cuda")
+        qg.qg_gemv_swiglu(blob, I, K, bits, group, dev(x), h[:I], ws)
+        h2 = qg.qg_gemv_swiglu(blob, I, K, bits, group, dev(x), None, ws)          # workspace reuse
+        y = host(qg.qg_gemv(blob, 2 * I, K, bits, group, dev(x)))                  # same launch shape
+        torch.cuda.synchronize()
+    finally:
+        qg.qg_set_gemv_tuning(0, 0, 0)
+    hh = host(h)
+    assert np.all(hh[I:] == 7.0), "write past the end of h"
+    assert np.array_equal(hh[:I], host(h2)), "not deterministic / workspace not left clean"
+    assert np.all(host(ws) == 0xFF), "workspace not left in its prepared state"
+    assert np.all(np.abs(hh[:I] - h_ref) <= tol), float(np.max(np.abs(hh[:I] - h_ref) / tol))
+    # and it is the plain product (same split of K, so the same bits) followed by the elementwise step
+    yg, yu = y[:I].astype(np.float64), y[I:].astype(np.float64)
+    assert np.allclose(hh[:I], yg / (1.0 + np.exp(-yg)) * yu, rtol=2e-6, atol=1e-30)
+
+
 def test_gemv_autotune_leaves_a_working_choice(qg, oracle):
     _announce("gemv autotune")
     specs = [(300, 2048, 4, 128), (200, 1024, 4, 128), (130, 4096, 4, 128)]

@@ -394,3 +394,25 @@ def test_row_norms_match_numpy(oracle):
     q, s, z = oracle.quantize(W, 4, 16)
     ref = np.linalg.norm(oracle.dequantize(q, s, z, 16), axis=1)
     assert np.allclose(oracle.row_norms(q, s, z, 16), ref, rtol=1e-14)
+
+
+# ------------------------------------------------------------------ gated combination (silu(g) * u)
+
+def test_swiglu_against_identities(oracle):
+    # silu(t) = t * sigmoid(t): checked against the tanh form of the sigmoid, the odd-part identity
+    # silu(t) - silu(-t) = t, its values at 0 and far out, and linearity in u
+    rng = np.random.default_rng(11)
+    g = np.concatenate([rng.standard_normal(200) * 4.0, [0.0, 50.0, -50.0, 1e-9]])
+    u = rng.standard_normal(g.size)
+    one = np.ones_like(g)
+    silu = oracle.swiglu(g, one)
+    near = np.abs(g) < 12.0          # further out 1 + tanh cancels; the limits below cover that range
+    assert np.allclose(silu[near], (g * 0.5 * (1.0 + np.tanh(0.5 * g)))[near], rtol=1e-9, atol=1e-300)
+    assert np.allclose(silu - oracle.swiglu(-g, one), g, rtol=1e-13, atol=1e-15)
+    assert silu[200] == 0.0 and abs(silu[201] - 50.0) < 1e-19 * 50 + 1e-15 and abs(silu[202]) < 1e-19
+    assert np.allclose(oracle.swiglu(g, u), silu * u, rtol=1e-15)
+    assert np.allclose(oracle.swiglu(g, 3.0 * u), 3.0 * oracle.swiglu(g, u), rtol=1e-15)
+    # derivative at 0 is 1/2: silu(t) ~ t/2 + t^2/4 for small t
+    t = np.array([1e-4])
+    assert abs(oracle.swiglu(t, np.ones(1))[0] - (t[0] / 2 + t[0] ** 2 / 4)) < 1e-13
+
