@@ -31,6 +31,8 @@
 #include "qg_common.h"
 
 size_t qg_gemm_workspace_bytes(const QgLayout &L, int M);
+int qg_gemm_rows16(const void *packed, int64_t N, int64_t K, int bits, int group, const float *X,
+                   int M, float *Y, void *workspace, void *stream);   // qg_gemv.hip
 
 namespace {
 
@@ -389,7 +391,7 @@ size_t qg_gemm_workspace_bytes(const QgLayout &L, int M)
 
 extern "C" int qg_set_gemm_tuning(int splits, int shape)
 {
-    if (splits < 0 || splits > MAX_SPLITS || shape < 0 || shape > NSHAPES) return QG_ERR_SHAPE;
+    if (splits < 0 || splits > MAX_SPLITS || shape < -1 || shape > NSHAPES) return QG_ERR_SHAPE;
     g_tune_splits = splits;
     g_tune_shape = shape;
     return QG_OK;
@@ -409,6 +411,14 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     if (!qg_aligned16(workspace)) return QG_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
 
+    // Up to 16 rows: the barrier-free kernel on the GEMV's launch structure, where it applies.
+    // It has one workgroup per tile and no split of K over workgroups, so it needs enough tiles
+    // to cover the chip (measured: ahead from about 128 tiles; shape -1 forces it).
+    if (M <= 16 && (g_tune_shape == 0 ? L.tiles >= 128 : g_tune_shape < 0)) {
+        const int r = qg_gemm_rows16(packed, N, K, bits, group, X, M, Y, workspace, stream);
+        if (r != QG_ERR_UNSUPPORTED) return r;
+    }
+
     if (!fast_path(L)) {
         // fp32 GEMV per activation row (rows of X stay 64-byte aligned only if K % 16 == 0)
         if (K % 16 != 0 && M > 1) return QG_ERR_UNSUPPORTED;
@@ -425,7 +435,7 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     // the price of dequantizing twice, which pays as long as the launch cannot fill the chip),
     // four tiles x two k-slices.  Eight wavefronts per workgroup: one workgroup per compute unit.
     int shape = M <= 32 ? 1 : 5;
-    if (g_tune_shape && (SHAPES[g_tune_shape - 1].mb == 1) == (M <= 32)) shape = g_tune_shape - 1;
+    if (g_tune_shape > 0 && (SHAPES[g_tune_shape - 1].mb == 1) == (M <= 32)) shape = g_tune_shape - 1;
     const int rows_per_block = SHAPES[shape].mb * 32;
     const int zblocks = (M + rows_per_block - 1) / rows_per_block;
     const int kw = SHAPES[shape].kw, tn = SHAPES[shape].tn;

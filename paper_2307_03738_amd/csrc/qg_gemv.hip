@@ -51,6 +51,7 @@ struct GemvProblem {
     int block_begin;       // first block of this problem in the grid
     int pair_tiles;        // > 0: outputs [0, 64 pair_tiles) gate outputs [64 pair_tiles, ...), see emit_output
     float *h;              // gated result (pair_tiles > 0)
+    int rows;              // gemm_rows16 only: activation rows M (x is X [M][K], y is Y [M][N])
 };
 
 #define QG_SLOT_EMPTY 0xffffffffu
@@ -770,6 +771,195 @@ __global__ __launch_bounds__(512) void gemv_mma(const GemvArgs A)
 }
 
 // ---------------------------------------------------------------------------------------
+// Up to 16 activation rows at once (a few prompt tokens): Y = X What^T with the launch
+// structure of the GEMV -- one wavefront per 64 outputs and K range, no workgroup barrier in
+// the loop, K split over the wavefronts of a team -- and the arithmetic of gemv_mma: 4-bit
+// codes become exact bf16 integers 128 + q, the matrix instruction multiplies them with the
+// rows of X (rounded to bf16; rows 16-31 of the A operand are zero), and per group
+//     Y[m][n] += s_n (T[m][n] - (128 + z_n) xhat[m]),   xhat[m] = sum_k bf16(X[m][k]),
+// where xhat comes out of one more matrix instruction per operand (X times a column of ones),
+// so it sits in the same registers as T.  Each wavefront converts the X rows of its own step
+// and keeps them in its own LDS region, one 16-byte operand piece per (row, cell).
+// ---------------------------------------------------------------------------------------
+template <int CPG>
+__global__ __launch_bounds__(512) void gemm_rows16(const GemvArgs A)
+{
+    using F = Fmt<4>;
+    constexpr int L = loads_per_step<4>();          // 4 code vectors per step
+    constexpr int S = codes_per_step<4>();          // 128 k per step
+    constexpr int CELLS = cells_per_step<4>();      // 16 cells of 8 codes
+    constexpr int GPS = CELLS / CPG;
+    constexpr int ZPER = 32 / F::ZBITS;
+    constexpr int ZW = GPS > ZPER ? GPS / ZPER : 1;
+    constexpr int PITCH = S + 8;                    // bf16 per LDS row: conflict-free 128-bit reads
+    constexpr int XL = 16 * CELLS / QG_WAVE;        // (row, cell) pieces per lane and step: 4
+    static_assert(CPG >= 2 && CPG % 2 == 0, "a group must hold whole pairs of cells");
+    // per wavefront: 16 rows of X for one step (reused at the end for the team's partial
+    // results); one row of zeros for rows 16-31 of the A operand
+    extern __shared__ __attribute__((aligned(16))) lds_u16 rows_raw[];
+    __shared__ __attribute__((aligned(16))) lds_u16 zero_row[PITCH];
+
+    const int pi = find_problem(A, blockIdx.x);
+    const GemvProblem P = A.p[pi];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.steps, wave);
+    if (!job.work) return;                      // no work: leave before the barrier
+    const int tile = job.tile, s0 = job.item0, s1 = job.item1;
+    const int M = P.rows;
+
+    const uint4 *codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
+    const float *scales = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
+    const uint32_t *zeros = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+    lds_u16 *xs = rows_raw + (size_t)wave * 16 * PITCH;
+
+#pragma unroll
+    for (int i = lane; i < PITCH; i += QG_WAVE) zero_row[i] = 0;
+
+    struct Regs {
+        uint4 v[L];
+        float s[GPS];
+        uint32_t zw[ZW];
+        float4 x[XL][2];       // pieces (row, cell) = (4 j + lane / 16, lane % 16): 8 consecutive k of X
+    };
+    // rows past M read row M - 1 again and are cleared on their way into LDS
+    const int xrow0 = lane >> 4, xcell = lane & 15;
+    auto fetch = [&](int step, Regs &r) {
+#pragma unroll
+        for (int i = 0; i < L; ++i) r.v[i] = codes[((size_t)step * L + i) * QG_WAVE];
+#pragma unroll
+        for (int g = 0; g < GPS; ++g) r.s[g] = scales[(size_t)(step * GPS + g) * QG_WAVE];
+#pragma unroll
+        for (int w = 0; w < ZW; ++w) r.zw[w] = zeros[(size_t)((step * GPS) / ZPER + w) * QG_WAVE];
+#pragma unroll
+        for (int j = 0; j < XL; ++j) {
+            int m = 4 * j + xrow0;
+            m = m < M ? m : M - 1;
+            const float4 *src = (const float4 *)(P.x + (size_t)m * P.K + (size_t)step * S + xcell * 8);
+            r.x[j][0] = src[0];
+            r.x[j][1] = src[1];
+        }
+    };
+    // X of one step into LDS: per piece the eight values in the order the unpacked codes have
+    // inside an operand (register j = codes j and j + 4)
+    auto stage = [&](const Regs &r) {
+#pragma unroll
+        for (int j = 0; j < XL; ++j) {
+            const int m = 4 * j + xrow0;
+            const float4 a = r.x[j][0], b = r.x[j][1];
+            const float keep = m < M ? 1.0f : 0.0f;
+            MmaOperand o;
+            mma_floatx2 t2;
+            t2[0] = a.x * keep; t2[1] = b.x * keep;
+            { const mma_bf16x2 h = __builtin_convertvector(t2, mma_bf16x2); o.r[0] = *(const uint32_t *)&h; }
+            t2[0] = a.y * keep; t2[1] = b.y * keep;
+            { const mma_bf16x2 h = __builtin_convertvector(t2, mma_bf16x2); o.r[1] = *(const uint32_t *)&h; }
+            t2[0] = a.z * keep; t2[1] = b.z * keep;
+            { const mma_bf16x2 h = __builtin_convertvector(t2, mma_bf16x2); o.r[2] = *(const uint32_t *)&h; }
+            t2[0] = a.w * keep; t2[1] = b.w * keep;
+            { const mma_bf16x2 h = __builtin_convertvector(t2, mma_bf16x2); o.r[3] = *(const uint32_t *)&h; }
+            *(lds_u128 *)(xs + m * PITCH + xcell * 8) = o.q;
+        }
+    };
+
+    // A operand: row = lane % 32 (rows 16-31 are zero), half = lane / 32 = which cell of the pair
+    const int row = lane & 31, half = lane >> 5;
+    const lds_u16 *abase = row < 16 ? xs + row * PITCH + half * 8 : zero_row + half * 8;
+    const MmaConst mc = mma_constants<4>();
+    MmaOperand ones;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) ones.r[j] = 0x3f803f80u;     // two bf16 1.0
+
+    // results of this wavefront: rows 8 (i / 4) + 4 half + i % 4 (i < 8) of outputs lane % 32 (P)
+    // and 32 + lane % 32 (Q) of the tile
+    float yp[8], yq[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { yp[i] = 0.0f; yq[i] = 0.0f; }
+
+    auto compute = [&](const Regs &r, int step) {
+        mma_floatx16 accP, accQ, accX;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accQ[i] = 0.0f; accX[i] = 0.0f; }
+#pragma unroll
+        for (int cp = 0; cp < CELLS / 2; ++cp) {
+            const int c0 = 2 * cp, u = c0 >> 2, j = c0 & 3;
+            const auto sw = __builtin_amdgcn_permlane32_swap(word_of(r.v[u], j), word_of(r.v[u], j + 1), false, false);
+            uint32_t wp[1] = {sw[0]}, wq[1] = {sw[1]};
+            MmaOperand bp[1], bq[1], a;
+            mma_unpack<4>(wp, mc, bp);
+            mma_unpack<4>(wq, mc, bq);
+            a.q = *(const lds_u128 *)(abase + cp * 16);
+            accP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bp[0].v, accP, 0, 0, 0);
+            accQ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bq[0].v, accQ, 0, 0, 0);
+            accX = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, ones.v, accX, 0, 0, 0);
+            if ((2 * cp + 2) % CPG == 0) {
+                const int gs = (2 * cp + 2) / CPG - 1;
+                const int gabs = step * GPS + gs;
+                const uint32_t zword = r.zw[ZW > 1 ? gs / ZPER : 0];
+                const float s = r.s[gs];
+                const float nzs = -(float)(((zword >> (F::ZBITS * (gabs % ZPER))) & ((1u << F::ZBITS) - 1u)) + 128u) * s;
+                // scale and zero term of the outputs this lane's accumulators belong to
+                const auto ss = __builtin_amdgcn_permlane32_swap(__float_as_uint(s), __float_as_uint(s), false, false);
+                const auto zz = __builtin_amdgcn_permlane32_swap(__float_as_uint(nzs), __float_as_uint(nzs), false, false);
+                const float sP = __uint_as_float(ss[0]), sQ = __uint_as_float(ss[1]);
+                const float zP = __uint_as_float(zz[0]), zQ = __uint_as_float(zz[1]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    yp[i] += fmaf(sP, accP[i], zP * accX[i]);
+                    yq[i] += fmaf(sQ, accQ[i], zQ * accX[i]);
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accQ[i] = 0.0f; accX[i] = 0.0f; }
+            }
+        }
+    };
+
+    // two register buffers used alternately; the rows of X of a step are converted into the
+    // wavefront's LDS region right before the step is computed
+    const int last = s1 - 1;
+    Regs ra, rb;
+    fetch(s0, ra);
+    for (int s = s0; s < s1; s += 2) {
+        const int sb = s + 1 < last ? s + 1 : last;
+        const int sc = s + 2 < last ? s + 2 : last;
+        fetch(sb, rb);
+        stage(ra);
+        compute(ra, s);
+        if (s + 1 >= s1) break;                       // odd number of steps
+        fetch(sc, ra);
+        stage(rb);
+        compute(rb, sb);
+    }
+
+    // team reduction through LDS (each wavefront writes its own region first), then the lead
+    // adds the partial results in wavefront order and stores Y
+    float *mine = (float *)(rows_raw + (size_t)wave * 16 * PITCH);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        mine[i * QG_WAVE + lane] = yp[i];
+        mine[(8 + i) * QG_WAVE + lane] = yq[i];
+    }
+    __syncthreads();
+    if (wave != job.lead) return;
+    for (int w = 1; w < job.team; ++w) {
+        const float *other = (const float *)(rows_raw + (size_t)(job.lead + w) * 16 * PITCH);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            yp[i] += other[i * QG_WAVE + lane];
+            yq[i] += other[(8 + i) * QG_WAVE + lane];
+        }
+    }
+    const int col = lane & 31;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int m = 8 * (i / 4) + 4 * half + (i % 4);
+        const int np = tile * QG_WAVE + col, nq = np + 32;
+        if (m < M && np < P.N) P.y[(size_t)m * P.N + np] = yp[i];
+        if (m < M && nq < P.N) P.y[(size_t)m * P.N + nq] = yq[i];
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Groups that are a whole number of steps (G = 256, ..., up to one group per output: the
 // full-column case of eq. (1)).  A wavefront's range of steps need not begin or end at a group
 // boundary: s (sum q x - z sum x) is linear in the two sums, so the pieces of a group that
@@ -1008,8 +1198,18 @@ bool use_mma(int bits, int cpg)
 }
 
 // One launch for problems that share (bits, group, kernel kind).
+template <int CPG>
+void launch_rows16(unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+{
+    const size_t lds = (size_t)(threads / QG_WAVE) * 16 * (codes_per_step<4>() + 8) * sizeof(uint16_t);
+    hipLaunchKernelGGL((gemm_rows16<CPG>), dim3(blocks), dim3(threads), lds, st, A);
+}
+
+// rows > 0: the problems are products with `rows` <= 16 activation rows (x = X [rows][K],
+// y = Y [rows][N]) for gemm_rows16; the caller has checked that the kernel applies.
 int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const size_t *ws_off,
-                 char *workspace, hipStream_t st, const int64_t *gate_rows, float *const *gated)
+                 char *workspace, hipStream_t st, const int64_t *gate_rows, float *const *gated,
+                 int rows = 0)
 {
     GemvArgs A;
     A.count = count;
@@ -1032,8 +1232,9 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     // `target` per wavefront so that the chip is still covered.
     // wavefronts per team, at most (measured: 12 is best for the 4-bit kernels, 8 for the
     // 2- and 3-bit ones, which hold more registers per wavefront)
-    const bool mma = kind == KIND_STATIC && use_mma(L[0].bits, L[0].group / L[0].cell);
+    const bool mma = rows == 0 && kind == KIND_STATIC && use_mma(L[0].bits, L[0].group / L[0].cell);
     int cap = g_tune_wpb > 0 ? g_tune_wpb : (L[0].bits == 4 ? 12 : 8);
+    if (rows > 0 && cap > 8) cap = 8;          // gemm_rows16 is built for at most 8 wavefronts
     if (mma) {                                 // the matrix-core kernel is built for at most 8 wavefronts;
         if (cap > 8) cap = 8;                  // measured: teams of 4 are best for it
         if (g_tune_wpb == 0) cap = 4;
@@ -1059,7 +1260,8 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         // on a tie the fewest workgroups, then the smallest team.
         bool found = false;
         int64_t best_miss = 0;
-        for (int64_t chunks = 1; chunks <= QG_MAX_CHUNKS; chunks *= 2) {
+        // (the many-row kernel has no reduction across workgroups)
+        for (int64_t chunks = 1; chunks <= (rows > 0 ? 1 : QG_MAX_CHUNKS); chunks *= 2) {
             for (int64_t team = 1; team <= cap; ++team) {
                 const int64_t spw = (q.items + chunks * team - 1) / (chunks * team);
                 if (spw > q.max_spw) continue;
@@ -1108,6 +1310,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         P.tiles_per_block = P.chunks > 1 ? 1 : wpb / P.waves_per_tile;
         P.pair_tiles = gate_rows ? (int)(gate_rows[idx[i]] / QG_WAVE) : 0;
         P.h = gated ? gated[idx[i]] : nullptr;
+        P.rows = rows;
         P.block_begin = blocks;
         A.block_begin[i] = blocks;
         const int64_t nb = P.chunks > 1 ? (int64_t)P.tiles * P.chunks
@@ -1118,7 +1321,14 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
 
     const unsigned threads = (unsigned)wpb * QG_WAVE;
     const int bits = L[0].bits;
-    if (kind == KIND_STATIC) {
+    if (rows > 0) {
+        switch (L[0].group / L[0].cell) {
+        case 2: launch_rows16<2>(blocks, threads, st, A); break;
+        case 4: launch_rows16<4>(blocks, threads, st, A); break;
+        case 8: launch_rows16<8>(blocks, threads, st, A); break;
+        default: launch_rows16<16>(blocks, threads, st, A); break;
+        }
+    } else if (kind == KIND_STATIC) {
         const int cpg = L[0].group / L[0].cell;
         if (mma) {
             if (bits == 4) launch_mma<4>(cpg, blocks, threads, st, A);
@@ -1230,6 +1440,31 @@ extern "C" int qg_gemv_grouped(const qg_gemv_desc *descs, int count, void *works
                                size_t workspace_bytes, void *stream)
 {
     return gemv_grouped(descs, count, workspace, workspace_bytes, stream, nullptr, nullptr);
+}
+
+// Y = X What^T for M <= 16 rows on the GEMV's launch structure (used by qg_gemm_small).
+// Returns QG_ERR_UNSUPPORTED if the shape is not one gemm_rows16 takes; the arguments have
+// been checked by the caller.
+int qg_gemm_rows16(const void *packed, int64_t N, int64_t K, int bits, int group, const float *X,
+                   int M, float *Y, void *workspace, void *stream)
+{
+    QgLayout L;
+    if (qg_make_layout(N, K, bits, group, &L) != QG_OK) return QG_ERR_UNSUPPORTED;
+    const Plan pl = make_plan(L);
+    const int cpg = group / L.cell;
+    if (bits != 4 || M < 1 || M > 16 || pl.kind != KIND_STATIC || cpg < 2) return QG_ERR_UNSUPPORTED;
+    if ((int64_t)M * K >= ((int64_t)1 << 31)) return QG_ERR_UNSUPPORTED;
+    qg_gemv_desc d;
+    d.packed = packed;
+    d.N = N;
+    d.K = K;
+    d.bits = bits;
+    d.group = group;
+    d.x = X;
+    d.y = Y;
+    const int idx = 0;
+    const size_t ws_off = 0;
+    return launch_class(&d, &idx, 1, &ws_off, (char *)workspace, (hipStream_t)stream, nullptr, nullptr, M);
 }
 
 extern "C" int qg_gemv_swiglu(const void *packed, int64_t I, int64_t K, int bits, int group,

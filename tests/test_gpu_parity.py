@@ -397,6 +397,25 @@ def test_gemm_small_matches_oracle(qg, oracle, N, K, bits, group, M):
     assert err <= TOL_BF16, err
 
 
+@pytest.mark.parametrize("tuning", [(0, 0, 0), (1, 4096, 0), (3, 8192, 0), (8, 65536, 0)])
+@pytest.mark.parametrize("N,K,group,M", [(200, 1024, 128, 16), (130, 512, 16, 7), (70, 1408, 32, 1), (300, 2304, 64, 13),
+                                         (64, 11008, 128, 16), (1000, 128, 128, 9)])
+def test_gemm_small_up_to_16_rows(qg, oracle, N, K, group, M, tuning):
+    # the barrier-free kernel for a few rows: every group size it takes, ragged N and M, one
+    # step, long K over a team of wavefronts, different team sizes
+    _announce("gemm rows16", N, K, group, M, tuning)
+    W, X = synth.small_case(3000 + N + M, N, K, 0.02, True, m=max(M, 2))
+    X = X[:M]
+    qg.qg_set_gemv_tuning(*tuning)
+    qg.qg_set_gemm_tuning(0, -1)                 # this kernel whatever the number of tiles
+    try:
+        err = _gemm_case(qg, oracle, W, X, 4, group)
+    finally:
+        qg.qg_set_gemv_tuning(0, 0, 0)
+        qg.qg_set_gemm_tuning(0, 0)
+    assert err <= TOL_BF16, err
+
+
 def test_gemm_small_longest_k_of_the_matrix_core_path(qg, oracle):
     _announce("gemm_small K = 2^20")
     N, K, bits, group, M = 70, 1 << 20, 4, 128, 9
@@ -420,7 +439,7 @@ def test_gemm_small_rows_agree_with_gemv(qg, oracle):
 
 
 @pytest.mark.parametrize("splits", [1, 2, 3, 8])
-@pytest.mark.parametrize("M", [8, 48, 96])
+@pytest.mark.parametrize("M", [24, 48, 96])
 def test_gemm_small_every_split_count(qg, oracle, splits, M):
     _announce("gemm_small splits", splits, M)
     N, K, bits, group = 200, 2304, 4, 128          # 18 steps
