@@ -66,20 +66,22 @@ union Operand {
     bf16x2 p[4];
 };
 
-// Eight 4-bit codes of one word -> eight bf16 values s*(q - z), in code order.
+// Eight 4-bit codes of one word -> eight bf16 values s*(q - z), in code order.  The odd codes
+// are taken with one mask, sixteen times too large, and multiplied by s / 16 (exact).
 __device__ inline bf16x8 dequant_word(uint32_t w, float s, float nzs)
 {
     const uint32_t lo = opaque(w & 0x0f0f0f0fu);          // codes 0, 2, 4, 6
-    const uint32_t hi = opaque((w >> 4) & 0x0f0f0f0fu);   // codes 1, 3, 5, 7
+    const uint32_t hi = opaque(w & 0xf0f0f0f0u);          // codes 1, 3, 5, 7, times 16
+    const float sh = s * 0.0625f;
     Operand o;
     floatx2 t;
-    t[0] = fmaf((float)(lo & 0xffu), s, nzs);          t[1] = fmaf((float)(hi & 0xffu), s, nzs);
+    t[0] = fmaf((float)(lo & 0xffu), s, nzs);          t[1] = fmaf((float)(hi & 0xffu), sh, nzs);
     o.p[0] = __builtin_convertvector(t, bf16x2);
-    t[0] = fmaf((float)((lo >> 8) & 0xffu), s, nzs);   t[1] = fmaf((float)((hi >> 8) & 0xffu), s, nzs);
+    t[0] = fmaf((float)((lo >> 8) & 0xffu), s, nzs);   t[1] = fmaf((float)((hi >> 8) & 0xffu), sh, nzs);
     o.p[1] = __builtin_convertvector(t, bf16x2);
-    t[0] = fmaf((float)((lo >> 16) & 0xffu), s, nzs);  t[1] = fmaf((float)((hi >> 16) & 0xffu), s, nzs);
+    t[0] = fmaf((float)((lo >> 16) & 0xffu), s, nzs);  t[1] = fmaf((float)((hi >> 16) & 0xffu), sh, nzs);
     o.p[2] = __builtin_convertvector(t, bf16x2);
-    t[0] = fmaf((float)(lo >> 24), s, nzs);            t[1] = fmaf((float)(hi >> 24), s, nzs);
+    t[0] = fmaf((float)(lo >> 24), s, nzs);            t[1] = fmaf((float)(hi >> 24), sh, nzs);
     o.p[3] = __builtin_convertvector(t, bf16x2);
     return o.v;
 }

@@ -123,10 +123,18 @@ __device__ inline XBatch load_x32(const float *__restrict__ p)
 //         A, B, C and the word T gathered from the spare bits.
 // Two independent accumulation chains per wavefront: a single dependent chain of FMAs can only
 // issue every ~5 cycles, two chains keep the SIMD busy with fewer resident wavefronts.  The
-// two halves are added once per group.
+// two halves are added once per group.  The second chain takes the upper field of every byte
+// WITHOUT shifting it down (one mask instead of shift and mask): its codes count 2^BITS times
+// too much, which acc_total undoes -- powers of two, so every bit of the result is the same.
 struct Acc2 {
     float a, b;
 };
+
+template <int BITS>
+__device__ inline float acc_total(const Acc2 &acc)
+{
+    return fmaf(acc.b, 1.0f / (float)(1 << BITS), acc.a);
+}
 
 template <int BITS>
 __device__ inline void octet_dot(const uint4 *v, int bt, int o, const XBatch &xb, Acc2 &acc)
@@ -135,7 +143,7 @@ __device__ inline void octet_dot(const uint4 *v, int bt, int o, const XBatch &xb
         const int cell = bt * 4 + o;
         const uint32_t w = word_of(v[cell >> 2], cell & 3);
         const uint32_t lo = opaque(w & 0x0f0f0f0fu);          // even codes
-        const uint32_t hi = opaque((w >> 4) & 0x0f0f0f0fu);   // odd codes
+        const uint32_t hi = opaque(w & 0xf0f0f0f0u);          // odd codes, times 16
         const int x0 = 8 * o;
         acc.a = fmaf(QG_B0(lo), xb[x0 + 0], acc.a);  acc.b = fmaf(QG_B0(hi), xb[x0 + 1], acc.b);
         acc.a = fmaf(QG_B1(lo), xb[x0 + 2], acc.a);  acc.b = fmaf(QG_B1(hi), xb[x0 + 3], acc.b);
@@ -147,7 +155,7 @@ __device__ inline void octet_dot(const uint4 *v, int bt, int o, const XBatch &xb
         const int x0 = 16 * (o >> 1);
         const int f = 2 * (o & 1);
         const uint32_t m0 = opaque((w >> (2 * f)) & 0x03030303u);
-        const uint32_t m1 = opaque((w >> (2 * f + 2)) & 0x03030303u);
+        const uint32_t m1 = opaque((w >> (2 * f)) & 0x0c0c0c0cu);      // the next field set, times 4
         acc.a = fmaf(QG_B0(m0), xb[x0 + f], acc.a);       acc.b = fmaf(QG_B0(m1), xb[x0 + f + 1], acc.b);
         acc.a = fmaf(QG_B1(m0), xb[x0 + 4 + f], acc.a);   acc.b = fmaf(QG_B1(m1), xb[x0 + 4 + f + 1], acc.b);
         acc.a = fmaf(QG_B2(m0), xb[x0 + 8 + f], acc.a);   acc.b = fmaf(QG_B2(m1), xb[x0 + 8 + f + 1], acc.b);
@@ -165,7 +173,7 @@ __device__ inline void octet_dot(const uint4 *v, int bt, int o, const XBatch &xb
             src = ((a >> 6) & 0x03030303u) | ((b >> 4) & 0x0c0c0c0cu) | ((c >> 2) & 0x30303030u);
         }
         const uint32_t m0 = opaque(src & 0x07070707u);
-        const uint32_t m1 = opaque((src >> 3) & 0x07070707u);
+        const uint32_t m1 = opaque(src & 0x38383838u);                 // the upper codes, times 8
         const int x0 = 8 * o;
         acc.a = fmaf(QG_B0(m0), xb[x0 + 0], acc.a);  acc.b = fmaf(QG_B0(m1), xb[x0 + 4], acc.b);
         acc.a = fmaf(QG_B1(m0), xb[x0 + 1], acc.a);  acc.b = fmaf(QG_B1(m1), xb[x0 + 5], acc.b);
@@ -448,7 +456,7 @@ __device__ inline void compute_step(const StepData<BITS, GPS> &d, const float *_
                     const uint32_t zword = d.zw[D::ZW > 1 ? gs / D::ZPER : 0];
                     const float zf = (float)((zword >> (F::ZBITS * (gabs % D::ZPER))) & ((1u << F::ZBITS) - 1u));
                     // a step past the end of the wavefront's range counts with scale 0
-                    yacc = fmaf(valid ? d.s[gs] : 0.0f, fmaf(-zf, xhat[gs], acc.a + acc.b), yacc);
+                    yacc = fmaf(valid ? d.s[gs] : 0.0f, fmaf(-zf, xhat[gs], acc_total<BITS>(acc)), yacc);
                     acc.a = 0.0f;
                     acc.b = 0.0f;
                 }
@@ -1003,7 +1011,7 @@ __global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
         const float scale = T.scales[(size_t)g * QG_WAVE];
         const uint32_t zword = T.zeros[(size_t)(g / ZPER) * QG_WAVE];
         const float zf = (float)((zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u));
-        yacc = fmaf(scale, fmaf(-zf, xhat, acc.a + acc.b), yacc);
+        yacc = fmaf(scale, fmaf(-zf, xhat, acc_total<BITS>(acc)), yacc);
         acc.a = 0.0f;
         acc.b = 0.0f;
         xacc = 0.0f;
@@ -1085,7 +1093,7 @@ __global__ __launch_bounds__(1024) void gemv_generic(const GemvArgs A)
         }
         const uint32_t zword = zr[(size_t)(g / ZPER) * QG_WAVE];
         const float zf = (float)((zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u));
-        yacc = fmaf(sc[(size_t)g * QG_WAVE], fmaf(-zf, sx, acc.a + acc.b), yacc);
+        yacc = fmaf(sc[(size_t)g * QG_WAVE], fmaf(-zf, sx, acc_total<BITS>(acc)), yacc);
     }
     finish_tile(P, job, yacc, red);
 }
