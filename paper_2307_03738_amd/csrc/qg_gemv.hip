@@ -830,7 +830,8 @@ __global__ __launch_bounds__(512) void gemm_rows16(const GemvArgs A)
         uint32_t zw[ZW];
         float4 x[XL][2];       // pieces (row, cell) = (4 j + lane / 16, lane % 16): 8 consecutive k of X
     };
-    // rows past M read row M - 1 again and are cleared on their way into LDS
+    // groups of four rows with no real row are not loaded; other rows past M read row M - 1
+    // again; both are cleared on their way into LDS
     const int xrow0 = lane >> 4, xcell = lane & 15;
     auto fetch = [&](int step, Regs &r) {
 #pragma unroll
@@ -841,6 +842,7 @@ __global__ __launch_bounds__(512) void gemm_rows16(const GemvArgs A)
         for (int w = 0; w < ZW; ++w) r.zw[w] = zeros[(size_t)((step * GPS) / ZPER + w) * QG_WAVE];
 #pragma unroll
         for (int j = 0; j < XL; ++j) {
+            if (4 * j >= M) continue;                    // uniform
             int m = 4 * j + xrow0;
             m = m < M ? m : M - 1;
             const float4 *src = (const float4 *)(P.x + (size_t)m * P.K + (size_t)step * S + xcell * 8);
@@ -854,9 +856,14 @@ __global__ __launch_bounds__(512) void gemm_rows16(const GemvArgs A)
 #pragma unroll
         for (int j = 0; j < XL; ++j) {
             const int m = 4 * j + xrow0;
+            MmaOperand o;
+            if (4 * j >= M) {                            // uniform: nothing was loaded
+                o.q = make_uint4(0u, 0u, 0u, 0u);
+                *(lds_u128 *)(xs + m * PITCH + xcell * 8) = o.q;
+                continue;
+            }
             const float4 a = r.x[j][0], b = r.x[j][1];
             const float keep = m < M ? 1.0f : 0.0f;
-            MmaOperand o;
             mma_floatx2 t2;
             t2[0] = a.x * keep; t2[1] = b.x * keep;
             { const mma_bf16x2 h = __builtin_convertvector(t2, mma_bf16x2); o.r[0] = *(const uint32_t *)&h; }
