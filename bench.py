@@ -194,6 +194,61 @@ def bench_sweep(qg, args):
             "rows": rows}
 
 
+def bench_offline(qg, args):
+    """The off-line steps (quantize, pack, unpack) on the largest matrix of each layer set.
+    Each is a streaming pass; its bytes are what the step has to read and write once."""
+    L = qg.lib()
+    stream = torch.cuda.current_stream().cuda_stream
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(3, args.steps // 100)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        start.record()
+        for _ in range(reps):
+            fn()
+        stop.record()
+        torch.cuda.synchronize()
+        return start.elapsed_time(stop) / reps * 1e3
+
+    rows = []
+    for bits, group, N, K in ((4, 128, 11008, 4096), (3, 64, 13824, 5120), (2, 32, 22016, 8192)):
+        gen = torch.Generator(device="cuda").manual_seed(bits)
+        W = torch.randn((N, K), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+        q, s, z = qg.qg_quantize(W, bits, group)
+        G = K // group
+        row = {"N": N, "K": K, "bits": bits, "group": group}
+
+        def check(rc):
+            if rc != 0:
+                raise RuntimeError(f"library call failed with status {rc}")
+        us = timed(lambda: check(L.qg_quantize(W.data_ptr(), N, K, bits, group, q.data_ptr(), s.data_ptr(),
+                                               z.data_ptr(), stream)))
+        nbytes = 4 * N * K + N * K + 5 * N * G
+        row["quantize_us"], row["quantize_GBps"] = round(us, 1), round(nbytes / us / 1e3, 1)
+        for name, layout in (("device", qg.QG_LAYOUT_DEVICE), ("canonical", qg.QG_LAYOUT_CANONICAL)):
+            pb = qg.qg_packed_bytes(N, K, bits, group, layout)
+            blob = torch.empty(pb, dtype=torch.uint8, device="cuda")
+            us = timed(lambda: check(L.qg_pack(q.data_ptr(), s.data_ptr(), z.data_ptr(), N, K, bits, group,
+                                               layout, blob.data_ptr(), stream)))
+            nbytes = N * K + 5 * N * G + pb
+            row[f"pack_{name}_us"], row[f"pack_{name}_GBps"] = round(us, 1), round(nbytes / us / 1e3, 1)
+            q2, s2, z2 = torch.empty_like(q), torch.empty_like(s), torch.empty_like(z)
+            us = timed(lambda: check(L.qg_unpack(blob.data_ptr(), N, K, bits, group, layout, q2.data_ptr(),
+                                                 s2.data_ptr(), z2.data_ptr(), stream)))
+            row[f"unpack_{name}_us"], row[f"unpack_{name}_GBps"] = round(us, 1), round(nbytes / us / 1e3, 1)
+            if not (torch.equal(q, q2) and torch.equal(s, s2) and torch.equal(z, z2)):
+                raise RuntimeError("pack / unpack round trip changed the data")
+            del blob, q2, s2, z2
+        rows.append(row)
+        del W, q, s, z
+    return {"metric": "us per off-line step (quantize, pack, unpack) on the largest matrix of each layer set",
+            "unit": "us", "n_gpus": 1, "data": "synthetic", "repeats": reps, "hbm_peak_GBps": HBM_PEAK_GBS,
+            "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -207,6 +262,8 @@ def main():
                     help="group sizes of --sweep; 0 = one group per output")
     ap.add_argument("--sweep", action="store_true",
                     help="time every group size x bit width on the three layer-set shapes instead")
+    ap.add_argument("--offline", action="store_true",
+                    help="time the off-line steps (quantize, pack, unpack) instead")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of 256 MiB (reference for HBM byte counters)")
     ap.add_argument("--wpb", type=int, default=0)
@@ -223,6 +280,9 @@ def main():
     cfg = synth.CONFIGS[args.config]
     if args.sweep:
         print(json.dumps(bench_sweep(qg, args)))
+        return
+    if args.offline:
+        print(json.dumps(bench_offline(qg, args)))
         return
     if args.config == "C5":
         print(json.dumps(bench_gemm(cfg, qg, args)))

@@ -5,193 +5,497 @@
 
 namespace {
 
-// ------------------------------------------------------------------ canonical layout
+// Every kernel here moves a block of 64 rows (outputs) x SPAN columns of a row-major matrix
+// through LDS, so that the row-major side is read or written in 16-byte pieces, 16 or more
+// consecutive lanes on one row, and the packed side with lane = output, 64 lanes on
+// consecutive words.  A workgroup is 256 threads = 4 wavefronts.  Rows of the LDS image are
+// PITCH = SPAN + 16 bytes apart: with lane = row, 128-bit LDS accesses then fall on distinct
+// banks.
+constexpr int PK_THREADS = 256;
 
-// Word w of the bit stream of output n: bits [32w, 32w+32) of sum_k v[n][k] << (b k).
-__global__ void canon_pack_stream(const uint8_t *__restrict__ v, int64_t N, int64_t count,
-                                  int bits, int64_t words, uint32_t *__restrict__ P)
+// rows [r0, r0+64) x columns [c0, c0+SPAN) of v [rows][cols] -> lds; zeros outside the matrix.
+// `wide`: cols % 16 == 0 and v 16-byte aligned, so the block is moved in 16-byte pieces.
+template <int SPAN>
+__device__ inline void rows_to_lds(const uint8_t *__restrict__ v, int64_t rows, int64_t cols,
+                                   int64_t r0, int64_t c0, bool wide, uint8_t *lds)
 {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= words * N) return;
-    const int64_t w = idx / N, n = idx % N;
-    const int64_t first = (32 * w) / bits;
-    const int64_t last = (32 * w + 31) / bits;
-    uint32_t word = 0;
-    for (int64_t k = first; k <= last && k < count; ++k) {
-        const uint32_t c = v[n * count + k];
-        const int pos = (int)(bits * k - 32 * w);
-        word |= pos >= 0 ? c << pos : c >> (-pos);
+    constexpr int PITCH = SPAN + 16;
+    if (wide) {
+        constexpr int PIECES = SPAN / 16;
+        for (int i = threadIdx.x; i < QG_WAVE * PIECES; i += PK_THREADS) {
+            const int r = i / PIECES, p = i % PIECES;
+            const int64_t n = r0 + r, c = c0 + 16 * p;
+            uint4 val = make_uint4(0u, 0u, 0u, 0u);
+            if (n < rows && c < cols) val = *(const uint4 *)(v + n * cols + c);
+            *(uint4 *)(lds + r * PITCH + 16 * p) = val;
+        }
+    } else {
+        for (int i = threadIdx.x; i < QG_WAVE * SPAN; i += PK_THREADS) {
+            const int r = i / SPAN, b = i % SPAN;
+            const int64_t n = r0 + r, c = c0 + b;
+            lds[r * PITCH + b] = (n < rows && c < cols) ? v[n * cols + c] : (uint8_t)0;
+        }
     }
-    P[idx] = word;
 }
 
-__global__ void canon_unpack_stream(const uint32_t *__restrict__ P, int64_t N, int64_t count,
-                                    int bits, uint8_t *__restrict__ v)
+// the inverse: the part of the block that lies inside the matrix is written
+template <int SPAN>
+__device__ inline void lds_to_rows(uint8_t *__restrict__ v, int64_t rows, int64_t cols,
+                                   int64_t r0, int64_t c0, bool wide, const uint8_t *lds)
 {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= N * count) return;
-    const int64_t n = idx / count, k = idx % count;
-    const int64_t bit = bits * k;
-    const int64_t w = bit / 32;
-    const int off = (int)(bit % 32);
-    uint32_t c = P[w * N + n] >> off;
-    if (off + bits > 32) c |= P[(w + 1) * N + n] << (32 - off);   // field straddles two words
-    v[idx] = (uint8_t)(c & ((1u << bits) - 1u));
+    constexpr int PITCH = SPAN + 16;
+    if (wide) {
+        constexpr int PIECES = SPAN / 16;
+        for (int i = threadIdx.x; i < QG_WAVE * PIECES; i += PK_THREADS) {
+            const int r = i / PIECES, p = i % PIECES;
+            const int64_t n = r0 + r, c = c0 + 16 * p;
+            if (n < rows && c < cols) *(uint4 *)(v + n * cols + c) = *(const uint4 *)(lds + r * PITCH + 16 * p);
+        }
+    } else {
+        for (int i = threadIdx.x; i < QG_WAVE * SPAN; i += PK_THREADS) {
+            const int r = i / SPAN, b = i % SPAN;
+            const int64_t n = r0 + r, c = c0 + b;
+            if (n < rows && c < cols) v[n * cols + c] = lds[r * PITCH + b];
+        }
+    }
 }
 
-// s [N][G] <-> St [G][N]
-__global__ void transpose_f32(const float *__restrict__ in, int64_t rows, int64_t cols,
-                              float *__restrict__ out)
+// Four codes, one per byte of d, <-> their fields side by side in the low bits.
+__device__ inline uint32_t squeeze4(uint32_t d)          // -> 16 bits
 {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= rows * cols) return;
-    const int64_t c = idx / rows, r = idx % rows;   // out [cols][rows], r contiguous
-    out[idx] = in[r * cols + c];
+    const uint32_t t = (d | (d >> 4)) & 0x00ff00ffu;
+    return (t | (t >> 8)) & 0xffffu;
+}
+__device__ inline uint32_t squeeze2(uint32_t d)          // -> 8 bits
+{
+    const uint32_t t = (d | (d >> 6)) & 0x000f000fu;
+    return (t | (t >> 12)) & 0xffu;
+}
+__device__ inline uint32_t squeeze3(uint32_t d)          // -> 12 bits
+{
+    const uint32_t t = (d | (d >> 5)) & 0x003f003fu;
+    return (t | (t >> 10)) & 0xfffu;
+}
+__device__ inline uint32_t spread4(uint32_t u)
+{
+    const uint32_t t = (u | (u << 8)) & 0x00ff00ffu;
+    return (t | (t << 4)) & 0x0f0f0f0fu;
+}
+__device__ inline uint32_t spread2(uint32_t u)
+{
+    const uint32_t t = (u | (u << 12)) & 0x000f000fu;
+    return (t | (t << 6)) & 0x03030303u;
+}
+__device__ inline uint32_t spread3(uint32_t u)
+{
+    const uint32_t t = (u | (u << 10)) & 0x003f003fu;
+    return (t | (t << 5)) & 0x07070707u;
 }
 
-// ------------------------------------------------------------------ device layout
+// Words of the little-endian bit stream of FB-bit fields (Section 3 "Data format";
+// Algorithm 2 for 4 bits) built from / cut back into codes held one per byte, four to a
+// dword.  A "run" is the shortest piece of the stream that ends on a word boundary:
+// 8 codes = 1 word at 4 bits, 16 codes = 1 word at 2 bits, 32 codes = 3 words at 3 bits.
+template <int FB> struct Run;
+template <> struct Run<4> {
+    static constexpr int CODES = 8, WORDS = 1;
+    static __device__ inline void pack(const uint32_t *d, uint32_t *w) { w[0] = squeeze4(d[0]) | (squeeze4(d[1]) << 16); }
+    static __device__ inline void unpack(const uint32_t *w, uint32_t *d)
+    {
+        d[0] = spread4(w[0] & 0xffffu);
+        d[1] = spread4(w[0] >> 16);
+    }
+};
+template <> struct Run<2> {
+    static constexpr int CODES = 16, WORDS = 1;
+    static __device__ inline void pack(const uint32_t *d, uint32_t *w)
+    {
+        w[0] = squeeze2(d[0]) | (squeeze2(d[1]) << 8) | (squeeze2(d[2]) << 16) | (squeeze2(d[3]) << 24);
+    }
+    static __device__ inline void unpack(const uint32_t *w, uint32_t *d)
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) d[i] = spread2((w[0] >> (8 * i)) & 0xffu);
+    }
+};
+template <> struct Run<3> {
+    static constexpr int CODES = 32, WORDS = 3;
+    static __device__ inline void pack(const uint32_t *d, uint32_t *w)
+    {
+        uint32_t p[8];                                   // 12 bits each
+#pragma unroll
+        for (int i = 0; i < 8; ++i) p[i] = squeeze3(d[i]);
+        w[0] = p[0] | (p[1] << 12) | (p[2] << 24);
+        w[1] = (p[2] >> 8) | (p[3] << 4) | (p[4] << 16) | (p[5] << 28);
+        w[2] = (p[5] >> 4) | (p[6] << 8) | (p[7] << 20);
+    }
+    static __device__ inline void unpack(const uint32_t *w, uint32_t *d)
+    {
+        d[0] = spread3(w[0] & 0xfffu);
+        d[1] = spread3((w[0] >> 12) & 0xfffu);
+        d[2] = spread3(((w[0] >> 24) | (w[1] << 8)) & 0xfffu);
+        d[3] = spread3((w[1] >> 4) & 0xfffu);
+        d[4] = spread3((w[1] >> 16) & 0xfffu);
+        d[5] = spread3(((w[1] >> 28) | (w[2] << 4)) & 0xfffu);
+        d[6] = spread3((w[2] >> 8) & 0xfffu);
+        d[7] = spread3(w[2] >> 20);
+    }
+};
 
-__device__ inline uint32_t byte_of(uint32_t w, int i) { return (w >> (8 * i)) & 0xffu; }
+// columns of the row-major side that one workgroup handles
+template <int FB> constexpr int span_of() { return FB == 3 ? 512 : 256; }
 
-// One thread builds the `planes` uint4 of one (tile, unit, lane).
+// ------------------------------------------------------------------ bit-stream words
+//
+// v [N][cols], one FB-bit value per byte  <->  words of the bit stream of each row, stored
+//   canonical:  P [word][n]                  (TILED = false)
+//   per tile:   P [tile][word][lane]         (TILED = true; lanes past N hold zero words)
+// `words` = words per row.  Each wavefront of the workgroup takes a quarter of the block's runs.
+template <int FB, bool TILED>
+__global__ __launch_bounds__(PK_THREADS) void stream_pack(const uint8_t *__restrict__ v, int64_t N,
+                                                          int64_t cols, int64_t words, int spans,
+                                                          bool wide, uint32_t *__restrict__ P)
+{
+    using R = Run<FB>;
+    constexpr int SPAN = span_of<FB>(), PITCH = SPAN + 16;
+    constexpr int RUNS = SPAN / R::CODES / 4;            // per wavefront
+    __shared__ __align__(16) uint8_t lds[QG_WAVE * PITCH];
+    const int64_t tile = blockIdx.x / spans;
+    const int span = blockIdx.x % spans;
+    rows_to_lds<SPAN>(v, N, cols, tile * QG_WAVE, (int64_t)span * SPAN, wide, lds);
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t n = tile * QG_WAVE + lane;
+    if (!TILED && n >= N) return;
+#pragma unroll
+    for (int r = 0; r < RUNS; ++r) {
+        const int run = wave * RUNS + r;                 // within the block
+        uint32_t d[R::CODES / 4], w[R::WORDS];
+        const uint4 *src = (const uint4 *)(lds + lane * PITCH + run * R::CODES);
+        if constexpr (R::CODES == 8) {
+            const uint2 a = *(const uint2 *)src;
+            d[0] = a.x; d[1] = a.y;
+        } else {
+#pragma unroll
+            for (int i = 0; i < R::CODES / 16; ++i) {
+                const uint4 a = src[i];
+                d[4 * i] = a.x; d[4 * i + 1] = a.y; d[4 * i + 2] = a.z; d[4 * i + 3] = a.w;
+            }
+        }
+        R::pack(d, w);
+#pragma unroll
+        for (int j = 0; j < R::WORDS; ++j) {
+            const int64_t word = ((int64_t)span * (SPAN / R::CODES) + run) * R::WORDS + j;
+            if (word < words) P[TILED ? (tile * words + word) * QG_WAVE + lane : word * N + n] = w[j];
+        }
+    }
+}
+
+template <int FB, bool TILED>
+__global__ __launch_bounds__(PK_THREADS) void stream_unpack(const uint32_t *__restrict__ P, int64_t N,
+                                                            int64_t cols, int64_t words, int spans,
+                                                            bool wide, uint8_t *__restrict__ v)
+{
+    using R = Run<FB>;
+    constexpr int SPAN = span_of<FB>(), PITCH = SPAN + 16;
+    constexpr int RUNS = SPAN / R::CODES / 4;
+    __shared__ __align__(16) uint8_t lds[QG_WAVE * PITCH];
+    const int64_t tile = blockIdx.x / spans;
+    const int span = blockIdx.x % spans;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t n = tile * QG_WAVE + lane;
+    if (TILED || n < N) {
+#pragma unroll
+        for (int r = 0; r < RUNS; ++r) {
+            const int run = wave * RUNS + r;
+            uint32_t d[R::CODES / 4], w[R::WORDS];
+#pragma unroll
+            for (int j = 0; j < R::WORDS; ++j) {
+                const int64_t word = ((int64_t)span * (SPAN / R::CODES) + run) * R::WORDS + j;
+                w[j] = word < words ? P[TILED ? (tile * words + word) * QG_WAVE + lane : word * N + n] : 0u;
+            }
+            R::unpack(w, d);
+            uint4 *dst = (uint4 *)(lds + lane * PITCH + run * R::CODES);
+            if constexpr (R::CODES == 8) {
+                *(uint2 *)dst = make_uint2(d[0], d[1]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < R::CODES / 16; ++i)
+                    dst[i] = make_uint4(d[4 * i], d[4 * i + 1], d[4 * i + 2], d[4 * i + 3]);
+            }
+        }
+    }
+    __syncthreads();
+    lds_to_rows<SPAN>(v, N, cols, tile * QG_WAVE, (int64_t)span * SPAN, wide, lds);
+}
+
+// ------------------------------------------------------------------ device layout: codes
+
+// One cell (CELL codes, one per byte in d) -> its word (2, 4 bits) or its three plane words.
 template <int BITS>
-__global__ __launch_bounds__(256) void device_pack_codes(const uint8_t *__restrict__ q,
-                                                         int64_t N, int64_t K, int64_t tiles,
-                                                         int64_t units, uint4 *__restrict__ out)
+__device__ inline void cell_pack(const uint32_t *d, uint32_t *w)
+{
+    if constexpr (BITS != 3) {
+        Run<BITS>::pack(d, w);
+    } else {
+        const uint32_t t = d[6] | (d[7] << 3);           // codes 24+i, 28+i: the 6 spare bits of byte i
+        w[0] = d[0] | (d[1] << 3) | ((t & 0x03030303u) << 6);
+        w[1] = d[2] | (d[3] << 3) | (((t >> 2) & 0x03030303u) << 6);
+        w[2] = d[4] | (d[5] << 3) | (((t >> 4) & 0x03030303u) << 6);
+    }
+}
+
+template <int BITS>
+__device__ inline void cell_unpack(const uint32_t *w, uint32_t *d)
+{
+    if constexpr (BITS != 3) {
+        Run<BITS>::unpack(w, d);
+    } else {
+        constexpr uint32_t M3 = 0x07070707u, M2 = 0x03030303u;
+        d[0] = w[0] & M3;  d[1] = (w[0] >> 3) & M3;
+        d[2] = w[1] & M3;  d[3] = (w[1] >> 3) & M3;
+        d[4] = w[2] & M3;  d[5] = (w[2] >> 3) & M3;
+        const uint32_t t = ((w[0] >> 6) & M2) | (((w[1] >> 6) & M2) << 2) | (((w[2] >> 6) & M2) << 4);
+        d[6] = t & M3;     d[7] = (t >> 3) & M3;
+    }
+}
+
+// q [N][K] -> codes uint4 [tile][unit][plane][lane].  A workgroup takes one tile and
+// 4 * UPW consecutive units; a wavefront UPW of them, lane = output.
+template <int BITS>
+__global__ __launch_bounds__(PK_THREADS) void device_pack_codes(const uint8_t *__restrict__ q, int64_t N,
+                                                                int64_t K, int64_t units, int spans,
+                                                                bool wide, uint4 *__restrict__ out)
 {
     constexpr int CELL = BITS == 4 ? 8 : BITS == 2 ? 16 : 32;
     constexpr int PLANES = BITS == 3 ? 3 : 1;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= tiles * units * QG_WAVE) return;
-    const int lane = (int)(idx % QG_WAVE);
-    const int64_t unit = (idx / QG_WAVE) % units;
-    const int64_t tile = idx / QG_WAVE / units;
-    const int64_t n = tile * QG_WAVE + lane;
-
-    uint32_t words[PLANES][4];
+    constexpr int UNIT = 4 * CELL;
+    constexpr int SPAN = span_of<BITS>(), PITCH = SPAN + 16;
+    constexpr int UPW = SPAN / UNIT / 4;
+    __shared__ __align__(16) uint8_t lds[QG_WAVE * PITCH];
+    const int64_t tile = blockIdx.x / spans;
+    const int span = blockIdx.x % spans;
+    rows_to_lds<SPAN>(q, N, K, tile * QG_WAVE, (int64_t)span * SPAN, wide, lds);
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int64_t k0 = (unit * 4 + j) * CELL;
-        uint8_t c[CELL];
+    for (int u = 0; u < UPW; ++u) {
+        const int64_t unit = (int64_t)span * (4 * UPW) + wave * UPW + u;
+        if (unit >= units) break;
+        uint32_t words[PLANES][4];
 #pragma unroll
-        for (int i = 0; i < CELL; ++i)
-            c[i] = (n < N && k0 + i < K) ? q[n * K + k0 + i] : (uint8_t)0;
-        if constexpr (BITS == 4 || BITS == 2) {
-            uint32_t w = 0;
+        for (int j = 0; j < 4; ++j) {
+            uint32_t d[CELL / 4], w[PLANES];
+            const uint8_t *src = lds + lane * PITCH + ((wave * UPW + u) * 4 + j) * CELL;
+            if constexpr (CELL == 8) {
+                const uint2 a = *(const uint2 *)src;
+                d[0] = a.x; d[1] = a.y;
+            } else {
 #pragma unroll
-            for (int i = 0; i < CELL; ++i) w |= (uint32_t)c[i] << (BITS * i);
-            words[0][j] = w;
-        } else {
-            uint32_t a = 0, b = 0, cc = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t t = (uint32_t)c[24 + i] | ((uint32_t)c[28 + i] << 3);  // 6 spare bits
-                a |= ((uint32_t)c[i] | ((uint32_t)c[4 + i] << 3) | ((t & 3u) << 6)) << (8 * i);
-                b |= ((uint32_t)c[8 + i] | ((uint32_t)c[12 + i] << 3) | (((t >> 2) & 3u) << 6)) << (8 * i);
-                cc |= ((uint32_t)c[16 + i] | ((uint32_t)c[20 + i] << 3) | (((t >> 4) & 3u) << 6)) << (8 * i);
+                for (int i = 0; i < CELL / 16; ++i) {
+                    const uint4 a = ((const uint4 *)src)[i];
+                    d[4 * i] = a.x; d[4 * i + 1] = a.y; d[4 * i + 2] = a.z; d[4 * i + 3] = a.w;
+                }
             }
-            words[0][j] = a;
-            words[1 % PLANES][j] = b;
-            words[2 % PLANES][j] = cc;
-        }
-    }
+            cell_pack<BITS>(d, w);
 #pragma unroll
-    for (int p = 0; p < PLANES; ++p)
-        out[((tile * units + unit) * PLANES + p) * QG_WAVE + lane] =
-            make_uint4(words[p][0], words[p][1], words[p][2], words[p][3]);
+            for (int p = 0; p < PLANES; ++p) words[p][j] = w[p];
+        }
+#pragma unroll
+        for (int p = 0; p < PLANES; ++p)
+            out[((tile * units + unit) * PLANES + p) * QG_WAVE + lane] =
+                make_uint4(words[p][0], words[p][1], words[p][2], words[p][3]);
+    }
 }
 
 template <int BITS>
-__global__ __launch_bounds__(256) void device_unpack_codes(const uint4 *__restrict__ in,
-                                                           int64_t N, int64_t K, int64_t tiles,
-                                                           int64_t units, uint8_t *__restrict__ q)
+__global__ __launch_bounds__(PK_THREADS) void device_unpack_codes(const uint4 *__restrict__ in, int64_t N,
+                                                                  int64_t K, int64_t units, int spans,
+                                                                  bool wide, uint8_t *__restrict__ q)
 {
     constexpr int CELL = BITS == 4 ? 8 : BITS == 2 ? 16 : 32;
     constexpr int PLANES = BITS == 3 ? 3 : 1;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= tiles * units * QG_WAVE) return;
-    const int lane = (int)(idx % QG_WAVE);
-    const int64_t unit = (idx / QG_WAVE) % units;
-    const int64_t tile = idx / QG_WAVE / units;
-    const int64_t n = tile * QG_WAVE + lane;
-    if (n >= N) return;
-
-    uint32_t words[PLANES][4];
+    constexpr int UNIT = 4 * CELL;
+    constexpr int SPAN = span_of<BITS>(), PITCH = SPAN + 16;
+    constexpr int UPW = SPAN / UNIT / 4;
+    __shared__ __align__(16) uint8_t lds[QG_WAVE * PITCH];
+    const int64_t tile = blockIdx.x / spans;
+    const int span = blockIdx.x % spans;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-    for (int p = 0; p < PLANES; ++p) {
-        const uint4 v = in[((tile * units + unit) * PLANES + p) * QG_WAVE + lane];
-        words[p][0] = v.x; words[p][1] = v.y; words[p][2] = v.z; words[p][3] = v.w;
-    }
+    for (int u = 0; u < UPW; ++u) {
+        const int64_t unit = (int64_t)span * (4 * UPW) + wave * UPW + u;
+        if (unit >= units) break;                        // that part of the block lies past K
+        uint32_t words[PLANES][4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int64_t k0 = (unit * 4 + j) * CELL;
-        uint8_t c[CELL];
-        if constexpr (BITS == 4 || BITS == 2) {
+        for (int p = 0; p < PLANES; ++p) {
+            const uint4 a = in[((tile * units + unit) * PLANES + p) * QG_WAVE + lane];
+            words[p][0] = a.x; words[p][1] = a.y; words[p][2] = a.z; words[p][3] = a.w;
+        }
 #pragma unroll
-            for (int i = 0; i < CELL; ++i)
-                c[i] = (uint8_t)((words[0][j] >> (BITS * i)) & ((1u << BITS) - 1u));
-        } else {
-            const uint32_t a = words[0][j], b = words[1 % PLANES][j], cc = words[2 % PLANES][j];
+        for (int j = 0; j < 4; ++j) {
+            uint32_t d[CELL / 4], w[PLANES];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t ba = byte_of(a, i), bb = byte_of(b, i), bc = byte_of(cc, i);
-                const uint32_t t = (ba >> 6) | ((bb >> 6) << 2) | ((bc >> 6) << 4);
-                c[i] = ba & 7u;        c[4 + i] = (ba >> 3) & 7u;
-                c[8 + i] = bb & 7u;    c[12 + i] = (bb >> 3) & 7u;
-                c[16 + i] = bc & 7u;   c[20 + i] = (bc >> 3) & 7u;
-                c[24 + i] = t & 7u;    c[28 + i] = (t >> 3) & 7u;
+            for (int p = 0; p < PLANES; ++p) w[p] = words[p][j];
+            cell_unpack<BITS>(w, d);
+            uint8_t *dst = lds + lane * PITCH + ((wave * UPW + u) * 4 + j) * CELL;
+            if constexpr (CELL == 8) {
+                *(uint2 *)dst = make_uint2(d[0], d[1]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < CELL / 16; ++i)
+                    ((uint4 *)dst)[i] = make_uint4(d[4 * i], d[4 * i + 1], d[4 * i + 2], d[4 * i + 3]);
             }
         }
-#pragma unroll
-        for (int i = 0; i < CELL; ++i)
-            if (k0 + i < K) q[n * K + k0 + i] = c[i];
+    }
+    __syncthreads();
+    lds_to_rows<SPAN>(q, N, K, tile * QG_WAVE, (int64_t)span * SPAN, wide, lds);
+}
+
+// ------------------------------------------------------------------ scales
+//
+// s [N][G] (row-major)  <->  canonical St [G][N]  or  per tile sd [tile][G][lane] (lanes past
+// N hold 0).  A workgroup moves 64 outputs x 64 groups through LDS.
+template <bool TILED>
+__global__ __launch_bounds__(PK_THREADS) void scales_pack(const float *__restrict__ s, int64_t N, int64_t G,
+                                                          int spans, float *__restrict__ out)
+{
+    __shared__ float lds[QG_WAVE][QG_WAVE + 1];
+    const int64_t tile = blockIdx.x / spans;
+    const int64_t g0 = (int64_t)(blockIdx.x % spans) * QG_WAVE;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int r = wave; r < QG_WAVE; r += 4) {
+        const int64_t n = tile * QG_WAVE + r, g = g0 + lane;
+        lds[r][lane] = (n < N && g < G) ? s[n * G + g] : 0.0f;
+    }
+    __syncthreads();
+    const int64_t n = tile * QG_WAVE + lane;
+    for (int c = wave; c < QG_WAVE; c += 4) {
+        const int64_t g = g0 + c;
+        if (g >= G) break;
+        if (TILED) out[(tile * G + g) * QG_WAVE + lane] = lds[lane][c];
+        else if (n < N) out[g * N + n] = lds[lane][c];
     }
 }
 
-// scales [tile][group][lane] and zero words [tile][zword][lane]
-__global__ void device_pack_meta(const float *__restrict__ s, const uint8_t *__restrict__ z,
-                                 int64_t N, int64_t ngroups, int64_t tiles, int64_t zwords,
-                                 int zbits, float *__restrict__ sd, uint32_t *__restrict__ zd)
+template <bool TILED>
+__global__ __launch_bounds__(PK_THREADS) void scales_unpack(const float *__restrict__ in, int64_t N, int64_t G,
+                                                            int spans, float *__restrict__ s)
 {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t ns = tiles * ngroups * QG_WAVE;
-    const int64_t nz = tiles * zwords * QG_WAVE;
-    if (idx < ns) {
-        const int lane = (int)(idx % QG_WAVE);
-        const int64_t g = (idx / QG_WAVE) % ngroups;
-        const int64_t n = idx / QG_WAVE / ngroups * QG_WAVE + lane;
-        sd[idx] = n < N ? s[n * ngroups + g] : 0.0f;
-    } else if (idx < ns + nz) {
-        const int64_t i = idx - ns;
-        const int lane = (int)(i % QG_WAVE);
-        const int64_t w = (i / QG_WAVE) % zwords;
-        const int64_t n = i / QG_WAVE / zwords * QG_WAVE + lane;
-        const int per = 32 / zbits;
-        uint32_t word = 0;
-        for (int j = 0; j < per; ++j) {
-            const int64_t g = w * per + j;
-            if (n < N && g < ngroups) word |= (uint32_t)z[n * ngroups + g] << (zbits * j);
-        }
-        zd[i] = word;
+    __shared__ float lds[QG_WAVE][QG_WAVE + 1];
+    const int64_t tile = blockIdx.x / spans;
+    const int64_t g0 = (int64_t)(blockIdx.x % spans) * QG_WAVE;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t nl = tile * QG_WAVE + lane;
+    for (int c = wave; c < QG_WAVE; c += 4) {
+        const int64_t g = g0 + c;
+        float val = 0.0f;
+        if (g < G && (TILED || nl < N)) val = in[TILED ? (tile * G + g) * QG_WAVE + lane : g * N + nl];
+        lds[lane][c] = val;
+    }
+    __syncthreads();
+    for (int r = wave; r < QG_WAVE; r += 4) {
+        const int64_t n = tile * QG_WAVE + r, g = g0 + lane;
+        if (n < N && g < G) s[n * G + g] = lds[r][lane];
     }
 }
 
-__global__ void device_unpack_meta(const float *__restrict__ sd, const uint32_t *__restrict__ zd,
-                                   int64_t N, int64_t ngroups, int64_t zwords, int zbits,
-                                   float *__restrict__ s, uint8_t *__restrict__ z)
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// workgroups of a launch over `tiles` x `spans` blocks, or 0 if HIP's grid cannot hold them
+inline unsigned grid_for(int64_t tiles, int64_t spans)
 {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= N * ngroups) return;
-    const int64_t n = idx / ngroups, g = idx % ngroups;
-    const int64_t tile = n / QG_WAVE;
-    const int lane = (int)(n % QG_WAVE);
-    const int per = 32 / zbits;
-    s[idx] = sd[(tile * ngroups + g) * QG_WAVE + lane];
-    const uint32_t word = zd[(tile * zwords + g / per) * QG_WAVE + lane];
-    z[idx] = (uint8_t)((word >> (zbits * (int)(g % per))) & ((1u << zbits) - 1u));
+    return tiles * spans > 0x7fffffff ? 0u : (unsigned)(tiles * spans);
 }
 
-inline unsigned blocks_for(int64_t threads) { return (unsigned)((threads + 255) / 256); }
+// stream_pack / stream_unpack for a [N][cols] byte matrix with `fb`-bit fields
+template <bool TILED>
+int launch_stream(bool pack, int fb, const void *bytes, int64_t N, int64_t cols, int64_t words,
+                  const void *packed, hipStream_t st)
+{
+    const int64_t tiles = ceil_div(N, QG_WAVE);
+    const int spans = (int)ceil_div(cols, fb == 3 ? span_of<3>() : span_of<4>());
+    const unsigned grid = grid_for(tiles, spans);
+    if (!grid) return QG_ERR_SHAPE;
+    const bool wide = cols % 16 == 0 && qg_aligned16(bytes);
+    const uint8_t *vin = (const uint8_t *)bytes;
+    uint8_t *vout = (uint8_t *)bytes;
+    const uint32_t *pin = (const uint32_t *)packed;
+    uint32_t *pout = (uint32_t *)packed;
+#define QG_STREAM(FB)                                                                                   \
+    if (pack) hipLaunchKernelGGL((stream_pack<FB, TILED>), dim3(grid), dim3(PK_THREADS), 0, st, vin, N, \
+                                 cols, words, spans, wide, pout);                                       \
+    else hipLaunchKernelGGL((stream_unpack<FB, TILED>), dim3(grid), dim3(PK_THREADS), 0, st, pin, N,    \
+                            cols, words, spans, wide, vout)
+    if (fb == 4) { QG_STREAM(4); }
+    else if (fb == 2) { QG_STREAM(2); }
+    else { QG_STREAM(3); }
+#undef QG_STREAM
+    return QG_OK;
+}
+
+template <bool TILED>
+int launch_scales(bool pack, const float *s, int64_t N, int64_t G, const float *packed, hipStream_t st)
+{
+    const int spans = (int)ceil_div(G, QG_WAVE);
+    const unsigned grid = grid_for(ceil_div(N, QG_WAVE), spans);
+    if (!grid) return QG_ERR_SHAPE;
+    if (pack) hipLaunchKernelGGL(scales_pack<TILED>, dim3(grid), dim3(PK_THREADS), 0, st, s, N, G, spans,
+                                 (float *)packed);
+    else hipLaunchKernelGGL(scales_unpack<TILED>, dim3(grid), dim3(PK_THREADS), 0, st, packed, N, G, spans,
+                            (float *)s);
+    return QG_OK;
+}
+
+int launch_device_codes(bool pack, const QgLayout &L, const void *q, const void *codes, hipStream_t st)
+{
+    const int span_units = (L.bits == 3 ? span_of<3>() : span_of<4>()) / L.unit;
+    const int spans = (int)ceil_div(L.units, span_units);
+    const unsigned grid = grid_for(L.tiles, spans);
+    if (!grid) return QG_ERR_SHAPE;
+    const bool wide = L.K % 16 == 0 && qg_aligned16(q);
+#define QG_CODES(B)                                                                                      \
+    if (pack) hipLaunchKernelGGL(device_pack_codes<B>, dim3(grid), dim3(PK_THREADS), 0, st,              \
+                                 (const uint8_t *)q, L.N, L.K, L.units, spans, wide, (uint4 *)codes);    \
+    else hipLaunchKernelGGL(device_unpack_codes<B>, dim3(grid), dim3(PK_THREADS), 0, st,                 \
+                            (const uint4 *)codes, L.N, L.K, L.units, spans, wide, (uint8_t *)q)
+    if (L.bits == 4) { QG_CODES(4); }
+    else if (L.bits == 2) { QG_CODES(2); }
+    else { QG_CODES(3); }
+#undef QG_CODES
+    return QG_OK;
+}
+
+// both directions of qg_pack / qg_unpack: the same three sections either way
+int convert(bool pack, const void *q, const void *s, const void *z, int64_t N, int64_t K, int bits,
+            int group, int layout, const void *packed, hipStream_t st)
+{
+    if (layout != QG_LAYOUT_CANONICAL && layout != QG_LAYOUT_DEVICE) return QG_ERR_UNSUPPORTED;
+    QgLayout L;
+    int rc = qg_make_layout(N, K, bits, group, &L);
+    if (rc != QG_OK) return rc;
+    if (!q || !s || !z || !packed) return QG_ERR_NULL;
+    if (!qg_aligned16(packed)) return QG_ERR_ALIGN;
+    const char *base = (const char *)packed;
+
+    if (layout == QG_LAYOUT_CANONICAL) {
+        QgCanonical C;
+        rc = qg_make_canonical(N, K, bits, group, &C);
+        if (rc != QG_OK) return rc;
+        rc = launch_stream<false>(pack, bits, q, N, K, C.code_words, base + C.codes_off, st);
+        if (rc == QG_OK) rc = launch_scales<false>(pack, (const float *)s, N, C.ngroups,
+                                                   (const float *)(base + C.scales_off), st);
+        if (rc == QG_OK) rc = launch_stream<false>(pack, bits, z, N, C.ngroups, C.zero_words,
+                                                   base + C.zeros_off, st);
+    } else {
+        rc = launch_device_codes(pack, L, q, base + L.codes_off, st);
+        if (rc == QG_OK) rc = launch_scales<true>(pack, (const float *)s, N, L.ngroups,
+                                                  (const float *)(base + L.scales_off), st);
+        if (rc == QG_OK) rc = launch_stream<true>(pack, L.zbits, z, N, L.ngroups, L.zwords,
+                                                  base + L.zeros_off, st);
+    }
+    return rc == QG_OK ? qg_launch_status() : rc;
+}
 
 }  // namespace
 
@@ -229,84 +533,11 @@ extern "C" size_t qg_packed_bytes(int64_t N, int64_t K, int bits, int group, int
 extern "C" int qg_pack(const uint8_t *q, const float *s, const uint8_t *z, int64_t N, int64_t K,
                        int bits, int group, int layout, void *packed, void *stream)
 {
-    hipStream_t st = (hipStream_t)stream;
-    if (layout != QG_LAYOUT_CANONICAL && layout != QG_LAYOUT_DEVICE) return QG_ERR_UNSUPPORTED;
-    QgLayout L;
-    int rc = qg_make_layout(N, K, bits, group, &L);
-    if (rc != QG_OK) return rc;
-    if (!q || !s || !z || !packed) return QG_ERR_NULL;
-    if (!qg_aligned16(packed)) return QG_ERR_ALIGN;
-    char *base = (char *)packed;
-
-    if (layout == QG_LAYOUT_CANONICAL) {
-        QgCanonical C;
-        rc = qg_make_canonical(N, K, bits, group, &C);
-        if (rc != QG_OK) return rc;
-        hipLaunchKernelGGL(canon_pack_stream, dim3(blocks_for(C.code_words * N)), dim3(256), 0, st,
-                           q, N, K, bits, C.code_words, (uint32_t *)(base + C.codes_off));
-        hipLaunchKernelGGL(transpose_f32, dim3(blocks_for(N * C.ngroups)), dim3(256), 0, st,
-                           s, N, C.ngroups, (float *)(base + C.scales_off));
-        hipLaunchKernelGGL(canon_pack_stream, dim3(blocks_for(C.zero_words * N)), dim3(256), 0, st,
-                           z, N, C.ngroups, bits, C.zero_words, (uint32_t *)(base + C.zeros_off));
-        return qg_launch_status();
-    }
-
-    const int64_t threads = L.tiles * L.units * QG_WAVE;
-    uint4 *codes = (uint4 *)(base + L.codes_off);
-    if (bits == 4)
-        hipLaunchKernelGGL(device_pack_codes<4>, dim3(blocks_for(threads)), dim3(256), 0, st,
-                           q, N, K, L.tiles, L.units, codes);
-    else if (bits == 2)
-        hipLaunchKernelGGL(device_pack_codes<2>, dim3(blocks_for(threads)), dim3(256), 0, st,
-                           q, N, K, L.tiles, L.units, codes);
-    else
-        hipLaunchKernelGGL(device_pack_codes<3>, dim3(blocks_for(threads)), dim3(256), 0, st,
-                           q, N, K, L.tiles, L.units, codes);
-    const int64_t meta = L.tiles * (L.ngroups + L.zwords) * QG_WAVE;
-    hipLaunchKernelGGL(device_pack_meta, dim3(blocks_for(meta)), dim3(256), 0, st,
-                       s, z, N, L.ngroups, L.tiles, L.zwords, L.zbits,
-                       (float *)(base + L.scales_off), (uint32_t *)(base + L.zeros_off));
-    return qg_launch_status();
+    return convert(true, q, s, z, N, K, bits, group, layout, packed, (hipStream_t)stream);
 }
 
 extern "C" int qg_unpack(const void *packed, int64_t N, int64_t K, int bits, int group,
                          int layout, uint8_t *q, float *s, uint8_t *z, void *stream)
 {
-    hipStream_t st = (hipStream_t)stream;
-    if (layout != QG_LAYOUT_CANONICAL && layout != QG_LAYOUT_DEVICE) return QG_ERR_UNSUPPORTED;
-    QgLayout L;
-    int rc = qg_make_layout(N, K, bits, group, &L);
-    if (rc != QG_OK) return rc;
-    if (!q || !s || !z || !packed) return QG_ERR_NULL;
-    if (!qg_aligned16(packed)) return QG_ERR_ALIGN;
-    const char *base = (const char *)packed;
-
-    if (layout == QG_LAYOUT_CANONICAL) {
-        QgCanonical C;
-        rc = qg_make_canonical(N, K, bits, group, &C);
-        if (rc != QG_OK) return rc;
-        hipLaunchKernelGGL(canon_unpack_stream, dim3(blocks_for(N * K)), dim3(256), 0, st,
-                           (const uint32_t *)(base + C.codes_off), N, K, bits, q);
-        hipLaunchKernelGGL(transpose_f32, dim3(blocks_for(N * C.ngroups)), dim3(256), 0, st,
-                           (const float *)(base + C.scales_off), C.ngroups, N, s);
-        hipLaunchKernelGGL(canon_unpack_stream, dim3(blocks_for(N * C.ngroups)), dim3(256), 0, st,
-                           (const uint32_t *)(base + C.zeros_off), N, C.ngroups, bits, z);
-        return qg_launch_status();
-    }
-
-    const int64_t threads = L.tiles * L.units * QG_WAVE;
-    const uint4 *codes = (const uint4 *)(base + L.codes_off);
-    if (bits == 4)
-        hipLaunchKernelGGL(device_unpack_codes<4>, dim3(blocks_for(threads)), dim3(256), 0, st,
-                           codes, N, K, L.tiles, L.units, q);
-    else if (bits == 2)
-        hipLaunchKernelGGL(device_unpack_codes<2>, dim3(blocks_for(threads)), dim3(256), 0, st,
-                           codes, N, K, L.tiles, L.units, q);
-    else
-        hipLaunchKernelGGL(device_unpack_codes<3>, dim3(blocks_for(threads)), dim3(256), 0, st,
-                           codes, N, K, L.tiles, L.units, q);
-    hipLaunchKernelGGL(device_unpack_meta, dim3(blocks_for(N * L.ngroups)), dim3(256), 0, st,
-                       (const float *)(base + L.scales_off), (const uint32_t *)(base + L.zeros_off),
-                       N, L.ngroups, L.zwords, L.zbits, s, z);
-    return qg_launch_status();
+    return convert(false, q, s, z, N, K, bits, group, layout, packed, (hipStream_t)stream);
 }

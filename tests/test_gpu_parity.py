@@ -38,6 +38,10 @@ QUANT_CASES = [  # N, K, bits, group, std, outliers
     (16, 1024, 4, 1024, 0.02, True),      # one group per output (full column)
     (9, 96, 4, 8, 0.02, False),
     (5, 120, 4, 24, 1.0, False),
+    (7, 8192, 4, 4096, 0.02, True),       # the largest group held in registers
+    (3, 16384, 2, 8192, 0.02, False),     # larger: the looping kernel
+    (37, 1536, 3, 512, 0.02, True),
+    (1003, 256, 4, 256, 0.02, False),     # a last workgroup with idle teams
 ]
 
 
@@ -77,7 +81,9 @@ def test_quantize_special_values_bit_exact(qg, oracle):
 # ------------------------------------------------------------------ pack / unpack (bit-exact)
 
 PACK_CASES = [(512, 512, 4, 64), (200, 768, 4, 128), (130, 640, 3, 64), (77, 512, 2, 32),
-              (64, 256, 2, 16), (33, 384, 3, 32), (1, 96, 3, 96), (65, 160, 4, 32), (3, 64, 2, 64)]
+              (64, 256, 2, 16), (33, 384, 3, 32), (1, 96, 3, 96), (65, 160, 4, 32), (3, 64, 2, 64),
+              # rows that are not multiples of 16 bytes; more than one block of columns per tile
+              (70, 72, 4, 24), (9, 40, 4, 8), (129, 1160, 4, 8), (131, 1056, 3, 32), (67, 2064, 2, 16)]
 
 
 @pytest.mark.parametrize("N,K,bits,group", PACK_CASES)
@@ -109,6 +115,38 @@ def test_device_pack_unpack_identity(qg, N, K, bits, group):
     q2, s2, z2 = qg.qg_unpack(blob, N, K, bits, group, qg.QG_LAYOUT_DEVICE)
     assert np.array_equal(host(q2), q) and np.array_equal(host(z2), z)
     assert np.array_equal(host(s2).view(np.uint32), s.view(np.uint32))
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_pack_from_unaligned_arrays(qg, oracle, bits):
+    """Codes and zero-points that do not start on a 16-byte boundary take the byte-wise path."""
+    N, K, group = 75, 512, 32
+    _announce("unaligned pack", N, K, bits, group)
+    rng = np.random.default_rng(40 + bits)
+    q = rng.integers(0, 1 << bits, (N, K), dtype=np.uint8)
+    z = rng.integers(0, 1 << bits, (N, K // group), dtype=np.uint8)
+    s = rng.standard_normal((N, K // group)).astype(np.float32)
+    qd = torch.empty(N * K + 16, dtype=torch.uint8, device="cuda")[3:3 + N * K].view(N, K)
+    zd = torch.empty(z.size + 16, dtype=torch.uint8, device="cuda")[5:5 + z.size].view(N, K // group)
+    qd.copy_(dev(q)); zd.copy_(dev(z))
+    assert qd.data_ptr() % 16 and zd.data_ptr() % 16
+    for layout in (qg.QG_LAYOUT_CANONICAL, qg.QG_LAYOUT_DEVICE):
+        blob = qg.qg_pack(qd, dev(s), zd, bits, group, layout)
+        assert torch.equal(blob, qg.qg_pack(dev(q), dev(s), dev(z), bits, group, layout))
+        nbytes = qg.qg_packed_bytes(N, K, bits, group, layout)
+        lib = qg.lib()
+        q2 = torch.zeros(N * K + 16, dtype=torch.uint8, device="cuda")
+        z2 = torch.zeros(z.size + 16, dtype=torch.uint8, device="cuda")
+        s2 = torch.empty_like(dev(s))
+        rc = lib.qg_unpack(blob.data_ptr(), N, K, bits, group, layout, q2.data_ptr() + 3, s2.data_ptr(),
+                           z2.data_ptr() + 5, torch.cuda.current_stream().cuda_stream)
+        assert rc == 0 and blob.numel() == nbytes
+        torch.cuda.synchronize()
+        assert np.array_equal(host(q2)[3:3 + N * K].reshape(N, K), q)
+        assert np.array_equal(host(z2)[5:5 + z.size].reshape(N, -1), z)
+        assert not host(q2)[:3].any() and not host(q2)[3 + N * K:].any()      # nothing written outside
+        assert not host(z2)[:5].any() and not host(z2)[5 + z.size:].any()
+        assert np.array_equal(host(s2).view(np.uint32), s.view(np.uint32))
 
 
 # ------------------------------------------------------------------ GEMV (tolerance)
