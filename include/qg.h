@@ -164,8 +164,9 @@ int qg_gemv_autotune(const qg_gemv_desc *descs /* HOST */, int count, int sets,
                      int *waves_per_block, int *bytes_per_wave, int *kernel, float *best_us);
 
 /* Same for qg_gemm_small: splits in 1..8 = number of K ranges handled by different
- * workgroups (clamped to what the shape allows); shape in 1..7 = workgroup shape (how many
- * tiles and K slices the wavefronts of a workgroup cover; ignored if it does not fit M),
+ * workgroups (clamped to what the shape allows); shape in 1..12 = workgroup shape (how many
+ * rows, tiles and K slices the wavefronts of a workgroup cover, and which of the two kernels;
+ * ignored if it does not fit M),
  * shape = -1: the kernel for up to 16 rows whatever the number of tiles.
  * 0 restores the built-in choice. */
 int qg_set_gemm_tuning(int splits, int shape);

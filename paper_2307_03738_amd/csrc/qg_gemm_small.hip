@@ -28,6 +28,8 @@
 // fp32 partial results are added by a second small kernel in a fixed order.
 //
 // Other bit widths and group sizes take the fp32 GEMV kernel once per activation row.
+#include <type_traits>
+
 #include "qg_common.h"
 
 size_t qg_gemm_workspace_bytes(const QgLayout &L, int M);
@@ -330,6 +332,265 @@ __global__ __launch_bounds__(TN * KW * 64) void gemm_small_b4(const GemmArgs A)
         }
 }
 
+// ---------------------------------------------------------------------------------------
+// The same product for 33 ... 128 rows with every activation row in one wavefront, so each
+// weight is dequantized once however many rows there are, and with the dequantization of unit
+// u + 1 issued between the matrix instructions of unit u: a wavefront alone keeps the vector
+// ALU and the matrix core busy at the same time (the kernel above clumps them, and two
+// wavefronts per SIMD that leave a barrier together clump in step).
+//
+// A workgroup is TN wavefronts = TN neighbouring tiles over the same k range (no k-slices);
+// an iteration is a pair of steps (256 k).  The activations of the next pair go through
+// registers into the second LDS buffer an eighth at a time, each eighth stored DELAY units
+// after it was requested; codes, scales and zero words are requested one iteration (two
+// steps) ahead.
+// ---------------------------------------------------------------------------------------
+template <int MB, int TN>
+__global__ __launch_bounds__(TN * 64, MB == 2 ? 2 : 1) void gemm_wide_b4(const GemmArgs A)
+{
+    constexpr int THREADS = TN * 64;
+    constexpr int ROWS = MB * 32;
+    constexpr int XK = 2 * KC;                              // k per iteration
+    constexpr int XPITCH = XK + 8;                          // bf16 per LDS row
+    constexpr int XLOADS = ROWS * (XK / 4) / THREADS;       // float4 per thread and chunk
+    constexpr int XPART = XLOADS / 8;                       // ... and unit
+    constexpr int RPP = THREADS / (XK / 4);                 // rows between a thread's pieces
+    constexpr int DELAY = 2;                                // units between a request for activations and its use
+    constexpr int NM = MB * 4;                              // matrix instructions per unit
+    constexpr int PPM = 16 / NM;                            // pieces of dequantization per matrix instruction
+    static_assert(XPART >= 1 && XLOADS % 8 == 0, "a chunk is moved in eight parts");
+    static_assert(MB == 2 || MB == 4, "16 pieces are dealt over 8 or 16 matrix instructions");
+    __shared__ __attribute__((aligned(16))) char smem[2 * ROWS * XPITCH * 2];
+    __bf16 *Xs = (__bf16 *)smem;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tile = blockIdx.x * TN + wave;
+    const bool have_tile = tile < A.tiles;
+    const int rows = A.M < ROWS ? A.M : ROWS;
+    const int st0 = blockIdx.y * A.steps_per_split;
+    int st1 = st0 + A.steps_per_split;
+    if (st1 > A.steps) st1 = A.steps;
+    const int npairs = (st1 - st0 + 1) / 2;
+
+    const int tclamp = have_tile ? tile : A.tiles - 1;
+    const uint4 *codes = A.codes + (size_t)tclamp * A.steps * 4 * QG_WAVE + lane;
+    const float *sc = A.scales + (size_t)tclamp * A.ngroups * QG_WAVE + lane;
+    const uint32_t *zr = A.zeros + (size_t)tclamp * A.zwords * QG_WAVE + lane;
+
+    floatx16 acc[MB][2];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mb][nb][i] = 0.0f;
+
+    const int half = lane >> 5;
+    const int row = lane & 31;
+    const int step_shift = 7 - A.group_shift;
+    auto first_group = [&](int step) { return (step / A.steps_per_group) << step_shift; };
+    auto unit_group = [&](int g0, int u) { return g0 + ((u * 32) >> A.group_shift); };
+    auto fetch = [&](int step, StepRegs &r) {
+        step = step < st1 ? step : st1 - 1;            // past the range: loaded again, not used
+#pragma unroll
+        for (int u = 0; u < 4; ++u) r.v[u] = codes[((size_t)step * 4 + u) * QG_WAVE];
+        const int g0 = first_group(step);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) r.s[u] = sc[(size_t)unit_group(g0, u) * QG_WAVE];
+        r.zw = zr[(size_t)(g0 >> 3) * QG_WAVE];
+    };
+
+    // Activations: piece j of a thread is 4 consecutive k of row j * RPP + wave, so a wavefront
+    // reads 1 KB of one row.  Rows past M repeat the last real row (a row of the A operand only
+    // reaches the same row of the result, and those are not stored); k past K repeats the last
+    // piece of the row (it belongs to a step that is not run).  No branches: the loads of a
+    // part must stay countable for the waits that follow.
+    const int xcol = lane * 4;
+    auto load_x = [&](int k0, int j, float4 &dst) {
+        const float *base = A.X + k0;                          // uniform
+        const uint32_t last = (uint32_t)(A.K - 4 - k0);
+        const uint32_t col = (uint32_t)xcol < last ? (uint32_t)xcol : last;
+        int m = j * RPP + wave;                                // uniform
+        m = m < rows ? m : rows - 1;
+        dst = *(const float4 *)(base + ((size_t)m * (uint32_t)A.K + col));
+    };
+    auto store_x = [&](int buf, int j, const float4 &src) {
+        floatx2 a = {src.x, src.y}, b = {src.z, src.w};
+        bf16x2 pa = __builtin_convertvector(a, bf16x2), pb = __builtin_convertvector(b, bf16x2);
+        uint2 packed;
+        packed.x = *(uint32_t *)&pa;
+        packed.y = *(uint32_t *)&pb;
+        *(uint2 *)(Xs + (size_t)(buf * ROWS + j * RPP + wave) * XPITCH + xcol) = packed;
+    };
+
+    // Dequantization of one unit in 16 pieces (4 words x 4 byte positions, two codes each).
+    struct UnitPrep {
+        uint32_t lo[4], hi[4];     // words P0, Q0, P1, Q1: even codes, odd codes (times 16)
+        float s[2], sh[2], nz[2];  // of outputs 0-31 (P) and 32-63 (Q)
+    };
+    auto prepare = [&](const StepRegs &r, int g0, int u, UnitPrep &pr) {
+        const float s = r.s[u];
+        const int g = unit_group(g0, u);
+        const float nzs = -(float)((r.zw >> (4 * (g & 7))) & 15u) * s;
+        uint32_t sP, sQ, nP, nQ, w[4];
+        swap_halves(__float_as_uint(s), __float_as_uint(s), sP, sQ);
+        swap_halves(__float_as_uint(nzs), __float_as_uint(nzs), nP, nQ);
+        swap_halves(r.v[u].x, r.v[u].z, w[0], w[1]);       // k-octets 0 | 2
+        swap_halves(r.v[u].y, r.v[u].w, w[2], w[3]);       // k-octets 1 | 3
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            pr.lo[i] = opaque(w[i] & 0x0f0f0f0fu);
+            pr.hi[i] = opaque(w[i] & 0xf0f0f0f0u);
+        }
+        pr.s[0] = __uint_as_float(sP);  pr.s[1] = __uint_as_float(sQ);
+        pr.sh[0] = pr.s[0] * 0.0625f;   pr.sh[1] = pr.s[1] * 0.0625f;
+        pr.nz[0] = __uint_as_float(nP); pr.nz[1] = __uint_as_float(nQ);
+    };
+    auto piece = [&](const UnitPrep &pr, int i, Operand (&o)[4]) {
+        const int wd = i >> 2, j = i & 3, pq = wd & 1;
+        floatx2 t;
+        t[0] = fmaf((float)((pr.lo[wd] >> (8 * j)) & 0xffu), pr.s[pq], pr.nz[pq]);
+        t[1] = fmaf((float)((pr.hi[wd] >> (8 * j)) & 0xffu), pr.sh[pq], pr.nz[pq]);
+        bf16x2 pair = __builtin_convertvector(t, bf16x2);
+        // an empty volatile statement: keeps this piece in the slot it is written in
+        uint32_t bits = *(uint32_t *)&pair;
+        asm volatile("" : "+v"(bits));
+        o[wd].p[j] = *(bf16x2 *)&bits;
+    };
+
+    // The units of one iteration.  Matrix instruction k of unit uu is followed by pieces of
+    // the dequantization of unit uu + 1 (of the next pair's first step after the last unit,
+    // if NEXT), by the LDS reads of that unit's A operands and by the traffic of the next
+    // activation chunk; every such slot is fenced, so the order written here is the order
+    // issued.  bq: B operands P0, Q0, P1, Q1 of the unit about to be multiplied.
+    auto compute = [&](auto nu_tag, auto next_tag, const StepRegs &r0, const StepRegs &r1, const StepRegs &rn,
+                       int step0, int buf, Operand (&bq)[4]) {
+        constexpr int NU = decltype(nu_tag)::value;
+        constexpr bool NEXT = decltype(next_tag)::value;
+        const int g00 = first_group(step0), g01 = first_group(step0 + 1), g02 = first_group(step0 + 2);
+        const int xk0 = (step0 + 2) * KC;
+        const __bf16 *xs = Xs + (size_t)buf * ROWS * XPITCH + row * XPITCH + half * 16;
+        bf16x8 a0[MB], a1[MB], n0[MB], n1[MB];
+        float4 xr[DELAY + 1][XPART];
+        Operand bn[4];
+        UnitPrep pr;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            a0[mb] = *(const bf16x8 *)(xs + mb * 32 * XPITCH);
+            a1[mb] = *(const bf16x8 *)(xs + mb * 32 * XPITCH + 8);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int uu = 0; uu < NU; ++uu) {
+            const bool more = uu + 1 < NU;                  // next unit in this pair
+            const bool dq = more || NEXT;                   // something to dequantize
+#pragma unroll
+            for (int k = 0; k < NM; ++k) {
+                const int mb = (k % (MB * 2)) / 2, nb = k % 2;
+                if (k < MB * 2)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mb], bq[nb].v, acc[mb][nb], 0, 0, 0);
+                else
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[mb], bq[2 + nb].v, acc[mb][nb], 0, 0, 0);
+                if (k == 0) {
+                    if (NEXT) {
+#pragma unroll
+                        for (int i = 0; i < XPART; ++i) load_x(xk0, uu * XPART + i, xr[uu % (DELAY + 1)][i]);
+                    }
+                    if (more) {
+#pragma unroll
+                        for (int m2 = 0; m2 < MB; ++m2) {
+                            n0[m2] = *(const bf16x8 *)(xs + m2 * 32 * XPITCH + (uu + 1) * 32);
+                            n1[m2] = *(const bf16x8 *)(xs + m2 * 32 * XPITCH + (uu + 1) * 32 + 8);
+                        }
+                    }
+                    if (dq) {
+                        if (more) prepare(uu + 1 < 4 ? r0 : r1, uu + 1 < 4 ? g00 : g01, (uu + 1) & 3, pr);
+                        else prepare(rn, g02, 0, pr);
+                    }
+                }
+                if (dq) {
+#pragma unroll
+                    for (int q = 0; q < PPM; ++q) piece(pr, k * PPM + q, bn);
+                }
+                if (NEXT && k == NM / 2 && uu >= DELAY) {
+#pragma unroll
+                    for (int i = 0; i < XPART; ++i)
+                        store_x(buf ^ 1, (uu - DELAY) * XPART + i, xr[(uu - DELAY) % (DELAY + 1)][i]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (more) {
+#pragma unroll
+                for (int m2 = 0; m2 < MB; ++m2) {
+                    a0[m2] = n0[m2];
+                    a1[m2] = n1[m2];
+                }
+            }
+            if (dq) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) bq[i].v = bn[i].v;
+            }
+        }
+        if (NEXT) {
+#pragma unroll
+            for (int uu = NU - DELAY; uu < NU; ++uu)
+#pragma unroll
+                for (int i = 0; i < XPART; ++i) store_x(buf ^ 1, uu * XPART + i, xr[uu % (DELAY + 1)][i]);
+        }
+    };
+
+    using std::integral_constant;
+    StepRegs c0, c1, n0, n1;
+    Operand bq[4];
+    if (npairs > 0) {
+        fetch(st0, c0);
+        fetch(st0 + 1, c1);
+        float4 xall[XLOADS];
+#pragma unroll
+        for (int j = 0; j < XLOADS; ++j) load_x(st0 * KC, j, xall[j]);
+#pragma unroll
+        for (int j = 0; j < XLOADS; ++j) store_x(0, j, xall[j]);
+        UnitPrep pr;
+        prepare(c0, first_group(st0), 0, pr);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) piece(pr, i, bq);
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int p = 0; p + 1 < npairs; ++p) {
+        const int s = st0 + 2 * p;
+        fetch(s + 2, n0);
+        fetch(s + 3, n1);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(integral_constant<int, 8>(), integral_constant<bool, true>(), c0, c1, n0, s, buf, bq);
+        __builtin_amdgcn_sched_barrier(0);
+        c0 = n0;
+        c1 = n1;
+        __syncthreads();      // next chunk written, this chunk's readers done
+        buf ^= 1;
+    }
+    if (npairs > 0) {
+        const int s = st0 + 2 * (npairs - 1);
+        if (s + 1 < st1) compute(integral_constant<int, 8>(), integral_constant<bool, false>(), c0, c1, c1, s, buf, bq);
+        else compute(integral_constant<int, 4>(), integral_constant<bool, false>(), c0, c1, c1, s, buf, bq);
+    }
+
+    if (!have_tile) return;
+    float *out = A.out + (size_t)blockIdx.y * A.M * A.N;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            const int n = tile * QG_WAVE + nb * 32 + row;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int m = mb * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+                if (m < A.M && n < A.N) out[(size_t)m * A.N + n] = acc[mb][nb][i];
+            }
+        }
+}
+
 __global__ void add_splits(const float *__restrict__ partial, int splits, size_t count,
                            float *__restrict__ Y)
 {
@@ -358,13 +619,23 @@ void launch(const GemmArgs &A, dim3 grid, hipStream_t st)
     hipLaunchKernelGGL((gemm_small_b4<MB, TN, KW>), grid, dim3(TN * KW * 64), 0, st, A);
 }
 
-// Workgroup shapes: {rows / 32, tiles, k-slices}
+template <int MB, int TN>
+void launch_wide(const GemmArgs &A, dim3 grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((gemm_wide_b4<MB, TN>), grid, dim3(TN * 64), 0, st, A);
+}
+
+// Workgroup shapes: {rows / 32, tiles, k-slices, gemm_wide_b4 (all rows in one wavefront)}
 struct Shape {
     int mb, tn, kw;
+    bool wide;
 };
 constexpr Shape SHAPES[] = {
-    {1, 1, 4}, {1, 2, 4}, {1, 4, 2},                 // up to 32 rows
-    {2, 2, 2}, {2, 4, 1}, {2, 4, 2}, {2, 8, 1},      // blocks of 64 rows
+    {1, 1, 4, false}, {1, 2, 4, false}, {1, 4, 2, false},                       // up to 32 rows
+    {2, 2, 2, false}, {2, 4, 1, false}, {2, 4, 2, false}, {2, 8, 1, false},     // blocks of 64 rows
+    {2, 4, 1, true},  {2, 2, 1, true},                                          // up to 64 rows
+    {4, 4, 1, true},  {4, 2, 1, true},                                          // up to 128 rows
+    {2, 8, 1, true},                                                            // up to 64 rows
 };
 constexpr int NSHAPES = sizeof(SHAPES) / sizeof(SHAPES[0]);
 
@@ -377,7 +648,12 @@ void launch_shape(int i, const GemmArgs &A, dim3 grid, hipStream_t st)
     case 3: launch<2, 2, 2>(A, grid, st); break;
     case 4: launch<2, 4, 1>(A, grid, st); break;
     case 5: launch<2, 4, 2>(A, grid, st); break;
-    default: launch<2, 8, 1>(A, grid, st); break;
+    case 6: launch<2, 8, 1>(A, grid, st); break;
+    case 7: launch_wide<2, 4>(A, grid, st); break;
+    case 8: launch_wide<2, 2>(A, grid, st); break;
+    case 9: launch_wide<4, 4>(A, grid, st); break;
+    case 10: launch_wide<4, 2>(A, grid, st); break;
+    default: launch_wide<2, 8>(A, grid, st); break;
     }
 }
 
@@ -432,12 +708,17 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
         return QG_OK;
     }
 
-    // Workgroup shape.  Up to 32 rows: one block of rows, two tiles x four k-slices.  More:
-    // blocks of 64 rows on the grid's z axis (two blocks double the wavefronts of a launch at
-    // the price of dequantizing twice, which pays as long as the launch cannot fill the chip),
-    // four tiles x two k-slices.  Eight wavefronts per workgroup: one workgroup per compute unit.
-    int shape = M <= 32 ? 1 : 5;
-    if (g_tune_shape > 0 && (SHAPES[g_tune_shape - 1].mb == 1) == (M <= 32)) shape = g_tune_shape - 1;
+    // Workgroup shape (measured choices).  Up to 32 rows: one block of rows, two tiles x four
+    // k-slices.  Up to 64 rows: gemm_wide_b4 with four tiles per workgroup.  More: all rows
+    // in one wavefront (gemm_wide_b4, every weight dequantized once) when the launch has
+    // enough tiles for it, otherwise blocks of 64 rows on the grid's z axis, four tiles x two
+    // k-slices (two blocks double the wavefronts of a launch at the price of dequantizing
+    // twice, which pays as long as the launch cannot fill the chip).
+    int shape = M <= 32 ? 1 : M <= 64 ? 7 : L.tiles >= 128 ? 9 : 5;
+    if (g_tune_shape > 0) {
+        const Shape &s = SHAPES[g_tune_shape - 1];
+        if (s.wide ? (M > 32 && M <= s.mb * 32) : ((s.mb == 1) == (M <= 32))) shape = g_tune_shape - 1;
+    }
     const int rows_per_block = SHAPES[shape].mb * 32;
     const int zblocks = (M + rows_per_block - 1) / rows_per_block;
     const int kw = SHAPES[shape].kw, tn = SHAPES[shape].tn;

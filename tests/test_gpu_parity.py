@@ -490,11 +490,12 @@ def test_gemm_small_every_split_count(qg, oracle, splits, M):
     assert err <= TOL_BF16, err
 
 
-@pytest.mark.parametrize("shape", [1, 2, 3, 4, 5, 6, 7])
-@pytest.mark.parametrize("N,K,group", [(610, 1408, 64), (130, 1152, 384)])
+@pytest.mark.parametrize("shape", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12])
+@pytest.mark.parametrize("N,K,group", [(610, 1408, 64), (130, 1152, 384), (200, 128, 32), (70, 2560, 128)])
 def test_gemm_small_every_workgroup_shape(qg, oracle, shape, N, K, group):
-    # shapes 1-3 hold up to 32 rows, 4-7 blocks of 64 rows; ragged tiles, steps and rows
-    M = 23 if shape <= 3 else 77
+    # shapes 1-3 hold up to 32 rows, 4-7 blocks of 64 rows, 8-9 up to 64 rows in one wavefront,
+    # 10-11 up to 128; ragged tiles and rows, odd and even numbers of steps, a single step
+    M = 23 if shape <= 3 else 77 if shape <= 7 else 50 if shape in (8, 9, 12) else 101
     _announce("gemm_small shape", shape, N, K, group, M)
     W, X = synth.small_case(900 + shape, N, K, 0.02, True, m=M)
     for splits in (0, 2):
