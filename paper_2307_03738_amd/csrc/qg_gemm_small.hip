@@ -27,7 +27,8 @@
 // computed.  K may also be cut into `splits` ranges handled by different workgroups; their
 // fp32 partial results are added by a second small kernel in a fixed order.
 //
-// Other bit widths and group sizes take the fp32 GEMV kernel once per activation row.
+// Other bit widths and group sizes take the fp32 GEMV kernel once per activation row, up to
+// 16 rows per launch.
 #include <type_traits>
 
 #include "qg_common.h"
@@ -661,10 +662,12 @@ void launch_shape(int i, const GemmArgs &A, dim3 grid, hipStream_t st)
 
 size_t qg_gemm_workspace_bytes(const QgLayout &L, int M)
 {
-    // partial results of the K split, or the GEMV workspace for the row-by-row path
+    // partial results of the K split, or the GEMV workspaces of the rows of one grouped launch
     const size_t partial = (size_t)MAX_SPLITS * M * L.N * sizeof(float);
-    const size_t gemv = (size_t)L.tiles * (QG_MAX_CHUNKS + 1) * QG_WAVE * sizeof(uint32_t);   // as qg_gemv asks
-    return qg_round_up(fast_path(L) ? partial : gemv, QG_SECTION_ALIGN);
+    const size_t gemv = qg_round_up((size_t)L.tiles * (QG_MAX_CHUNKS + 1) * QG_WAVE * sizeof(uint32_t),
+                                    QG_SECTION_ALIGN);                                    // as qg_gemv asks
+    const int rows = M < QG_MAX_GROUPED ? M : QG_MAX_GROUPED;
+    return qg_round_up(fast_path(L) ? partial : gemv * rows, QG_SECTION_ALIGN);
 }
 
 extern "C" int qg_set_gemm_tuning(int splits, int shape)
@@ -698,11 +701,22 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     }
 
     if (!fast_path(L)) {
-        // fp32 GEMV per activation row (rows of X stay 64-byte aligned only if K % 16 == 0)
+        // the fp32 GEMV once per activation row, up to 16 rows per launch (rows of X stay
+        // 64-byte aligned only if K % 16 == 0)
         if (K % 16 != 0 && M > 1) return QG_ERR_UNSUPPORTED;
-        for (int m = 0; m < M; ++m) {
-            const int r = qg_gemv(packed, N, K, bits, group, X + (size_t)m * K, Y + (size_t)m * N,
-                                  workspace, workspace_bytes, stream);
+        for (int m0 = 0; m0 < M; m0 += QG_MAX_GROUPED) {
+            qg_gemv_desc d[QG_MAX_GROUPED];
+            const int rows = M - m0 < QG_MAX_GROUPED ? M - m0 : QG_MAX_GROUPED;
+            for (int i = 0; i < rows; ++i) {
+                d[i].packed = packed;
+                d[i].N = N;
+                d[i].K = K;
+                d[i].bits = bits;
+                d[i].group = group;
+                d[i].x = X + (size_t)(m0 + i) * K;
+                d[i].y = Y + (size_t)(m0 + i) * N;
+            }
+            const int r = qg_gemv_grouped(d, rows, workspace, workspace_bytes, stream);
             if (r != QG_OK) return r;
         }
         return QG_OK;

@@ -423,6 +423,8 @@ GEMM_CASES = [  # N, K, bits, group, M
     (130, 512, 3, 64, 7),        # other widths: fp32 row-by-row path
     (96, 512, 2, 32, 4),
     (90, 480, 4, 24, 3),
+    (130, 1280, 3, 64, 37),      # more rows than one grouped launch of the row-by-row path holds
+    (200, 512, 2, 16, 16),
 ]
 
 
