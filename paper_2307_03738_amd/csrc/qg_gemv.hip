@@ -31,7 +31,7 @@
 
 namespace {
 
-struct GemvProblem {
+struct alignas(128) GemvProblem {
     const uint4 *codes;
     const float *scales;
     const uint32_t *zeros;
@@ -53,6 +53,18 @@ struct GemvProblem {
     float *h;              // gated result (pair_tiles > 0)
     int rows;              // gemm_rows16 only: activation rows M (x is X [M][K], y is Y [M][N])
 };
+
+// Every field of a problem entry in scalar registers at one point: the loads that fetch the
+// entry from the argument buffer are then issued together and waited for once, instead of
+// one miss after the other as the fields come into use.
+__device__ inline void pin_problem(const GemvProblem &P)
+{
+    asm volatile("" ::"s"(P.codes), "s"(P.scales), "s"(P.zeros), "s"(P.x), "s"(P.y), "s"(P.slots), "s"(P.h));
+    asm volatile("" ::"s"(P.N), "s"(P.K), "s"(P.tiles), "s"(P.steps), "s"(P.ngroups), "s"(P.zwords), "s"(P.group),
+                 "s"(P.chunks), "s"(P.chunk_shift), "s"(P.waves_per_tile), "s"(P.inv_waves_per_tile),
+                 "s"(P.team_full), "s"(P.tiles_per_block), "s"(P.steps_per_wave), "s"(P.steps_per_group),
+                 "s"(P.block_begin), "s"(P.pair_tiles), "s"(P.rows));
+}
 
 #define QG_SLOT_EMPTY 0xffffffffu
 
@@ -337,13 +349,29 @@ __device__ inline void finish_tile(const GemvProblem &P, const WaveJob &j, float
     emit_output(P, tile, lane, v);
 }
 
+// The first blocks of problems 1 ... 12 once more, as twelve leading scalar kernel arguments:
+// those are handed to a wavefront in registers when it starts (kernel-argument preload), so
+// the search below does not begin with a load from the argument buffer, and the load of the
+// problem's own entry is the only one in front of the first loads of weights.
+typedef int qg_v4i __attribute__((ext_vector_type(4)));
+struct FirstBlocks {
+    qg_v4i a, b, c;        // block_begin[1 .. 12]
+};
+#define QG_FIRST_BLOCKS const qg_v4i fb_a, const qg_v4i fb_b, const qg_v4i fb_c
+
 // Index of the problem a block belongs to: the last one whose first block is <= bid.
-__device__ inline int find_problem(const GemvArgs &A, int bid)
+__device__ inline int find_problem(const qg_v4i fa, const qg_v4i fb, const qg_v4i fc, const GemvArgs &A, int bid)
 {
+    const int first[12] = {fa.x, fa.y, fa.z, fa.w, fb.x, fb.y, fb.z, fb.w, fc.x, fc.y, fc.z, fc.w};
     int p = 0;
 #pragma unroll
-    for (int i = 1; i < QG_MAX_GROUPED; ++i)
-        if (bid >= A.block_begin[i]) p = i;
+    for (int i = 0; i < 12; ++i)
+        if (bid >= first[i]) p = i + 1;
+    if (first[11] != 0x7fffffff) {              // more than 12 problems: the rest from the buffer
+#pragma unroll
+        for (int i = 13; i < QG_MAX_GROUPED; ++i)
+            if (bid >= A.block_begin[i]) p = i;
+    }
     return p;
 }
 
@@ -470,15 +498,16 @@ __device__ inline void compute_step(const StepData<BITS, GPS> &d, const float *_
 // Groups no larger than a step: CPG cells per group, GPS = groups per step, all static.
 // ---------------------------------------------------------------------------------------
 template <int BITS, int CPG>
-__global__ __launch_bounds__(1024) void gemv_static(const GemvArgs A)
+__global__ __launch_bounds__(1024) void gemv_static(QG_FIRST_BLOCKS, const GemvArgs A)
 {
     constexpr int L = loads_per_step<BITS>();
     constexpr int S = codes_per_step<BITS>();
     constexpr int GPS = cells_per_step<BITS>() / CPG;
     __shared__ float red[16][QG_WAVE];
 
-    const int pi = find_problem(A, blockIdx.x);
+    const int pi = find_problem(fb_a, fb_b, fb_c, A, blockIdx.x);
     const GemvProblem P = A.p[pi];                 // one copy: all fields fetched at once
+    pin_problem(P);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.steps, wave);
@@ -641,7 +670,7 @@ __device__ inline void step_group_sums(const StepData<BITS, GPS> &d, float *xhat
 }
 
 template <int BITS, int CPG>
-__global__ __launch_bounds__(512) void gemv_mma(const GemvArgs A)
+__global__ __launch_bounds__(512) void gemv_mma(QG_FIRST_BLOCKS, const GemvArgs A)
 {
     using F = Fmt<BITS>;
     constexpr int L = loads_per_step<BITS>();
@@ -660,8 +689,9 @@ __global__ __launch_bounds__(512) void gemv_mma(const GemvArgs A)
     extern __shared__ __attribute__((aligned(16))) lds_u16 xs_raw[];
     lds_u16(*xs)[2][3][S] = (lds_u16(*)[2][3][S])xs_raw;
 
-    const int pi = find_problem(A, blockIdx.x);
+    const int pi = find_problem(fb_a, fb_b, fb_c, A, blockIdx.x);
     const GemvProblem P = A.p[pi];
+    pin_problem(P);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.steps, wave);
@@ -790,7 +820,7 @@ __global__ __launch_bounds__(512) void gemv_mma(const GemvArgs A)
 // and keeps them in its own LDS region, one 16-byte operand piece per (row, cell).
 // ---------------------------------------------------------------------------------------
 template <int CPG>
-__global__ __launch_bounds__(512) void gemm_rows16(const GemvArgs A)
+__global__ __launch_bounds__(512) void gemm_rows16(QG_FIRST_BLOCKS, const GemvArgs A)
 {
     using F = Fmt<4>;
     constexpr int L = loads_per_step<4>();          // 4 code vectors per step
@@ -807,8 +837,9 @@ __global__ __launch_bounds__(512) void gemm_rows16(const GemvArgs A)
     extern __shared__ __attribute__((aligned(16))) lds_u16 rows_raw[];
     __shared__ __attribute__((aligned(16))) lds_u16 zero_row[PITCH];
 
-    const int pi = find_problem(A, blockIdx.x);
+    const int pi = find_problem(fb_a, fb_b, fb_c, A, blockIdx.x);
     const GemvProblem P = A.p[pi];
+    pin_problem(P);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.steps, wave);
@@ -982,7 +1013,7 @@ __global__ __launch_bounds__(512) void gemm_rows16(const GemvArgs A)
 // in the team's reduction.
 // ---------------------------------------------------------------------------------------
 template <int BITS>
-__global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
+__global__ __launch_bounds__(1024) void gemv_runtime(QG_FIRST_BLOCKS, const GemvArgs A)
 {
     using F = Fmt<BITS>;
     constexpr int L = loads_per_step<BITS>();
@@ -990,8 +1021,9 @@ __global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
     constexpr int ZPER = 32 / F::ZBITS;
     __shared__ float red[16][QG_WAVE];
 
-    const int pi = find_problem(A, blockIdx.x);
+    const int pi = find_problem(fb_a, fb_b, fb_c, A, blockIdx.x);
     const GemvProblem P = A.p[pi];                 // one copy: all fields fetched at once
+    pin_problem(P);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int spg = P.steps_per_group;
@@ -1050,15 +1082,16 @@ __global__ __launch_bounds__(1024) void gemv_runtime(const GemvArgs A)
 // serially.  Slow and simple; covers shapes the two kernels above do not.
 // ---------------------------------------------------------------------------------------
 template <int BITS>
-__global__ __launch_bounds__(1024) void gemv_generic(const GemvArgs A)
+__global__ __launch_bounds__(1024) void gemv_generic(QG_FIRST_BLOCKS, const GemvArgs A)
 {
     using F = Fmt<BITS>;
     constexpr int L = loads_per_step<BITS>();
     constexpr int ZPER = 32 / F::ZBITS;
     __shared__ float red[16][QG_WAVE];
 
-    const int pi = find_problem(A, blockIdx.x);
+    const int pi = find_problem(fb_a, fb_b, fb_c, A, blockIdx.x);
     const GemvProblem P = A.p[pi];                 // one copy: all fields fetched at once
+    pin_problem(P);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int cpg = P.group / F::CELL;
@@ -1171,17 +1204,28 @@ size_t workspace_for(const QgLayout &L)
     return (size_t)L.tiles * (QG_MAX_CHUNKS + 1) * QG_WAVE * sizeof(uint32_t);
 }
 
+FirstBlocks first_blocks(const GemvArgs &A)
+{
+    FirstBlocks f;
+    for (int i = 0; i < 4; ++i) {
+        f.a[i] = A.block_begin[1 + i];
+        f.b[i] = A.block_begin[5 + i];
+        f.c[i] = A.block_begin[9 + i];
+    }
+    return f;
+}
+
 template <int BITS>
 void launch_static(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
 {
     switch (cpg) {
-    case 1: hipLaunchKernelGGL((gemv_static<BITS, 1>), dim3(blocks), dim3(threads), 0, st, A); break;
-    case 2: hipLaunchKernelGGL((gemv_static<BITS, 2>), dim3(blocks), dim3(threads), 0, st, A); break;
-    case 4: hipLaunchKernelGGL((gemv_static<BITS, 4>), dim3(blocks), dim3(threads), 0, st, A); break;
-    case 8: hipLaunchKernelGGL((gemv_static<BITS, 8>), dim3(blocks), dim3(threads), 0, st, A); break;
+    case 1: hipLaunchKernelGGL((gemv_static<BITS, 1>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
+    case 2: hipLaunchKernelGGL((gemv_static<BITS, 2>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
+    case 4: hipLaunchKernelGGL((gemv_static<BITS, 4>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
+    case 8: hipLaunchKernelGGL((gemv_static<BITS, 8>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
     case 16:
         if constexpr (BITS != 3)
-            hipLaunchKernelGGL((gemv_static<BITS, 16>), dim3(blocks), dim3(threads), 0, st, A);
+            hipLaunchKernelGGL((gemv_static<BITS, 16>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
         break;
     }
 }
@@ -1192,12 +1236,12 @@ void launch_mma(int cpg, unsigned blocks, unsigned threads, hipStream_t st, cons
     // x of one step in three bf16 parts, two buffers, per wavefront
     const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 3 * codes_per_step<BITS>() * sizeof(uint16_t);
     switch (cpg) {
-    case 2: hipLaunchKernelGGL((gemv_mma<BITS, 2>), dim3(blocks), dim3(threads), lds, st, A); break;
-    case 4: hipLaunchKernelGGL((gemv_mma<BITS, 4>), dim3(blocks), dim3(threads), lds, st, A); break;
-    case 8: hipLaunchKernelGGL((gemv_mma<BITS, 8>), dim3(blocks), dim3(threads), lds, st, A); break;
+    case 2: hipLaunchKernelGGL((gemv_mma<BITS, 2>), dim3(blocks), dim3(threads), lds, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
+    case 4: hipLaunchKernelGGL((gemv_mma<BITS, 4>), dim3(blocks), dim3(threads), lds, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
+    case 8: hipLaunchKernelGGL((gemv_mma<BITS, 8>), dim3(blocks), dim3(threads), lds, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
     case 16:
         if constexpr (BITS != 3)
-            hipLaunchKernelGGL((gemv_mma<BITS, 16>), dim3(blocks), dim3(threads), lds, st, A);
+            hipLaunchKernelGGL((gemv_mma<BITS, 16>), dim3(blocks), dim3(threads), lds, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
         break;
     }
 }
@@ -1217,7 +1261,7 @@ template <int CPG>
 void launch_rows16(unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
 {
     const size_t lds = (size_t)(threads / QG_WAVE) * 16 * (codes_per_step<4>() + 8) * sizeof(uint16_t);
-    hipLaunchKernelGGL((gemm_rows16<CPG>), dim3(blocks), dim3(threads), lds, st, A);
+    hipLaunchKernelGGL((gemm_rows16<CPG>), dim3(blocks), dim3(threads), lds, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
 }
 
 // rows > 0: the problems are products with `rows` <= 16 activation rows (x = X [rows][K],
@@ -1353,13 +1397,13 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         else if (bits == 2) launch_static<2>(cpg, blocks, threads, st, A);
         else launch_static<3>(cpg, blocks, threads, st, A);
     } else if (kind == KIND_RUNTIME) {
-        if (bits == 4) hipLaunchKernelGGL(gemv_runtime<4>, dim3(blocks), dim3(threads), 0, st, A);
-        else if (bits == 2) hipLaunchKernelGGL(gemv_runtime<2>, dim3(blocks), dim3(threads), 0, st, A);
-        else hipLaunchKernelGGL(gemv_runtime<3>, dim3(blocks), dim3(threads), 0, st, A);
+        if (bits == 4) hipLaunchKernelGGL(gemv_runtime<4>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
+        else if (bits == 2) hipLaunchKernelGGL(gemv_runtime<2>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
+        else hipLaunchKernelGGL(gemv_runtime<3>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
     } else {
-        if (bits == 4) hipLaunchKernelGGL(gemv_generic<4>, dim3(blocks), dim3(threads), 0, st, A);
-        else if (bits == 2) hipLaunchKernelGGL(gemv_generic<2>, dim3(blocks), dim3(threads), 0, st, A);
-        else hipLaunchKernelGGL(gemv_generic<3>, dim3(blocks), dim3(threads), 0, st, A);
+        if (bits == 4) hipLaunchKernelGGL(gemv_generic<4>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
+        else if (bits == 2) hipLaunchKernelGGL(gemv_generic<2>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
+        else hipLaunchKernelGGL(gemv_generic<3>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
     }
     return qg_launch_status();
 }
