@@ -287,6 +287,26 @@ def test_gemv_grouped_mixed_problems(qg, oracle):
         assert scaled_error(host(y), y_ref, norms, x) <= TOL_FP32
 
 
+@pytest.mark.parametrize("count", [12, 13, 14, 16])
+def test_gemv_grouped_many_problems_of_one_format(qg, oracle, count):
+    # one kernel launch with up to the maximum number of problems (the block table is searched
+    # in two parts: twelve entries in registers, the rest from the argument buffer)
+    _announce("gemv grouped, one format", count)
+    problems, refs = [], []
+    for i in range(count):
+        N, K, bits, group = 64 + 37 * i, 512 + 128 * (i % 5), 4, 128
+        W, x = synth.small_case(4000 + i, N, K, 0.02, False)
+        q0, s0, z0 = oracle.quantize(W, bits, group)
+        refs.append((oracle.matvec(q0, s0, z0, group, x), oracle.row_norms(q0, s0, z0, group), x))
+        q, s, z = qg.qg_quantize(dev(W), bits, group)
+        problems.append(dict(packed=qg.qg_pack(q, s, z, bits, group), N=N, K=K, bits=bits, group=group,
+                             x=dev(x), y=torch.empty(N, dtype=torch.float32, device="cuda")))
+    ys = qg.qg_gemv_grouped(problems)
+    torch.cuda.synchronize()
+    for y, (y_ref, norms, x) in zip(ys, refs):
+        assert scaled_error(host(y), y_ref, norms, x) <= TOL_FP32
+
+
 @pytest.mark.parametrize("I,K,bits,group,tuning", [(128, 512, 4, 128, (0, 0, 0)), (320, 1024, 4, 64, (0, 0, 0)),
                                                    (192, 4096, 4, 128, (2, 4096, 1)),      # K cut over workgroups
                                                    (256, 1536, 3, 64, (0, 0, 0)), (256, 1536, 3, 64, (0, 0, 1)),
