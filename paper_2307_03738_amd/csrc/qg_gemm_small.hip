@@ -107,7 +107,7 @@ struct StepRegs {
     uint32_t zw;
 };
 
-template <int MB, int TN, int KW>
+template <int MB, int TN, int KW, bool G128>
 __global__ __launch_bounds__(TN * KW * 64) void gemm_small_b4(const GemmArgs A)
 {
     constexpr int GEMM_THREADS = TN * KW * 64; // TN tiles x KW k-slices, one wavefront each
@@ -211,6 +211,7 @@ __global__ __launch_bounds__(TN * KW * 64) void gemm_small_b4(const GemmArgs A)
         const int g0 = first_group(step);
         const __bf16 *xs = Xs + (size_t)buf * ROWS * XPITCH + kw * KC + row * XPITCH + half * 16;
         bf16x8 a0[MB], a1[MB], n0[MB], n1[MB];
+        uint32_t sP = 0, sQ = 0, nP = 0, nQ = 0;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             a0[mb] = *(const bf16x8 *)(xs + mb * 32 * XPITCH);          // octet 0 or 2
@@ -226,13 +227,17 @@ __global__ __launch_bounds__(TN * KW * 64) void gemm_small_b4(const GemmArgs A)
                     n1[mb] = *(const bf16x8 *)(xs + mb * 32 * XPITCH + (u + 1) * 32 + 8);
                 }
             }
-            const float s = r.s[u];
-            const int g = unit_group(g0, u);
-            const float nzs = -(float)((r.zw >> (4 * (g & 7))) & 15u) * s;
-            // outputs 0-31 of the tile in both halves (P), outputs 32-63 in both halves (Q)
-            uint32_t sP, sQ, nP, nQ, P0, Q0, P1, Q1;
-            swap_halves(__float_as_uint(s), __float_as_uint(s), sP, sQ);
-            swap_halves(__float_as_uint(nzs), __float_as_uint(nzs), nP, nQ);
+            // outputs 0-31 of the tile in both halves (P), outputs 32-63 in both halves (Q);
+            // G128: the units of a step share one group, whose scale and zero term are
+            // exchanged once per step (the lane exchange costs about five issue slots)
+            uint32_t P0, Q0, P1, Q1;
+            if (!G128 || u == 0) {
+                const float s = r.s[u];
+                const int g = unit_group(g0, u);
+                const float nzs = -(float)((r.zw >> (4 * (g & 7))) & 15u) * s;
+                swap_halves(__float_as_uint(s), __float_as_uint(s), sP, sQ);
+                swap_halves(__float_as_uint(nzs), __float_as_uint(nzs), nP, nQ);
+            }
             swap_halves(r.v[u].x, r.v[u].z, P0, Q0);   // k-octets 0 (low lanes) and 2 (high lanes)
             swap_halves(r.v[u].y, r.v[u].w, P1, Q1);   // k-octets 1 and 3
             const bf16x8 bP0 = dequant_word(P0, __uint_as_float(sP), __uint_as_float(nP));
@@ -346,7 +351,7 @@ __global__ __launch_bounds__(TN * KW * 64) void gemm_small_b4(const GemmArgs A)
 // after it was requested; codes, scales and zero words are requested one iteration (two
 // steps) ahead.
 // ---------------------------------------------------------------------------------------
-template <int MB, int TN>
+template <int MB, int TN, bool G128>
 __global__ __launch_bounds__(TN * 64, MB == 2 ? 2 : 1) void gemm_wide_b4(const GemmArgs A)
 {
     constexpr int THREADS = TN * 64;
@@ -430,13 +435,22 @@ __global__ __launch_bounds__(TN * 64, MB == 2 ? 2 : 1) void gemm_wide_b4(const G
         uint32_t lo[4], hi[4];     // words P0, Q0, P1, Q1: even codes, odd codes (times 16)
         float s[2], sh[2], nz[2];  // of outputs 0-31 (P) and 32-63 (Q)
     };
+    // G128: the four units of a step share one group (G >= 128), so the scale and zero term
+    // are exchanged between the halves once per step (the lane exchange is the most expensive
+    // vector instruction of the loop: about five issue slots)
     auto prepare = [&](const StepRegs &r, int g0, int u, UnitPrep &pr) {
-        const float s = r.s[u];
-        const int g = unit_group(g0, u);
-        const float nzs = -(float)((r.zw >> (4 * (g & 7))) & 15u) * s;
-        uint32_t sP, sQ, nP, nQ, w[4];
-        swap_halves(__float_as_uint(s), __float_as_uint(s), sP, sQ);
-        swap_halves(__float_as_uint(nzs), __float_as_uint(nzs), nP, nQ);
+        uint32_t w[4];
+        if (!G128 || u == 0) {
+            const float s = r.s[u];
+            const int g = unit_group(g0, u);
+            const float nzs = -(float)((r.zw >> (4 * (g & 7))) & 15u) * s;
+            uint32_t sP, sQ, nP, nQ;
+            swap_halves(__float_as_uint(s), __float_as_uint(s), sP, sQ);
+            swap_halves(__float_as_uint(nzs), __float_as_uint(nzs), nP, nQ);
+            pr.s[0] = __uint_as_float(sP);  pr.s[1] = __uint_as_float(sQ);
+            pr.sh[0] = pr.s[0] * 0.0625f;   pr.sh[1] = pr.s[1] * 0.0625f;
+            pr.nz[0] = __uint_as_float(nP); pr.nz[1] = __uint_as_float(nQ);
+        }
         swap_halves(r.v[u].x, r.v[u].z, w[0], w[1]);       // k-octets 0 | 2
         swap_halves(r.v[u].y, r.v[u].w, w[2], w[3]);       // k-octets 1 | 3
 #pragma unroll
@@ -444,10 +458,8 @@ __global__ __launch_bounds__(TN * 64, MB == 2 ? 2 : 1) void gemm_wide_b4(const G
             pr.lo[i] = opaque(w[i] & 0x0f0f0f0fu);
             pr.hi[i] = opaque(w[i] & 0xf0f0f0f0u);
         }
-        pr.s[0] = __uint_as_float(sP);  pr.s[1] = __uint_as_float(sQ);
-        pr.sh[0] = pr.s[0] * 0.0625f;   pr.sh[1] = pr.s[1] * 0.0625f;
-        pr.nz[0] = __uint_as_float(nP); pr.nz[1] = __uint_as_float(nQ);
     };
+    UnitPrep pr;               // lives across units and iterations: with G128 its scale part is per step
     auto piece = [&](const UnitPrep &pr, int i, Operand (&o)[4]) {
         const int wd = i >> 2, j = i & 3, pq = wd & 1;
         floatx2 t;
@@ -475,7 +487,6 @@ __global__ __launch_bounds__(TN * 64, MB == 2 ? 2 : 1) void gemm_wide_b4(const G
         bf16x8 a0[MB], a1[MB], n0[MB], n1[MB];
         float4 xr[DELAY + 1][XPART];
         Operand bn[4];
-        UnitPrep pr;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             a0[mb] = *(const bf16x8 *)(xs + mb * 32 * XPITCH);
@@ -552,7 +563,6 @@ __global__ __launch_bounds__(TN * 64, MB == 2 ? 2 : 1) void gemm_wide_b4(const G
         for (int j = 0; j < XLOADS; ++j) load_x(st0 * KC, j, xall[j]);
 #pragma unroll
         for (int j = 0; j < XLOADS; ++j) store_x(0, j, xall[j]);
-        UnitPrep pr;
         prepare(c0, first_group(st0), 0, pr);
 #pragma unroll
         for (int i = 0; i < 16; ++i) piece(pr, i, bq);
@@ -617,13 +627,17 @@ int gcd(int a, int b) { return b == 0 ? a : gcd(b, a % b); }
 template <int MB, int TN, int KW>
 void launch(const GemmArgs &A, dim3 grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((gemm_small_b4<MB, TN, KW>), grid, dim3(TN * KW * 64), 0, st, A);
+    if (A.group_shift == 7)
+        hipLaunchKernelGGL((gemm_small_b4<MB, TN, KW, true>), grid, dim3(TN * KW * 64), 0, st, A);
+    else
+        hipLaunchKernelGGL((gemm_small_b4<MB, TN, KW, false>), grid, dim3(TN * KW * 64), 0, st, A);
 }
 
 template <int MB, int TN>
 void launch_wide(const GemmArgs &A, dim3 grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((gemm_wide_b4<MB, TN>), grid, dim3(TN * 64), 0, st, A);
+    if (A.group_shift == 7) hipLaunchKernelGGL((gemm_wide_b4<MB, TN, true>), grid, dim3(TN * 64), 0, st, A);
+    else hipLaunchKernelGGL((gemm_wide_b4<MB, TN, false>), grid, dim3(TN * 64), 0, st, A);
 }
 
 // Workgroup shapes: {rows / 32, tiles, k-slices, gemm_wide_b4 (all rows in one wavefront)}
