@@ -590,6 +590,7 @@ __device__ inline uint32_t and_or(uint32_t v, uint32_t mask, uint32_t magic)
 
 struct MmaConst {
     uint32_t mask, magic;
+    uint32_t mask_up;      // 3 bits: the mask of the fields three bits further up
 };
 
 template <int BITS>
@@ -598,8 +599,10 @@ __device__ inline MmaConst mma_constants()
     MmaConst c;
     c.mask = BITS == 4 ? 0x000f000fu : BITS == 2 ? 0x00030003u : 0x00070007u;
     c.magic = QG_MMA_MAGIC;
+    c.mask_up = 0x00380038u;
     asm("" : "+s"(c.mask));
     asm("" : "+v"(c.magic));
+    asm("" : "+s"(c.mask_up));
     return c;
 }
 
@@ -637,21 +640,26 @@ __device__ inline void mma_unpack(const uint32_t *w, const MmaConst &c, MmaOpera
 #pragma unroll
         for (int j = 0; j < 8; ++j) op[j >> 2].r[j & 3] = and_or(w[0] >> (2 * j), mask, magic);
     } else {
+        // The high field of a byte is taken where it stands, three bits up in the mantissa:
+        // those elements are 128 + 8 q instead of 128 + q (still exact in bf16), the x values
+        // they meet are stored divided by 8, and the group's closing accounts for the offset
+        // 16 instead of 128 (gemv_mma).  One shift per word instead of three.
         const uint32_t t = ((w[0] >> 6) & 0x03030303u) | ((w[1] >> 4) & 0x0c0c0c0cu) | ((w[2] >> 2) & 0x30303030u);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const uint32_t src = k < 3 ? w[k] : t;
+            const uint32_t up = src >> 8;
             op[k].r[0] = and_or(src, mask, magic);
-            op[k].r[1] = and_or(src >> 3, mask, magic);
-            op[k].r[2] = and_or(src >> 8, mask, magic);
-            op[k].r[3] = and_or(src >> 11, mask, magic);
+            op[k].r[1] = and_or(src, c.mask_up, magic);
+            op[k].r[2] = and_or(up, mask, magic);
+            op[k].r[3] = and_or(up, c.mask_up, magic);
         }
     }
 }
 
 // x-hat of the groups of a step from the per-lane x values (Algorithm 1's sum of x)
 template <int BITS, int GPS>
-__device__ inline void step_group_sums(const StepData<BITS, GPS> &d, float *xhat)
+__device__ inline void step_group_sums(const StepData<BITS, GPS> &d, float *xhat, float weight = 1.0f)
 {
     using D = StepData<BITS, GPS>;
     constexpr int G = codes_per_step<BITS>() / GPS;
@@ -661,11 +669,12 @@ __device__ inline void step_group_sums(const StepData<BITS, GPS> &d, float *xhat
             float v = 0.0f;
 #pragma unroll
             for (int i = 0; i < G / 128; ++i) v += d.xv[g * (G / 128) + i].x + d.xv[g * (G / 128) + i].y;
-            segment_sums<64>(v, &xhat[g]);
+            segment_sums<64>(v * weight, &xhat[g]);
         }
     } else {
 #pragma unroll
-        for (int i = 0; i < D::NXV; ++i) segment_sums<G / 2>(d.xv[i].x + d.xv[i].y, &xhat[i * (128 / G)]);
+        for (int i = 0; i < D::NXV; ++i)
+            segment_sums<G / 2>((d.xv[i].x + d.xv[i].y) * weight, &xhat[i * (128 / G)]);
     }
 }
 
@@ -725,11 +734,15 @@ __global__ __launch_bounds__(512) void gemv_mma(QG_FIRST_BLOCKS, const GemvArgs 
 #pragma unroll
     for (int b = 0; b < 2; ++b) abase[b] = row < 3 ? &xs[wave][b][row][half * 8] : &zeros[half * 8];
 
+    // 3 bits: this lane's two x values meet codes taken three bits up (8 q) if k % 8 >= 4,
+    // i.e. lane % 4 >= 2; they are stored divided by 8 (exact) and summed apart for x-hat
+    const bool up_class = BITS == 3 && (lane & 2);
+    const float xscale = up_class ? 0.125f : 1.0f;
     // splits the step's x values into three bf16 parts and stores them for the A operands
     auto stage_x = [&](const D &d, int buf) {
 #pragma unroll
         for (int i = 0; i < NXV; ++i) {
-            mma_floatx2 r = {d.xv[i].x, d.xv[i].y};
+            mma_floatx2 r = {d.xv[i].x * xscale, d.xv[i].y * xscale};
 #pragma unroll
             for (int part = 0; part < 3; ++part) {
                 const mma_bf16x2 h = __builtin_convertvector(r, mma_bf16x2);     // round to nearest even
@@ -746,8 +759,15 @@ __global__ __launch_bounds__(512) void gemv_mma(QG_FIRST_BLOCKS, const GemvArgs 
     float yacc = 0.0f;
 
     auto compute = [&](const D &d, int step, int buf) {
-        float xhat[GPS];
-        step_group_sums<BITS, GPS>(d, xhat);
+        // x-hat of the step's groups; at 3 bits apart for the codes read as 128 + q (xhat) and
+        // as 128 + 8 q (xhat_up)
+        float xhat[GPS], xhat_up[GPS];
+        if constexpr (BITS == 3) {
+            step_group_sums<BITS, GPS>(d, xhat, up_class ? 0.0f : 1.0f);
+            step_group_sums<BITS, GPS>(d, xhat_up, up_class ? 1.0f : 0.0f);
+        } else {
+            step_group_sums<BITS, GPS>(d, xhat);
+        }
         mma_floatx16 accP, accQ;
 #pragma unroll
         for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accQ[i] = 0.0f; }
@@ -781,8 +801,10 @@ __global__ __launch_bounds__(512) void gemv_mma(QG_FIRST_BLOCKS, const GemvArgs 
                 const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tp), __float_as_uint(tq), false, false);
                 const float tsum = __uint_as_float(sw[0]);           // lane l: output l of the tile
                 const uint32_t zword = d.zw[D::ZW > 1 ? gs / D::ZPER : 0];
-                const float zf = (float)(((zword >> (F::ZBITS * (gabs % D::ZPER))) & ((1u << F::ZBITS) - 1u)) + 128u);
-                yacc = fmaf(d.s[gs], fmaf(-zf, xhat[gs], tsum), yacc);
+                const uint32_t zq = (zword >> (F::ZBITS * (gabs % D::ZPER))) & ((1u << F::ZBITS) - 1u);
+                float tz = fmaf(-(float)(zq + 128u), xhat[gs], tsum);
+                if constexpr (BITS == 3) tz = fmaf(-(float)(zq + 16u), xhat_up[gs], tz);
+                yacc = fmaf(d.s[gs], tz, yacc);
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accQ[i] = 0.0f; }
             }
