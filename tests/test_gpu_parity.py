@@ -402,6 +402,38 @@ def test_full_size_matrix(qg, oracle, name, index):
     assert err <= TOL_FP32, err
 
 
+def _random_format(rng):
+    bits = int(rng.choice([2, 3, 4]))
+    cell = {4: 8, 2: 16, 3: 32}[bits]
+    mult = int(rng.choice([1, 1, 2, 4, 4, 8, 16]))
+    group = cell * mult
+    if bits == 3 and mult == 16:
+        group = 256
+    return bits, group
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_gemv_random_shapes_and_launch_shapes(qg, oracle, seed):
+    # seeded sweep over the launch-shape logic: ragged N, K from one group to many steps, every
+    # format, team sizes / bytes per wavefront / kernel picked at random
+    rng = np.random.default_rng(7000 + seed)
+    for case in range(8):
+        bits, group = _random_format(rng)
+        ngroups = int(rng.integers(1, 1 + max(1, 6000 // group)))
+        if rng.random() < 0.2:
+            group, ngroups = group * ngroups, 1                     # one group per output
+            if group > 8192:
+                group = 8192 // ({4: 8, 2: 16, 3: 32}[bits]) * ({4: 8, 2: 16, 3: 32}[bits])
+        K = group * ngroups
+        N = int(rng.integers(1, 400))
+        tuning = (int(rng.choice([0, 1, 2, 4, 7, 8, 12, 16])), int(rng.choice([0, 4096, 8192, 16384, 65536])),
+                  int(rng.choice([0, 1, 2])))
+        _announce("gemv random", seed, case, N, K, bits, group, tuning)
+        W, x = synth.small_case(seed * 100 + case, N, K, 0.02, bool(rng.integers(0, 2)))
+        err = _gemv_case(qg, oracle, W, x, bits, group, tuning)
+        assert err <= TOL_FP32, (N, K, bits, group, tuning, err)
+
+
 # ------------------------------------------------------------------ small-M GEMM (bf16 MFMA path)
 
 TOL_BF16 = 1e-2
@@ -527,6 +559,32 @@ def test_gemm_small_every_workgroup_shape(qg, oracle, shape, N, K, group):
         finally:
             qg.qg_set_gemm_tuning(0, 0)
         assert err <= TOL_BF16, (splits, err)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_gemm_small_random_shapes(qg, oracle, seed):
+    # seeded sweep: ragged N, M and step counts, the group sizes of the matrix-core path, split
+    # counts and workgroup shapes picked at random (a shape that does not fit M is ignored)
+    rng = np.random.default_rng(8000 + seed)
+    for case in range(6):
+        group = int(rng.choice([32, 64, 128, 128, 256, 384]))
+        steps = int(rng.integers(1, 24))
+        K = 128 * steps
+        if K % group:
+            K = group * max(1, K // group)
+            if K % 128:
+                K *= 128 // np.gcd(K, 128)
+        N = int(rng.integers(1, 700))
+        M = int(rng.integers(1, 129))
+        splits, shape = int(rng.integers(0, 9)), int(rng.integers(0, 13))
+        _announce("gemm random", seed, case, N, K, group, M, splits, shape)
+        W, X = synth.small_case(seed * 100 + case + 50, N, K, 0.02, True, m=max(M, 2))
+        qg.qg_set_gemm_tuning(splits, shape)
+        try:
+            err = _gemm_case(qg, oracle, W, X[:M], 4, group)
+        finally:
+            qg.qg_set_gemm_tuning(0, 0)
+        assert err <= TOL_BF16, (N, K, group, M, splits, shape, err)
 
 
 @pytest.mark.parametrize("index", [0, 1, 2])
