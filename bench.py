@@ -279,6 +279,7 @@ def main():
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
     if args.sweep:
+        qg.qg_set_gemv_tuning(args.wpb, args.bytes_per_wave, args.kernel)
         print(json.dumps(bench_sweep(qg, args)))
         return
     if args.offline:

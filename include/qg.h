@@ -148,7 +148,8 @@ int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
  * built-in choice.  waves_per_block in 1..16 = most wavefronts that share one tile of 64
  * outputs inside a workgroup; bytes_per_wave = packed code bytes one wavefront streams;
  * kernel = 1: multiply-adds on the vector ALU, 2: on the matrix cores (where that kernel
- * exists: groups of at least two cells and at most one step). */
+ * exists: groups of at least two cells and at most one step, and, at 2 and 3 bits, groups
+ * of whole steps). */
 int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel);
 /* Search for the fastest launch shape of one grouped launch by timing -- this machine's
  * counterpart of the paper's parameter search (Section 3, Algorithm 4).  `descs` holds `sets`

@@ -831,6 +831,164 @@ __global__ __launch_bounds__(512) void gemv_mma(QG_FIRST_BLOCKS, const GemvArgs 
 }
 
 // ---------------------------------------------------------------------------------------
+// gemv_mma for groups that are a whole number of steps (G = 256, ..., up to one group per
+// output, the full-column form of eq. (1)): the accumulators of the matrix instructions run
+// across steps, and a group -- or the piece of it that lies in this wavefront's range, since
+// s (sum q x - z sum x) is linear in the two sums -- is closed when it ends.  No per-step
+// group bookkeeping is left, which is what the 2-bit kernel spends a third of its vector
+// instructions on at small groups.
+// ---------------------------------------------------------------------------------------
+template <int BITS>
+__global__ __launch_bounds__(512) void gemv_mma_long(QG_FIRST_BLOCKS, const GemvArgs A)
+{
+    using F = Fmt<BITS>;
+    constexpr int L = loads_per_step<BITS>();
+    constexpr int S = codes_per_step<BITS>();
+    constexpr int CELLS = cells_per_step<BITS>();
+    constexpr int OPS = mma_ops<BITS>();
+    constexpr int NXV = S / 128;
+    constexpr int ZPER = 32 / F::ZBITS;
+    using D = StepData<BITS, 0>;
+    __shared__ float red[16][QG_WAVE];
+    __shared__ __attribute__((aligned(16))) lds_u16 zeros[S];
+    extern __shared__ __attribute__((aligned(16))) lds_u16 xs_raw[];
+    lds_u16(*xs)[2][3][S] = (lds_u16(*)[2][3][S])xs_raw;
+
+    const int pi = find_problem(fb_a, fb_b, fb_c, A, blockIdx.x);
+    const GemvProblem P = A.p[pi];
+    pin_problem(P);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int spg = P.steps_per_group;
+    const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.steps, wave);
+    if (!job.work) return;                      // no work: leave before the barrier
+    const int tile = job.tile, s0 = job.item0, s1 = job.item1;
+
+    TileView T;
+    T.codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
+    T.scales = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
+    T.zeros = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+    T.x = P.x;
+
+#pragma unroll
+    for (int i = lane; i < S; i += QG_WAVE) zeros[i] = 0;
+
+    int xpos[NXV][2];
+#pragma unroll
+    for (int i = 0; i < NXV; ++i)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int k = 128 * i + 2 * lane + e;
+            const int cell = k / F::CELL, slot = mma_slot<BITS>(k % F::CELL);
+            xpos[i][e] = (((cell >> 1) * OPS + (slot >> 3)) * 2 + (cell & 1)) * 8 + (slot & 7);
+        }
+    const int row = lane & 31, half = lane >> 5;
+    const lds_u16 *abase[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) abase[b] = row < 3 ? &xs[wave][b][row][half * 8] : &zeros[half * 8];
+
+    // 3 bits: see gemv_mma (codes taken three bits up meet x / 8 and have their own x-hat)
+    const bool up_class = BITS == 3 && (lane & 2);
+    const float xscale = up_class ? 0.125f : 1.0f;
+    float xacc = 0.0f, xacc_up = 0.0f;            // this lane's x values of the running piece
+    auto stage_x = [&](const D &d, int buf) {
+#pragma unroll
+        for (int i = 0; i < NXV; ++i) {
+            mma_floatx2 r = {d.xv[i].x * xscale, d.xv[i].y * xscale};
+#pragma unroll
+            for (int part = 0; part < 3; ++part) {
+                const mma_bf16x2 h = __builtin_convertvector(r, mma_bf16x2);
+                const uint32_t bits = *(const uint32_t *)&h;
+                xs[wave][buf][part][xpos[i][0]] = (uint16_t)bits;
+                xs[wave][buf][part][xpos[i][1]] = (uint16_t)(bits >> 16);
+                r[0] -= __uint_as_float(bits << 16);
+                r[1] -= __uint_as_float(bits & 0xffff0000u);
+            }
+        }
+    };
+
+    const MmaConst mc = mma_constants<BITS>();
+    float yacc = 0.0f;
+    mma_floatx16 accP, accQ;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accQ[i] = 0.0f; }
+
+    auto compute = [&](const D &d, int buf) {
+#pragma unroll
+        for (int i = 0; i < NXV; ++i) {
+            const float v = d.xv[i].x + d.xv[i].y;
+            if (up_class) xacc_up += v; else xacc += v;
+        }
+#pragma unroll
+        for (int cp = 0; cp < CELLS / 2; ++cp) {
+            uint32_t wp[F::PLANES], wq[F::PLANES];
+            const int c0 = 2 * cp, u = c0 >> 2, j = c0 & 3;
+#pragma unroll
+            for (int pl = 0; pl < F::PLANES; ++pl) {
+                const auto sw = __builtin_amdgcn_permlane32_swap(word_of(d.v[u * F::PLANES + pl], j),
+                                                                 word_of(d.v[u * F::PLANES + pl], j + 1), false, false);
+                wp[pl] = sw[0];
+                wq[pl] = sw[1];
+            }
+            MmaOperand bp[OPS], bq[OPS];
+            mma_unpack<BITS>(wp, mc, bp);
+            mma_unpack<BITS>(wq, mc, bq);
+#pragma unroll
+            for (int op = 0; op < OPS; ++op) {
+                MmaOperand a;
+                a.q = *(const lds_u128 *)(abase[buf] + (cp * OPS + op) * 16);
+                accP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bp[op].v, accP, 0, 0, 0);
+                accQ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bq[op].v, accQ, 0, 0, 0);
+            }
+        }
+    };
+
+    int g = s0 / spg;                                   // running group
+    int left = (g + 1) * spg - s0;                      // its steps still to come
+    // closes the piece of group g this wavefront has seen, if step s ends the group or the range
+    auto close_group = [&](int s) {
+        if (--left != 0 && s + 1 != s1) return;
+        float xhat, xhat_up = 0.0f;
+        segment_sums<64>(xacc, &xhat);
+        if constexpr (BITS == 3) segment_sums<64>(xacc_up, &xhat_up);
+        const float tp = accP[0] + accP[1] + accP[2], tq = accQ[0] + accQ[1] + accQ[2];
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tp), __float_as_uint(tq), false, false);
+        const float tsum = __uint_as_float(sw[0]);           // lane l: output l of the tile
+        const float scale = T.scales[(size_t)g * QG_WAVE];
+        const uint32_t zword = T.zeros[(size_t)(g / ZPER) * QG_WAVE];
+        const uint32_t zq = (zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u);
+        float tz = fmaf(-(float)(zq + 128u), xhat, tsum);
+        if constexpr (BITS == 3) tz = fmaf(-(float)(zq + 16u), xhat_up, tz);
+        yacc = fmaf(scale, tz, yacc);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accQ[i] = 0.0f; }
+        xacc = 0.0f;
+        xacc_up = 0.0f;
+        ++g;
+        left = spg;
+    };
+
+    const int last = s1 - 1;
+    D da, db;
+    fetch_step(da, T, s0, lane);
+    stage_x(da, 0);
+    for (int s = s0; s < s1; s += 2) {
+        const int sb = s + 1 < last ? s + 1 : last;
+        const int sc = s + 2 < last ? s + 2 : last;
+        fetch_step(db, T, sb, lane);
+        compute(da, 0);
+        close_group(s);
+        if (s + 1 >= s1) break;                       // odd number of steps
+        stage_x(db, 1);
+        fetch_step(da, T, sc, lane);
+        compute(db, 1);
+        close_group(sb);
+        stage_x(da, 0);
+    }
+    finish_tile(P, job, yacc, red);
+}
+
+// ---------------------------------------------------------------------------------------
 // Up to 16 activation rows at once (a few prompt tokens): Y = X What^T with the launch
 // structure of the GEMV -- one wavefront per 64 outputs and K range, no workgroup barrier in
 // the loop, K split over the wavefronts of a team -- and the arithmetic of gemv_mma: 4-bit
@@ -1268,9 +1426,26 @@ void launch_mma(int cpg, unsigned blocks, unsigned threads, hipStream_t st, cons
     }
 }
 
+template <int BITS>
+void launch_mma_long(unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+{
+    const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 3 * codes_per_step<BITS>() * sizeof(uint16_t);
+    hipLaunchKernelGGL(gemv_mma_long<BITS>, dim3(blocks), dim3(threads), lds, st, first_blocks(A).a,
+                       first_blocks(A).b, first_blocks(A).c, A);
+}
+
 // Whether a static-group problem runs on the matrix cores.  That kernel needs a group of at
 // least two cells.  Measured on the layer sets: ahead at 3 bits (by 8 %), level at 2 bits,
 // behind at 4 bits, where the vector-ALU kernel is bound by memory anyway.
+// The same for groups of whole steps (gemv_mma_long).  Measured on the layer sets with G = 256
+// and G = K: 8-10 % ahead at 3 bits, level or behind at 2 bits.
+bool use_mma_long(int bits)
+{
+    if (bits == 4) return false;
+    if (g_tune_kernel) return g_tune_kernel == 2;
+    return bits == 3;
+}
+
 bool use_mma(int bits, int cpg)
 {
     if (cpg < 2) return false;
@@ -1313,7 +1488,8 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     // `target` per wavefront so that the chip is still covered.
     // wavefronts per team, at most (measured: 12 is best for the 4-bit kernels, 8 for the
     // 2- and 3-bit ones, which hold more registers per wavefront)
-    const bool mma = rows == 0 && kind == KIND_STATIC && use_mma(L[0].bits, L[0].group / L[0].cell);
+    const bool mma = rows == 0 && ((kind == KIND_STATIC && use_mma(L[0].bits, L[0].group / L[0].cell)) ||
+                                   (kind == KIND_RUNTIME && use_mma_long(L[0].bits)));
     int cap = g_tune_wpb > 0 ? g_tune_wpb : (L[0].bits == 4 ? 12 : 8);
     if (rows > 0 && cap > 8) cap = 8;          // gemm_rows16 is built for at most 8 wavefronts
     if (mma) {                                 // the matrix-core kernel is built for at most 8 wavefronts;
@@ -1418,6 +1594,9 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         } else if (bits == 4) launch_static<4>(cpg, blocks, threads, st, A);
         else if (bits == 2) launch_static<2>(cpg, blocks, threads, st, A);
         else launch_static<3>(cpg, blocks, threads, st, A);
+    } else if (kind == KIND_RUNTIME && mma) {
+        if (bits == 2) launch_mma_long<2>(blocks, threads, st, A);
+        else launch_mma_long<3>(blocks, threads, st, A);
     } else if (kind == KIND_RUNTIME) {
         if (bits == 4) hipLaunchKernelGGL(gemv_runtime<4>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
         else if (bits == 2) hipLaunchKernelGGL(gemv_runtime<2>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
