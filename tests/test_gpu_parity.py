@@ -217,7 +217,9 @@ def test_gemv_matches_oracle(qg, oracle, N, K, bits, group, kernel):
 
 
 @pytest.mark.parametrize("bits,group", [(4, 16), (4, 32), (4, 64), (4, 128), (2, 32), (2, 64), (2, 128), (2, 256),
-                                        (3, 64), (3, 128), (3, 256)])
+                                        (3, 64), (3, 128), (3, 256),
+                                        # groups of whole steps: the accumulators run across steps
+                                        (2, 512), (2, 2048), (3, 512), (3, 1024), (3, 2048)])
 def test_gemv_matrix_core_kernel_every_group_size(qg, oracle, bits, group):
     # x with a wide range of magnitudes and both signs: its split into three bf16 parts must be exact
     _announce("gemv matrix cores", bits, group)
@@ -231,7 +233,8 @@ def test_gemv_matrix_core_kernel_every_group_size(qg, oracle, bits, group):
 @pytest.mark.parametrize("tuning", [(1, 4096, 1), (2, 4096, 1), (4, 8192, 1), (8, 4096, 1), (16, 4096, 1), (4, 65536, 1),
                                     (1, 4096, 2), (3, 8192, 2), (8, 4096, 2), (16, 4096, 2), (4, 65536, 2)])
 @pytest.mark.parametrize("N,K,bits,group", [(200, 4096, 4, 128), (130, 3072, 3, 64), (130, 4096, 2, 32),
-                                            (70, 4096, 4, 1024), (70, 5632, 4, 5632), (70, 3840, 3, 1280)])
+                                            (70, 4096, 4, 1024), (70, 5632, 4, 5632), (70, 3840, 3, 1280),
+                                            (70, 5632, 2, 2816), (130, 11008, 3, 11008)])
 def test_gemv_k_split_shapes(qg, oracle, N, K, bits, group, tuning):
     # the same product under different wavefront / workgroup splits of K, including the
     # path where the last-arriving workgroup adds the partial vectors
