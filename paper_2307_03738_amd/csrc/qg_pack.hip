@@ -21,13 +21,22 @@ __device__ inline void rows_to_lds(const uint8_t *__restrict__ v, int64_t rows, 
 {
     constexpr int PITCH = SPAN + 16;
     if (wide) {
+        // all loads of the thread are issued before the first is stored
         constexpr int PIECES = SPAN / 16;
-        for (int i = threadIdx.x; i < QG_WAVE * PIECES; i += PK_THREADS) {
+        constexpr int PER = QG_WAVE * PIECES / PK_THREADS;
+        uint4 val[PER];
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int i = threadIdx.x + j * PK_THREADS;
             const int r = i / PIECES, p = i % PIECES;
             const int64_t n = r0 + r, c = c0 + 16 * p;
-            uint4 val = make_uint4(0u, 0u, 0u, 0u);
-            if (n < rows && c < cols) val = *(const uint4 *)(v + n * cols + c);
-            *(uint4 *)(lds + r * PITCH + 16 * p) = val;
+            val[j] = make_uint4(0u, 0u, 0u, 0u);
+            if (n < rows && c < cols) val[j] = *(const uint4 *)(v + n * cols + c);
+        }
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int i = threadIdx.x + j * PK_THREADS;
+            *(uint4 *)(lds + (i / PIECES) * PITCH + 16 * (i % PIECES)) = val[j];
         }
     } else {
         for (int i = threadIdx.x; i < QG_WAVE * SPAN; i += PK_THREADS) {
@@ -364,13 +373,19 @@ __global__ __launch_bounds__(PK_THREADS) void scales_pack(const float *__restric
     const int64_t tile = blockIdx.x / spans;
     const int64_t g0 = (int64_t)(blockIdx.x % spans) * QG_WAVE;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int r = wave; r < QG_WAVE; r += 4) {
-        const int64_t n = tile * QG_WAVE + r, g = g0 + lane;
-        lds[r][lane] = (n < N && g < G) ? s[n * G + g] : 0.0f;
+    float val[QG_WAVE / 4];                    // all loads of the thread before the first store
+#pragma unroll
+    for (int j = 0; j < QG_WAVE / 4; ++j) {
+        const int64_t n = tile * QG_WAVE + wave + 4 * j, g = g0 + lane;
+        val[j] = (n < N && g < G) ? s[n * G + g] : 0.0f;
     }
+#pragma unroll
+    for (int j = 0; j < QG_WAVE / 4; ++j) lds[wave + 4 * j][lane] = val[j];
     __syncthreads();
     const int64_t n = tile * QG_WAVE + lane;
-    for (int c = wave; c < QG_WAVE; c += 4) {
+#pragma unroll
+    for (int j = 0; j < QG_WAVE / 4; ++j) {
+        const int c = wave + 4 * j;
         const int64_t g = g0 + c;
         if (g >= G) break;
         if (TILED) out[(tile * G + g) * QG_WAVE + lane] = lds[lane][c];
@@ -387,12 +402,15 @@ __global__ __launch_bounds__(PK_THREADS) void scales_unpack(const float *__restr
     const int64_t g0 = (int64_t)(blockIdx.x % spans) * QG_WAVE;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t nl = tile * QG_WAVE + lane;
-    for (int c = wave; c < QG_WAVE; c += 4) {
-        const int64_t g = g0 + c;
-        float val = 0.0f;
-        if (g < G && (TILED || nl < N)) val = in[TILED ? (tile * G + g) * QG_WAVE + lane : g * N + nl];
-        lds[lane][c] = val;
+    float val[QG_WAVE / 4];
+#pragma unroll
+    for (int j = 0; j < QG_WAVE / 4; ++j) {
+        const int64_t g = g0 + wave + 4 * j;
+        val[j] = 0.0f;
+        if (g < G && (TILED || nl < N)) val[j] = in[TILED ? (tile * G + g) * QG_WAVE + lane : g * N + nl];
     }
+#pragma unroll
+    for (int j = 0; j < QG_WAVE / 4; ++j) lds[lane][wave + 4 * j] = val[j];
     __syncthreads();
     for (int r = wave; r < QG_WAVE; r += 4) {
         const int64_t n = tile * QG_WAVE + r, g = g0 + lane;
