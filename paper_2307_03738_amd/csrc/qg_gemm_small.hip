@@ -602,13 +602,20 @@ __global__ __launch_bounds__(TN * 64, MB == 2 ? 2 : 1) void gemm_wide_b4(const G
         }
 }
 
+// Y = sum of the K-split partial results, in split order.  All (up to 8) loads of a thread
+// are issued before the first addition; a loop over a run-time split count would wait for
+// each load in turn.
 __global__ void add_splits(const float *__restrict__ partial, int splits, size_t count,
                            float *__restrict__ Y)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= count) return;
-    float t = partial[i];
-    for (int s = 1; s < splits; ++s) t += partial[(size_t)s * count + i];
+    float v[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) v[s] = s < splits ? partial[(size_t)s * count + i] : 0.0f;
+    float t = v[0];
+#pragma unroll
+    for (int s = 1; s < 8; ++s) t += v[s];       // the missing ones add +0.0
     Y[i] = t;
 }
 
