@@ -268,7 +268,7 @@ def main():
                     help="also run one plain device copy of 256 MiB (reference for HBM byte counters)")
     ap.add_argument("--wpb", type=int, default=0)
     ap.add_argument("--bytes-per-wave", type=int, default=0)
-    ap.add_argument("--kernel", type=int, default=0, help="0 built-in choice, 1 vector-ALU GEMV, 2 matrix-core GEMV")
+    ap.add_argument("--kernel", type=int, default=0, help="0 built-in choice, 1 vector-ALU GEMV, 2 matrix-core GEMV (32x32x16), 3 matrix-core GEMV (4x4x4)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: the path has no multi-GPU part (run with --gpus 1)",

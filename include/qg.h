@@ -147,16 +147,17 @@ int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
 /* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe).  0 restores the
  * built-in choice.  waves_per_block in 1..16 = most wavefronts that share one tile of 64
  * outputs inside a workgroup; bytes_per_wave = packed code bytes one wavefront streams;
- * kernel = 1: multiply-adds on the vector ALU, 2: on the matrix cores (where that kernel
- * exists: groups of at least two cells and at most one step, and, at 2 and 3 bits, groups
- * of whole steps). */
+ * kernel = 1: multiply-adds on the vector ALU; 2: on the matrix cores with the 32 x 32 x 16
+ * instruction (where that kernel exists: groups of at least two cells and at most one step,
+ * and, at 2 and 3 bits, groups of whole steps); 3: with the 4 x 4 x 4 instruction (groups of
+ * whole cells up to one step, and, at 2 and 3 bits, groups of whole steps). */
 int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel);
 /* Search for the fastest launch shape of one grouped launch by timing -- this machine's
  * counterpart of the paper's parameter search (Section 3, Algorithm 4).  `descs` holds `sets`
  * copies of the launch back to back (set i at descs + i * count; same shapes, normally
  * different packed buffers, so that a cache cannot serve the weights; sets = 1 times one set
- * again and again).  Runs the launch `repeats` times, rotating over the sets, for each of 50
- * candidates (team size x bytes per wavefront x vector-ALU or matrix-core kernel), WAITS for
+ * again and again).  Runs the launch `repeats` times, rotating over the sets, for each of 75
+ * candidates (team size x bytes per wavefront x vector-ALU or one of the two matrix-core kernels), WAITS for
  * the GPU (the only call that does), leaves the fastest installed as qg_set_gemv_tuning would,
  * and reports it (HOST pointers, each may be NULL; best_us = microseconds per launch).  The
  * outputs y are overwritten as by qg_gemv_grouped; all sets share the workspace. */

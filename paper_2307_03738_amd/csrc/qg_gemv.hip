@@ -989,6 +989,217 @@ __global__ __launch_bounds__(512) void gemv_mma_long(QG_FIRST_BLOCKS, const Gemv
 }
 
 // ---------------------------------------------------------------------------------------
+// The matrix-core GEMV on v_mfma_f32_4x4x4_16B_bf16: 16 independent 4 x 4 x 4 products per
+// instruction, one per group of four lanes.  Lane l supplies the B column of ITS OWN output
+// (four consecutive operand elements = four codes 128 + q), the A rows of a block are the
+// three bf16 parts of the four x values those codes meet (row 3 is zero; lane l supplies row
+// l % 4, the same in every block), and lane l receives its output's three partial sums in
+// registers 0-2 of the result.  Compared with gemv_mma (32 x 32 x 16): nothing is exchanged
+// between lanes, the accumulator is 4 registers instead of 32, and 64 outputs x 256 k take
+// 64 instructions of 8 cycles instead of 32 of 32 cycles.  The unpacking (mma_unpack) and
+// the exactness argument are the same; so is the 3-bit in-place high field.
+//
+// CPG > 0: groups of CPG cells inside a step (closed at compile-time positions).
+// CPG == 0: groups of whole steps; the accumulators run across steps (see gemv_mma_long).
+// ---------------------------------------------------------------------------------------
+typedef short mma4_ab __attribute__((ext_vector_type(4)));
+typedef float mma4_acc __attribute__((ext_vector_type(4)));
+typedef uint2 __attribute__((may_alias)) lds_u64;
+
+// Position (operand of the cell, element) of code c of a cell: operand o of a cell is the
+// register pair (2 o, 2 o + 1) of mma_unpack's output; returns 4 * operand + element.
+template <int BITS>
+__device__ inline int mma4_slot(int c)
+{
+    if constexpr (BITS == 3) {
+        const int w = c >> 3, r = c & 7;            // word (A, B, C, T), code within it
+        return (2 * w + (r & 1)) * 4 + (r >> 1);
+    } else {
+        constexpr int HALF = BITS == 2 ? 8 : 4;     // register j holds codes j and j + HALF
+        const int j = c % HALF, hi = c / HALF;
+        return (j >> 1) * 4 + (j & 1) * 2 + hi;
+    }
+}
+
+template <int BITS, int CPG>
+__global__ __launch_bounds__(512) void gemv_mma4(QG_FIRST_BLOCKS, const GemvArgs A)
+{
+    using F = Fmt<BITS>;
+    constexpr int L = loads_per_step<BITS>();
+    constexpr int S = codes_per_step<BITS>();
+    constexpr int CELLS = cells_per_step<BITS>();
+    constexpr int GPS = CPG > 0 ? CELLS / CPG : 0;
+    constexpr int OPC = F::CELL / 4;                // matrix instructions (operands) per cell
+    constexpr int NXV = S / 128;
+    constexpr int ZPER = 32 / F::ZBITS;
+    constexpr int PITCH = S + 8;                    // u16 per part: the four parts on different banks
+    using D = StepData<BITS, GPS>;
+    __shared__ float red[16][QG_WAVE];
+    // per wavefront and buffer: the three parts of the step's x in operand order, and a part of zeros
+    extern __shared__ __attribute__((aligned(16))) lds_u16 xs_raw[];
+    lds_u16(*xs)[2][4][PITCH] = (lds_u16(*)[2][4][PITCH])xs_raw;
+
+    const int pi = find_problem(fb_a, fb_b, fb_c, A, blockIdx.x);
+    const GemvProblem P = A.p[pi];
+    pin_problem(P);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.steps, wave);
+    if (!job.work) return;                      // no work: leave before the barrier
+    const int tile = job.tile, s0 = job.item0, s1 = job.item1;
+
+    TileView T;
+    T.codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
+    T.scales = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
+    T.zeros = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+    T.x = P.x;
+
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int i = lane; i < PITCH; i += QG_WAVE) xs[wave][b][3][i] = 0;
+
+    // where this lane's x values go: x[128 i + 2 lane + e] of the step
+    int xpos[NXV][2];
+#pragma unroll
+    for (int i = 0; i < NXV; ++i)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int k = 128 * i + 2 * lane + e;
+            xpos[i][e] = (k / F::CELL) * (OPC * 4) + mma4_slot<BITS>(k % F::CELL);
+        }
+    const lds_u16 *abase[2] = {&xs[wave][0][lane & 3][0], &xs[wave][1][lane & 3][0]};
+
+    const bool up_class = BITS == 3 && (lane & 2);      // see gemv_mma
+    const float xscale = up_class ? 0.125f : 1.0f;
+    auto stage_x = [&](const D &d, int buf) {
+#pragma unroll
+        for (int i = 0; i < NXV; ++i) {
+            mma_floatx2 r = {d.xv[i].x * xscale, d.xv[i].y * xscale};
+#pragma unroll
+            for (int part = 0; part < 3; ++part) {
+                const mma_bf16x2 h = __builtin_convertvector(r, mma_bf16x2);
+                const uint32_t bits = *(const uint32_t *)&h;
+                xs[wave][buf][part][xpos[i][0]] = (uint16_t)bits;
+                xs[wave][buf][part][xpos[i][1]] = (uint16_t)(bits >> 16);
+                r[0] -= __uint_as_float(bits << 16);
+                r[1] -= __uint_as_float(bits & 0xffff0000u);
+            }
+        }
+    };
+
+    const MmaConst mc = mma_constants<BITS>();
+    float yacc = 0.0f;
+    mma4_acc acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+    float xacc = 0.0f, xacc_up = 0.0f;              // CPG == 0: x of the running piece
+
+    // the matrix instructions of one cell: OPC operands, two per 128-bit read of A
+    auto cell_mfma = [&](const D &d, int cell, int buf) {
+        uint32_t w[F::PLANES];
+        const int u = cell >> 2, j = cell & 3;
+#pragma unroll
+        for (int pl = 0; pl < F::PLANES; ++pl) w[pl] = word_of(d.v[u * F::PLANES + pl], j);
+        MmaOperand op[mma_ops<BITS>()];
+        mma_unpack<BITS>(w, mc, op);
+#pragma unroll
+        for (int o = 0; o < OPC; o += 2) {
+            MmaOperand a;
+            a.q = *(const lds_u128 *)(abase[buf] + (cell * OPC + o) * 4);
+            const uint2 a0 = make_uint2(a.r[0], a.r[1]), a1 = make_uint2(a.r[2], a.r[3]);
+            const uint2 b0 = make_uint2(op[o >> 1].r[0], op[o >> 1].r[1]);
+            const uint2 b1 = make_uint2(op[o >> 1].r[2], op[o >> 1].r[3]);
+            acc0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(*(const mma4_ab *)&a0, *(const mma4_ab *)&b0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(*(const mma4_ab *)&a1, *(const mma4_ab *)&b1, acc1, 0, 0, 0);
+        }
+    };
+    // T of the finished group for this lane's output; clears the accumulators
+    auto take_sum = [&]() {
+        const float t = (acc0[0] + acc1[0]) + (acc0[1] + acc1[1]) + (acc0[2] + acc1[2]);
+        acc0 = mma4_acc{0.0f, 0.0f, 0.0f, 0.0f};
+        acc1 = mma4_acc{0.0f, 0.0f, 0.0f, 0.0f};
+        return t;
+    };
+
+    auto compute = [&](const D &d, int step, int buf) {
+        if constexpr (CPG > 0) {
+            float xhat[GPS], xhat_up[GPS];
+            if constexpr (BITS == 3) {
+                step_group_sums<BITS, GPS>(d, xhat, up_class ? 0.0f : 1.0f);
+                step_group_sums<BITS, GPS>(d, xhat_up, up_class ? 1.0f : 0.0f);
+            } else {
+                step_group_sums<BITS, GPS>(d, xhat);
+            }
+#pragma unroll
+            for (int cell = 0; cell < CELLS; ++cell) {
+                cell_mfma(d, cell, buf);
+                if ((cell + 1) % CPG == 0) {
+                    const int gs = (cell + 1) / CPG - 1;
+                    const int gabs = step * GPS + gs;
+                    const float tsum = take_sum();
+                    const uint32_t zword = d.zw[D::ZW > 1 ? gs / D::ZPER : 0];
+                    const uint32_t zq = (zword >> (F::ZBITS * (gabs % D::ZPER))) & ((1u << F::ZBITS) - 1u);
+                    float tz = fmaf(-(float)(zq + 128u), xhat[gs], tsum);
+                    if constexpr (BITS == 3) tz = fmaf(-(float)(zq + 16u), xhat_up[gs], tz);
+                    yacc = fmaf(d.s[gs], tz, yacc);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NXV; ++i) {
+                const float v = d.xv[i].x + d.xv[i].y;
+                if (up_class) xacc_up += v; else xacc += v;
+            }
+#pragma unroll
+            for (int cell = 0; cell < CELLS; ++cell) cell_mfma(d, cell, buf);
+        }
+    };
+
+    // CPG == 0: closes the piece of group g this wavefront has seen, if step s ends the group or the range
+    const int spg = P.steps_per_group;
+    int g = CPG == 0 ? s0 / spg : 0;
+    int left = CPG == 0 ? (g + 1) * spg - s0 : 0;
+    auto close_group = [&](int s) {
+        if constexpr (CPG == 0) {
+            if (--left != 0 && s + 1 != s1) return;
+            float xhat, xhat_up = 0.0f;
+            segment_sums<64>(xacc, &xhat);
+            if constexpr (BITS == 3) segment_sums<64>(xacc_up, &xhat_up);
+            const float tsum = take_sum();
+            const float scale = T.scales[(size_t)g * QG_WAVE];
+            const uint32_t zword = T.zeros[(size_t)(g / ZPER) * QG_WAVE];
+            const uint32_t zq = (zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u);
+            float tz = fmaf(-(float)(zq + 128u), xhat, tsum);
+            if constexpr (BITS == 3) tz = fmaf(-(float)(zq + 16u), xhat_up, tz);
+            yacc = fmaf(scale, tz, yacc);
+            xacc = 0.0f;
+            xacc_up = 0.0f;
+            ++g;
+            left = spg;
+        }
+    };
+
+    // two register buffers and two LDS buffers used alternately, as in gemv_static
+    const int last = s1 - 1;
+    D da, db;
+    fetch_step(da, T, s0, lane);
+    stage_x(da, 0);
+    for (int s = s0; s < s1; s += 2) {
+        const int sb = s + 1 < last ? s + 1 : last;
+        const int sc = s + 2 < last ? s + 2 : last;
+        fetch_step(db, T, sb, lane);
+        compute(da, s, 0);
+        close_group(s);
+        if (s + 1 >= s1) break;                       // odd number of steps
+        stage_x(db, 1);
+        fetch_step(da, T, sc, lane);
+        compute(db, sb, 1);
+        close_group(sb);
+        stage_x(da, 0);
+    }
+    finish_tile(P, job, yacc, red);
+}
+
+// ---------------------------------------------------------------------------------------
 // Up to 16 activation rows at once (a few prompt tokens): Y = X What^T with the launch
 // structure of the GEMV -- one wavefront per 64 outputs and K range, no workgroup barrier in
 // the loop, K split over the wavefronts of a team -- and the arithmetic of gemv_mma: 4-bit
@@ -1426,6 +1637,25 @@ void launch_mma(int cpg, unsigned blocks, unsigned threads, hipStream_t st, cons
     }
 }
 
+// gemv_mma4: cpg = cells per group, 0 for groups of whole steps
+template <int BITS>
+void launch_mma4(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+{
+    const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 4 * (codes_per_step<BITS>() + 8) * sizeof(uint16_t);
+    const FirstBlocks f = first_blocks(A);
+    switch (cpg) {
+    case 0: hipLaunchKernelGGL((gemv_mma4<BITS, 0>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
+    case 1: hipLaunchKernelGGL((gemv_mma4<BITS, 1>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
+    case 2: hipLaunchKernelGGL((gemv_mma4<BITS, 2>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
+    case 4: hipLaunchKernelGGL((gemv_mma4<BITS, 4>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
+    case 8: hipLaunchKernelGGL((gemv_mma4<BITS, 8>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
+    case 16:
+        if constexpr (BITS != 3)
+            hipLaunchKernelGGL((gemv_mma4<BITS, 16>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A);
+        break;
+    }
+}
+
 template <int BITS>
 void launch_mma_long(unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
 {
@@ -1434,23 +1664,20 @@ void launch_mma_long(unsigned blocks, unsigned threads, hipStream_t st, const Ge
                        first_blocks(A).b, first_blocks(A).c, A);
 }
 
-// Whether a static-group problem runs on the matrix cores.  That kernel needs a group of at
-// least two cells.  Measured on the layer sets: ahead at 3 bits (by 8 %), level at 2 bits,
-// behind at 4 bits, where the vector-ALU kernel is bound by memory anyway.
-// The same for groups of whole steps (gemv_mma_long).  Measured on the layer sets with G = 256
-// and G = K: 8-10 % ahead at 3 bits, level or behind at 2 bits.
-bool use_mma_long(int bits)
+// Which kernel multiplies: the vector ALU (gemv_static / gemv_runtime), the 32 x 32 x 16 matrix
+// instruction (gemv_mma, groups of at least two cells inside a step; gemv_mma_long, groups of
+// whole steps at 2 and 3 bits) or the 4 x 4 x 4 one (gemv_mma4, any group of the two kinds).
+// Measured on the three layer sets over G = 32 ... K: at 2 and 3 bits gemv_mma4 is ahead of
+// both others nearly everywhere (by 5-13 %, level at the smallest groups); at 4 bits the
+// vector-ALU kernel is bound by memory anyway.
+enum Mul { MUL_VALU, MUL_MMA32, MUL_MMA4 };
+Mul multiplier(int bits, int cpg, Kind kind)
 {
-    if (bits == 4) return false;
-    if (g_tune_kernel) return g_tune_kernel == 2;
-    return bits == 3;
-}
-
-bool use_mma(int bits, int cpg)
-{
-    if (cpg < 2) return false;
-    if (g_tune_kernel) return g_tune_kernel == 2;
-    return bits == 3;
+    if (kind != KIND_STATIC && kind != KIND_RUNTIME) return MUL_VALU;
+    const int want = g_tune_kernel ? g_tune_kernel : (bits == 4 ? 1 : 3);
+    if (want == 3 && (kind == KIND_STATIC || bits != 4)) return MUL_MMA4;
+    if (want == 2 && (kind == KIND_STATIC ? cpg >= 2 : bits != 4)) return MUL_MMA32;
+    return MUL_VALU;
 }
 
 // One launch for problems that share (bits, group, kernel kind).
@@ -1488,8 +1715,8 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     // `target` per wavefront so that the chip is still covered.
     // wavefronts per team, at most (measured: 12 is best for the 4-bit kernels, 8 for the
     // 2- and 3-bit ones, which hold more registers per wavefront)
-    const bool mma = rows == 0 && ((kind == KIND_STATIC && use_mma(L[0].bits, L[0].group / L[0].cell)) ||
-                                   (kind == KIND_RUNTIME && use_mma_long(L[0].bits)));
+    const Mul mul = rows == 0 ? multiplier(L[0].bits, L[0].group / L[0].cell, kind) : MUL_VALU;
+    const bool mma = mul != MUL_VALU;
     int cap = g_tune_wpb > 0 ? g_tune_wpb : (L[0].bits == 4 ? 12 : 8);
     if (rows > 0 && cap > 8) cap = 8;          // gemm_rows16 is built for at most 8 wavefronts
     if (mma) {                                 // the matrix-core kernel is built for at most 8 wavefronts;
@@ -1587,14 +1814,21 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         }
     } else if (kind == KIND_STATIC) {
         const int cpg = L[0].group / L[0].cell;
-        if (mma) {
+        if (mul == MUL_MMA4) {
+            if (bits == 4) launch_mma4<4>(cpg, blocks, threads, st, A);
+            else if (bits == 2) launch_mma4<2>(cpg, blocks, threads, st, A);
+            else launch_mma4<3>(cpg, blocks, threads, st, A);
+        } else if (mul == MUL_MMA32) {
             if (bits == 4) launch_mma<4>(cpg, blocks, threads, st, A);
             else if (bits == 2) launch_mma<2>(cpg, blocks, threads, st, A);
             else launch_mma<3>(cpg, blocks, threads, st, A);
         } else if (bits == 4) launch_static<4>(cpg, blocks, threads, st, A);
         else if (bits == 2) launch_static<2>(cpg, blocks, threads, st, A);
         else launch_static<3>(cpg, blocks, threads, st, A);
-    } else if (kind == KIND_RUNTIME && mma) {
+    } else if (kind == KIND_RUNTIME && mul == MUL_MMA4) {
+        if (bits == 2) launch_mma4<2>(0, blocks, threads, st, A);
+        else launch_mma4<3>(0, blocks, threads, st, A);
+    } else if (kind == KIND_RUNTIME && mul == MUL_MMA32) {
         if (bits == 2) launch_mma_long<2>(blocks, threads, st, A);
         else launch_mma_long<3>(blocks, threads, st, A);
     } else if (kind == KIND_RUNTIME) {
@@ -1613,7 +1847,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
 
 extern "C" int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel)
 {
-    if (waves_per_block < 0 || waves_per_block > 16 || bytes_per_wave < 0 || kernel < 0 || kernel > 2)
+    if (waves_per_block < 0 || waves_per_block > 16 || bytes_per_wave < 0 || kernel < 0 || kernel > 3)
         return QG_ERR_SHAPE;
     g_tune_wpb = waves_per_block;
     g_tune_bytes_per_wave = bytes_per_wave;
@@ -1790,7 +2024,7 @@ extern "C" int qg_gemv_autotune(const qg_gemv_desc *descs, int count, int sets, 
     static const int sizes[] = {0, 4096, 8192, 16384, 32768};
     int best[3] = {0, 0, 0};
     float best_ms = -1.0f;
-    for (int k = 1; k <= 2 && rc == QG_OK; ++k)
+    for (int k = 1; k <= 3 && rc == QG_OK; ++k)
         for (int a = 0; a < 5 && rc == QG_OK; ++a)
             for (int b = 0; b < 5 && rc == QG_OK; ++b) {
                 g_tune_wpb = teams[a];

@@ -220,18 +220,21 @@ def test_gemv_matches_oracle(qg, oracle, N, K, bits, group, kernel):
                                         (3, 64), (3, 128), (3, 256),
                                         # groups of whole steps: the accumulators run across steps
                                         (2, 512), (2, 2048), (3, 512), (3, 1024), (3, 2048)])
-def test_gemv_matrix_core_kernel_every_group_size(qg, oracle, bits, group):
+@pytest.mark.parametrize("kernel", [2, 3])
+def test_gemv_matrix_core_kernel_every_group_size(qg, oracle, bits, group, kernel):
     # x with a wide range of magnitudes and both signs: its split into three bf16 parts must be exact
-    _announce("gemv matrix cores", bits, group)
+    # (kernel 2: 32x32x16 matrix instruction, 3: 4x4x4)
+    _announce("gemv matrix cores", bits, group, kernel)
     N, K = 200, 2048
     W, x = synth.small_case(40 + bits + group, N, K, 0.02, True)
     x = (x * np.exp2(np.arange(K) % 40 - 20)).astype(np.float32)
-    err = _gemv_case(qg, oracle, W, x, bits, group, (0, 0, 2))
+    err = _gemv_case(qg, oracle, W, x, bits, group, (0, 0, kernel))
     assert err <= TOL_FP32, err
 
 
 @pytest.mark.parametrize("tuning", [(1, 4096, 1), (2, 4096, 1), (4, 8192, 1), (8, 4096, 1), (16, 4096, 1), (4, 65536, 1),
-                                    (1, 4096, 2), (3, 8192, 2), (8, 4096, 2), (16, 4096, 2), (4, 65536, 2)])
+                                    (1, 4096, 2), (3, 8192, 2), (8, 4096, 2), (16, 4096, 2), (4, 65536, 2),
+                                    (1, 4096, 3), (3, 8192, 3), (8, 4096, 3), (4, 65536, 3)])
 @pytest.mark.parametrize("N,K,bits,group", [(200, 4096, 4, 128), (130, 3072, 3, 64), (130, 4096, 2, 32),
                                             (70, 4096, 4, 1024), (70, 5632, 4, 5632), (70, 3840, 3, 1280),
                                             (70, 5632, 2, 2816), (130, 11008, 3, 11008)])
@@ -363,7 +366,7 @@ def test_gemv_autotune_leaves_a_working_choice(qg, oracle):
     twin = qg.GroupedGemv([dict(p, packed=p["packed"].clone()) for p in problems], launch.workspace)
     try:
         wpb, bpw, kernel, us = qg.qg_gemv_autotune([launch, twin], repeats=6)
-        assert wpb in (0, 4, 8, 12, 16) and bpw in (0, 4096, 8192, 16384, 32768) and kernel in (1, 2) and us > 0
+        assert wpb in (0, 4, 8, 12, 16) and bpw in (0, 4096, 8192, 16384, 32768) and kernel in (1, 2, 3) and us > 0
         for p in problems:
             p["y"].fill_(7.0)
         launch.launch()
