@@ -590,7 +590,8 @@ __device__ inline uint32_t and_or(uint32_t v, uint32_t mask, uint32_t magic)
 
 struct MmaConst {
     uint32_t mask, magic;
-    uint32_t mask_up;      // 3 bits: the mask of the fields three bits further up
+    uint32_t mask_up;      // the mask of the fields one field further up (3 bits: three bits up; 2 bits: two)
+    uint32_t mask_up2;     // 2 bits (gemv_mma4): the fields two fields further up
 };
 
 template <int BITS>
@@ -599,10 +600,12 @@ __device__ inline MmaConst mma_constants()
     MmaConst c;
     c.mask = BITS == 4 ? 0x000f000fu : BITS == 2 ? 0x00030003u : 0x00070007u;
     c.magic = QG_MMA_MAGIC;
-    c.mask_up = 0x00380038u;
+    c.mask_up = BITS == 2 ? 0x000c000cu : 0x00380038u;
+    c.mask_up2 = 0x00300030u;
     asm("" : "+s"(c.mask));
     asm("" : "+v"(c.magic));
     asm("" : "+s"(c.mask_up));
+    asm("" : "+s"(c.mask_up2));
     return c;
 }
 
@@ -659,7 +662,7 @@ __device__ inline void mma_unpack(const uint32_t *w, const MmaConst &c, MmaOpera
 
 // x-hat of the groups of a step from the per-lane x values (Algorithm 1's sum of x)
 template <int BITS, int GPS>
-__device__ inline void step_group_sums(const StepData<BITS, GPS> &d, float *xhat, float weight = 1.0f)
+__device__ inline void step_group_sums(const StepData<BITS, GPS> &d, float *xhat, float w0 = 1.0f, float w1 = 1.0f)
 {
     using D = StepData<BITS, GPS>;
     constexpr int G = codes_per_step<BITS>() / GPS;
@@ -668,13 +671,13 @@ __device__ inline void step_group_sums(const StepData<BITS, GPS> &d, float *xhat
         for (int g = 0; g < GPS; ++g) {
             float v = 0.0f;
 #pragma unroll
-            for (int i = 0; i < G / 128; ++i) v += d.xv[g * (G / 128) + i].x + d.xv[g * (G / 128) + i].y;
-            segment_sums<64>(v * weight, &xhat[g]);
+            for (int i = 0; i < G / 128; ++i) v += d.xv[g * (G / 128) + i].x * w0 + d.xv[g * (G / 128) + i].y * w1;
+            segment_sums<64>(v, &xhat[g]);
         }
     } else {
 #pragma unroll
         for (int i = 0; i < D::NXV; ++i)
-            segment_sums<G / 2>((d.xv[i].x + d.xv[i].y) * weight, &xhat[i * (128 / G)]);
+            segment_sums<G / 2>(d.xv[i].x * w0 + d.xv[i].y * w1, &xhat[i * (128 / G)]);
     }
 }
 
@@ -763,8 +766,8 @@ __global__ __launch_bounds__(512) void gemv_mma(QG_FIRST_BLOCKS, const GemvArgs 
         // as 128 + 8 q (xhat_up)
         float xhat[GPS], xhat_up[GPS];
         if constexpr (BITS == 3) {
-            step_group_sums<BITS, GPS>(d, xhat, up_class ? 0.0f : 1.0f);
-            step_group_sums<BITS, GPS>(d, xhat_up, up_class ? 1.0f : 0.0f);
+            step_group_sums<BITS, GPS>(d, xhat, up_class ? 0.0f : 1.0f, up_class ? 0.0f : 1.0f);
+            step_group_sums<BITS, GPS>(d, xhat_up, up_class ? 1.0f : 0.0f, up_class ? 1.0f : 0.0f);
         } else {
             step_group_sums<BITS, GPS>(d, xhat);
         }
@@ -831,164 +834,6 @@ __global__ __launch_bounds__(512) void gemv_mma(QG_FIRST_BLOCKS, const GemvArgs 
 }
 
 // ---------------------------------------------------------------------------------------
-// gemv_mma for groups that are a whole number of steps (G = 256, ..., up to one group per
-// output, the full-column form of eq. (1)): the accumulators of the matrix instructions run
-// across steps, and a group -- or the piece of it that lies in this wavefront's range, since
-// s (sum q x - z sum x) is linear in the two sums -- is closed when it ends.  No per-step
-// group bookkeeping is left, which is what the 2-bit kernel spends a third of its vector
-// instructions on at small groups.
-// ---------------------------------------------------------------------------------------
-template <int BITS>
-__global__ __launch_bounds__(512) void gemv_mma_long(QG_FIRST_BLOCKS, const GemvArgs A)
-{
-    using F = Fmt<BITS>;
-    constexpr int L = loads_per_step<BITS>();
-    constexpr int S = codes_per_step<BITS>();
-    constexpr int CELLS = cells_per_step<BITS>();
-    constexpr int OPS = mma_ops<BITS>();
-    constexpr int NXV = S / 128;
-    constexpr int ZPER = 32 / F::ZBITS;
-    using D = StepData<BITS, 0>;
-    __shared__ float red[16][QG_WAVE];
-    __shared__ __attribute__((aligned(16))) lds_u16 zeros[S];
-    extern __shared__ __attribute__((aligned(16))) lds_u16 xs_raw[];
-    lds_u16(*xs)[2][3][S] = (lds_u16(*)[2][3][S])xs_raw;
-
-    const int pi = find_problem(fb_a, fb_b, fb_c, A, blockIdx.x);
-    const GemvProblem P = A.p[pi];
-    pin_problem(P);
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int spg = P.steps_per_group;
-    const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.steps, wave);
-    if (!job.work) return;                      // no work: leave before the barrier
-    const int tile = job.tile, s0 = job.item0, s1 = job.item1;
-
-    TileView T;
-    T.codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
-    T.scales = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
-    T.zeros = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
-    T.x = P.x;
-
-#pragma unroll
-    for (int i = lane; i < S; i += QG_WAVE) zeros[i] = 0;
-
-    int xpos[NXV][2];
-#pragma unroll
-    for (int i = 0; i < NXV; ++i)
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int k = 128 * i + 2 * lane + e;
-            const int cell = k / F::CELL, slot = mma_slot<BITS>(k % F::CELL);
-            xpos[i][e] = (((cell >> 1) * OPS + (slot >> 3)) * 2 + (cell & 1)) * 8 + (slot & 7);
-        }
-    const int row = lane & 31, half = lane >> 5;
-    const lds_u16 *abase[2];
-#pragma unroll
-    for (int b = 0; b < 2; ++b) abase[b] = row < 3 ? &xs[wave][b][row][half * 8] : &zeros[half * 8];
-
-    // 3 bits: see gemv_mma (codes taken three bits up meet x / 8 and have their own x-hat)
-    const bool up_class = BITS == 3 && (lane & 2);
-    const float xscale = up_class ? 0.125f : 1.0f;
-    float xacc = 0.0f, xacc_up = 0.0f;            // this lane's x values of the running piece
-    auto stage_x = [&](const D &d, int buf) {
-#pragma unroll
-        for (int i = 0; i < NXV; ++i) {
-            mma_floatx2 r = {d.xv[i].x * xscale, d.xv[i].y * xscale};
-#pragma unroll
-            for (int part = 0; part < 3; ++part) {
-                const mma_bf16x2 h = __builtin_convertvector(r, mma_bf16x2);
-                const uint32_t bits = *(const uint32_t *)&h;
-                xs[wave][buf][part][xpos[i][0]] = (uint16_t)bits;
-                xs[wave][buf][part][xpos[i][1]] = (uint16_t)(bits >> 16);
-                r[0] -= __uint_as_float(bits << 16);
-                r[1] -= __uint_as_float(bits & 0xffff0000u);
-            }
-        }
-    };
-
-    const MmaConst mc = mma_constants<BITS>();
-    float yacc = 0.0f;
-    mma_floatx16 accP, accQ;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accQ[i] = 0.0f; }
-
-    auto compute = [&](const D &d, int buf) {
-#pragma unroll
-        for (int i = 0; i < NXV; ++i) {
-            const float v = d.xv[i].x + d.xv[i].y;
-            if (up_class) xacc_up += v; else xacc += v;
-        }
-#pragma unroll
-        for (int cp = 0; cp < CELLS / 2; ++cp) {
-            uint32_t wp[F::PLANES], wq[F::PLANES];
-            const int c0 = 2 * cp, u = c0 >> 2, j = c0 & 3;
-#pragma unroll
-            for (int pl = 0; pl < F::PLANES; ++pl) {
-                const auto sw = __builtin_amdgcn_permlane32_swap(word_of(d.v[u * F::PLANES + pl], j),
-                                                                 word_of(d.v[u * F::PLANES + pl], j + 1), false, false);
-                wp[pl] = sw[0];
-                wq[pl] = sw[1];
-            }
-            MmaOperand bp[OPS], bq[OPS];
-            mma_unpack<BITS>(wp, mc, bp);
-            mma_unpack<BITS>(wq, mc, bq);
-#pragma unroll
-            for (int op = 0; op < OPS; ++op) {
-                MmaOperand a;
-                a.q = *(const lds_u128 *)(abase[buf] + (cp * OPS + op) * 16);
-                accP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bp[op].v, accP, 0, 0, 0);
-                accQ = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bq[op].v, accQ, 0, 0, 0);
-            }
-        }
-    };
-
-    int g = s0 / spg;                                   // running group
-    int left = (g + 1) * spg - s0;                      // its steps still to come
-    // closes the piece of group g this wavefront has seen, if step s ends the group or the range
-    auto close_group = [&](int s) {
-        if (--left != 0 && s + 1 != s1) return;
-        float xhat, xhat_up = 0.0f;
-        segment_sums<64>(xacc, &xhat);
-        if constexpr (BITS == 3) segment_sums<64>(xacc_up, &xhat_up);
-        const float tp = accP[0] + accP[1] + accP[2], tq = accQ[0] + accQ[1] + accQ[2];
-        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tp), __float_as_uint(tq), false, false);
-        const float tsum = __uint_as_float(sw[0]);           // lane l: output l of the tile
-        const float scale = T.scales[(size_t)g * QG_WAVE];
-        const uint32_t zword = T.zeros[(size_t)(g / ZPER) * QG_WAVE];
-        const uint32_t zq = (zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u);
-        float tz = fmaf(-(float)(zq + 128u), xhat, tsum);
-        if constexpr (BITS == 3) tz = fmaf(-(float)(zq + 16u), xhat_up, tz);
-        yacc = fmaf(scale, tz, yacc);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accQ[i] = 0.0f; }
-        xacc = 0.0f;
-        xacc_up = 0.0f;
-        ++g;
-        left = spg;
-    };
-
-    const int last = s1 - 1;
-    D da, db;
-    fetch_step(da, T, s0, lane);
-    stage_x(da, 0);
-    for (int s = s0; s < s1; s += 2) {
-        const int sb = s + 1 < last ? s + 1 : last;
-        const int sc = s + 2 < last ? s + 2 : last;
-        fetch_step(db, T, sb, lane);
-        compute(da, 0);
-        close_group(s);
-        if (s + 1 >= s1) break;                       // odd number of steps
-        stage_x(db, 1);
-        fetch_step(da, T, sc, lane);
-        compute(db, 1);
-        close_group(sb);
-        stage_x(da, 0);
-    }
-    finish_tile(P, job, yacc, red);
-}
-
-// ---------------------------------------------------------------------------------------
 // The matrix-core GEMV on v_mfma_f32_4x4x4_16B_bf16: 16 independent 4 x 4 x 4 products per
 // instruction, one per group of four lanes.  Lane l supplies the B column of ITS OWN output
 // (four consecutive operand elements = four codes 128 + q), the A rows of a block are the
@@ -1000,7 +845,9 @@ __global__ __launch_bounds__(512) void gemv_mma_long(QG_FIRST_BLOCKS, const Gemv
 // the exactness argument are the same; so is the 3-bit in-place high field.
 //
 // CPG > 0: groups of CPG cells inside a step (closed at compile-time positions).
-// CPG == 0: groups of whole steps; the accumulators run across steps (see gemv_mma_long).
+// CPG == 0: groups of whole steps (G = 256 ... K).  The accumulators run across steps, and a
+// group -- or the piece of it inside this wavefront's range, since s (sum q x - z sum x) is
+// linear in the two sums -- is closed when it ends; no per-step group work is left.
 // ---------------------------------------------------------------------------------------
 typedef short mma4_ab __attribute__((ext_vector_type(4)));
 typedef float mma4_acc __attribute__((ext_vector_type(4)));
@@ -1021,6 +868,47 @@ __device__ inline int mma4_slot(int c)
     }
 }
 
+// Fields taken where they stand.  A field that sits f bits up in the mantissa makes the
+// element 128 + 2^f q instead of 128 + q, still exact in bf16 as long as it stays below 256;
+// the x values such an element meets are stored divided by 2^f (exact), so the product is
+// (128 / 2^f) x + q x, and the closing of a group subtracts (128 / 2^f + z) times the sum of
+// those x values.  Codes therefore fall into classes by their f:
+//   4 bits: one class (every field is shifted down to f = 0);
+//   3 bits: f = 0 for the low field of a byte, f = 3 for the high field (as in gemv_mma);
+//   2 bits: register j of a word (codes j and j + 8, field at bit 2 j) is read from the word
+//           shifted by 6 (j / 3) with f = 2 (j % 3): two shifts per word instead of seven.
+template <int BITS> struct Mma4Classes;
+template <> struct Mma4Classes<4> { static constexpr int N = 1; };
+template <> struct Mma4Classes<3> { static constexpr int N = 2; };
+template <> struct Mma4Classes<2> { static constexpr int N = 3; };
+
+// class (0 .. N-1, f = BITS * class) of code c of a cell
+template <int BITS>
+__device__ inline int mma4_class(int c)
+{
+    if constexpr (BITS == 4) return 0;
+    else if constexpr (BITS == 3) return (c & 7) >> 2;      // code within its word: 4 .. 7 are high fields
+    else return (c & 7) % 3;
+}
+
+template <int BITS>
+__device__ inline void mma4_unpack(const uint32_t *w, const MmaConst &c, MmaOperand *op)
+{
+    if constexpr (BITS == 2) {
+        const uint32_t w6 = w[0] >> 6, w12 = w[0] >> 12;
+        op[0].r[0] = and_or(w[0], c.mask, c.magic);
+        op[0].r[1] = and_or(w[0], c.mask_up, c.magic);
+        op[0].r[2] = and_or(w[0], c.mask_up2, c.magic);
+        op[0].r[3] = and_or(w6, c.mask, c.magic);
+        op[1].r[0] = and_or(w6, c.mask_up, c.magic);
+        op[1].r[1] = and_or(w6, c.mask_up2, c.magic);
+        op[1].r[2] = and_or(w12, c.mask, c.magic);
+        op[1].r[3] = and_or(w12, c.mask_up, c.magic);
+    } else {
+        mma_unpack<BITS>(w, c, op);
+    }
+}
+
 template <int BITS, int CPG>
 __global__ __launch_bounds__(512) void gemv_mma4(QG_FIRST_BLOCKS, const GemvArgs A)
 {
@@ -1033,6 +921,7 @@ __global__ __launch_bounds__(512) void gemv_mma4(QG_FIRST_BLOCKS, const GemvArgs
     constexpr int NXV = S / 128;
     constexpr int ZPER = 32 / F::ZBITS;
     constexpr int PITCH = S + 8;                    // u16 per part: the four parts on different banks
+    constexpr int NCL = Mma4Classes<BITS>::N;
     using D = StepData<BITS, GPS>;
     __shared__ float red[16][QG_WAVE];
     // per wavefront and buffer: the three parts of the step's x in operand order, and a part of zeros
@@ -1059,8 +948,18 @@ __global__ __launch_bounds__(512) void gemv_mma4(QG_FIRST_BLOCKS, const GemvArgs
 #pragma unroll
         for (int i = lane; i < PITCH; i += QG_WAVE) xs[wave][b][3][i] = 0;
 
-    // where this lane's x values go: x[128 i + 2 lane + e] of the step
+    // where this lane's x values go: x[128 i + 2 lane + e] of the step; and the class of the
+    // codes they meet (the same for every i: 128 is a multiple of the cell size), as a scale
+    // for the stored value and as 0 / 1 weights for the x-hat of each class
     int xpos[NXV][2];
+    float xscale[2], cw[NCL][2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int cls = mma4_class<BITS>((2 * lane + e) % F::CELL);
+        xscale[e] = cls == 0 ? 1.0f : cls == 1 ? (BITS == 3 ? 0.125f : 0.25f) : 0.0625f;
+#pragma unroll
+        for (int c = 0; c < NCL; ++c) cw[c][e] = cls == c ? 1.0f : 0.0f;
+    }
 #pragma unroll
     for (int i = 0; i < NXV; ++i)
 #pragma unroll
@@ -1070,12 +969,10 @@ __global__ __launch_bounds__(512) void gemv_mma4(QG_FIRST_BLOCKS, const GemvArgs
         }
     const lds_u16 *abase[2] = {&xs[wave][0][lane & 3][0], &xs[wave][1][lane & 3][0]};
 
-    const bool up_class = BITS == 3 && (lane & 2);      // see gemv_mma
-    const float xscale = up_class ? 0.125f : 1.0f;
     auto stage_x = [&](const D &d, int buf) {
 #pragma unroll
         for (int i = 0; i < NXV; ++i) {
-            mma_floatx2 r = {d.xv[i].x * xscale, d.xv[i].y * xscale};
+            mma_floatx2 r = {d.xv[i].x * xscale[0], d.xv[i].y * xscale[1]};
 #pragma unroll
             for (int part = 0; part < 3; ++part) {
                 const mma_bf16x2 h = __builtin_convertvector(r, mma_bf16x2);
@@ -1091,7 +988,11 @@ __global__ __launch_bounds__(512) void gemv_mma4(QG_FIRST_BLOCKS, const GemvArgs
     const MmaConst mc = mma_constants<BITS>();
     float yacc = 0.0f;
     mma4_acc acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
-    float xacc = 0.0f, xacc_up = 0.0f;              // CPG == 0: x of the running piece
+    float xacc[NCL];                                // CPG == 0: x of the running piece, per class
+#pragma unroll
+    for (int c = 0; c < NCL; ++c) xacc[c] = 0.0f;
+    // (128 / 2^f + z) of class c
+    auto offset_of = [](int c, uint32_t zq) { return (float)(zq + (c == 0 ? 128u : c == 1 ? (BITS == 3 ? 16u : 32u) : 8u)); };
 
     // the matrix instructions of one cell: OPC operands, two per 128-bit read of A
     auto cell_mfma = [&](const D &d, int cell, int buf) {
@@ -1100,7 +1001,7 @@ __global__ __launch_bounds__(512) void gemv_mma4(QG_FIRST_BLOCKS, const GemvArgs
 #pragma unroll
         for (int pl = 0; pl < F::PLANES; ++pl) w[pl] = word_of(d.v[u * F::PLANES + pl], j);
         MmaOperand op[mma_ops<BITS>()];
-        mma_unpack<BITS>(w, mc, op);
+        mma4_unpack<BITS>(w, mc, op);
 #pragma unroll
         for (int o = 0; o < OPC; o += 2) {
             MmaOperand a;
@@ -1122,13 +1023,9 @@ __global__ __launch_bounds__(512) void gemv_mma4(QG_FIRST_BLOCKS, const GemvArgs
 
     auto compute = [&](const D &d, int step, int buf) {
         if constexpr (CPG > 0) {
-            float xhat[GPS], xhat_up[GPS];
-            if constexpr (BITS == 3) {
-                step_group_sums<BITS, GPS>(d, xhat, up_class ? 0.0f : 1.0f);
-                step_group_sums<BITS, GPS>(d, xhat_up, up_class ? 1.0f : 0.0f);
-            } else {
-                step_group_sums<BITS, GPS>(d, xhat);
-            }
+            float xhat[NCL][GPS];
+#pragma unroll
+            for (int c = 0; c < NCL; ++c) step_group_sums<BITS, GPS>(d, xhat[c], cw[c][0], cw[c][1]);
 #pragma unroll
             for (int cell = 0; cell < CELLS; ++cell) {
                 cell_mfma(d, cell, buf);
@@ -1138,17 +1035,17 @@ __global__ __launch_bounds__(512) void gemv_mma4(QG_FIRST_BLOCKS, const GemvArgs
                     const float tsum = take_sum();
                     const uint32_t zword = d.zw[D::ZW > 1 ? gs / D::ZPER : 0];
                     const uint32_t zq = (zword >> (F::ZBITS * (gabs % D::ZPER))) & ((1u << F::ZBITS) - 1u);
-                    float tz = fmaf(-(float)(zq + 128u), xhat[gs], tsum);
-                    if constexpr (BITS == 3) tz = fmaf(-(float)(zq + 16u), xhat_up[gs], tz);
+                    float tz = tsum;
+#pragma unroll
+                    for (int c = 0; c < NCL; ++c) tz = fmaf(-offset_of(c, zq), xhat[c][gs], tz);
                     yacc = fmaf(d.s[gs], tz, yacc);
                 }
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < NXV; ++i) {
-                const float v = d.xv[i].x + d.xv[i].y;
-                if (up_class) xacc_up += v; else xacc += v;
-            }
+            for (int i = 0; i < NXV; ++i)
+#pragma unroll
+                for (int c = 0; c < NCL; ++c) xacc[c] += d.xv[i].x * cw[c][0] + d.xv[i].y * cw[c][1];
 #pragma unroll
             for (int cell = 0; cell < CELLS; ++cell) cell_mfma(d, cell, buf);
         }
@@ -1161,18 +1058,20 @@ __global__ __launch_bounds__(512) void gemv_mma4(QG_FIRST_BLOCKS, const GemvArgs
     auto close_group = [&](int s) {
         if constexpr (CPG == 0) {
             if (--left != 0 && s + 1 != s1) return;
-            float xhat, xhat_up = 0.0f;
-            segment_sums<64>(xacc, &xhat);
-            if constexpr (BITS == 3) segment_sums<64>(xacc_up, &xhat_up);
+            float xhat[NCL];
+#pragma unroll
+            for (int c = 0; c < NCL; ++c) segment_sums<64>(xacc[c], &xhat[c]);
             const float tsum = take_sum();
             const float scale = T.scales[(size_t)g * QG_WAVE];
             const uint32_t zword = T.zeros[(size_t)(g / ZPER) * QG_WAVE];
             const uint32_t zq = (zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u);
-            float tz = fmaf(-(float)(zq + 128u), xhat, tsum);
-            if constexpr (BITS == 3) tz = fmaf(-(float)(zq + 16u), xhat_up, tz);
+            float tz = tsum;
+#pragma unroll
+            for (int c = 0; c < NCL; ++c) {
+                tz = fmaf(-offset_of(c, zq), xhat[c], tz);
+                xacc[c] = 0.0f;
+            }
             yacc = fmaf(scale, tz, yacc);
-            xacc = 0.0f;
-            xacc_up = 0.0f;
             ++g;
             left = spg;
         }
@@ -1656,17 +1555,9 @@ void launch_mma4(int cpg, unsigned blocks, unsigned threads, hipStream_t st, con
     }
 }
 
-template <int BITS>
-void launch_mma_long(unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
-{
-    const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 3 * codes_per_step<BITS>() * sizeof(uint16_t);
-    hipLaunchKernelGGL(gemv_mma_long<BITS>, dim3(blocks), dim3(threads), lds, st, first_blocks(A).a,
-                       first_blocks(A).b, first_blocks(A).c, A);
-}
-
 // Which kernel multiplies: the vector ALU (gemv_static / gemv_runtime), the 32 x 32 x 16 matrix
-// instruction (gemv_mma, groups of at least two cells inside a step; gemv_mma_long, groups of
-// whole steps at 2 and 3 bits) or the 4 x 4 x 4 one (gemv_mma4, any group of the two kinds).
+// instruction (gemv_mma, groups of at least two cells inside a step) or the 4 x 4 x 4 one
+// (gemv_mma4, groups of whole cells inside a step, and groups of whole steps at 2 and 3 bits).
 // Measured on the three layer sets over G = 32 ... K: at 2 and 3 bits gemv_mma4 is ahead of
 // both others nearly everywhere (by 5-13 %, level at the smallest groups); at 4 bits the
 // vector-ALU kernel is bound by memory anyway.
@@ -1676,7 +1567,7 @@ Mul multiplier(int bits, int cpg, Kind kind)
     if (kind != KIND_STATIC && kind != KIND_RUNTIME) return MUL_VALU;
     const int want = g_tune_kernel ? g_tune_kernel : (bits == 4 ? 1 : 3);
     if (want == 3 && (kind == KIND_STATIC || bits != 4)) return MUL_MMA4;
-    if (want == 2 && (kind == KIND_STATIC ? cpg >= 2 : bits != 4)) return MUL_MMA32;
+    if (want == 2 && kind == KIND_STATIC && cpg >= 2) return MUL_MMA32;
     return MUL_VALU;
 }
 
@@ -1828,9 +1719,6 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     } else if (kind == KIND_RUNTIME && mul == MUL_MMA4) {
         if (bits == 2) launch_mma4<2>(0, blocks, threads, st, A);
         else launch_mma4<3>(0, blocks, threads, st, A);
-    } else if (kind == KIND_RUNTIME && mul == MUL_MMA32) {
-        if (bits == 2) launch_mma_long<2>(blocks, threads, st, A);
-        else launch_mma_long<3>(blocks, threads, st, A);
     } else if (kind == KIND_RUNTIME) {
         if (bits == 4) hipLaunchKernelGGL(gemv_runtime<4>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
         else if (bits == 2) hipLaunchKernelGGL(gemv_runtime<2>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
