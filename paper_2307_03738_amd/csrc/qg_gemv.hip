@@ -1610,11 +1610,18 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     const bool mma = mul != MUL_VALU;
     int cap = g_tune_wpb > 0 ? g_tune_wpb : (L[0].bits == 4 ? 12 : 8);
     if (rows > 0 && cap > 8) cap = 8;          // gemm_rows16 is built for at most 8 wavefronts
-    if (mma) {                                 // the matrix-core kernel is built for at most 8 wavefronts;
-        if (cap > 8) cap = 8;                  // measured: teams of 4 are best for it
+    if (mma) {                                 // the matrix-core kernels are built for at most 8 wavefronts;
+        if (cap > 8) cap = 8;                  // measured: teams of 4 are best for them ...
         if (g_tune_wpb == 0) cap = 4;
     }
     size_t target = (size_t)g_tune_bytes_per_wave;               // code bytes per wavefront
+    // ... except for 3-bit groups of up to 64 weights on gemv_mma4: there teams of up to 8 with a
+    // single step per wavefront are 8-12 % ahead on the 7B- and 13B-shaped sets (level on the
+    // 65B-shaped one); larger groups lose with that shape
+    if (mul == MUL_MMA4 && L[0].bits == 3 && kind == KIND_STATIC && L[0].group <= 64) {
+        if (g_tune_wpb == 0) cap = 8;
+        if (target == 0) target = pl[0].item_bytes;
+    }
     if (target == 0) {
         size_t code_bytes = 0;
         for (int i = 0; i < count; ++i) code_bytes += (size_t)L[i].tiles * pl[i].items * pl[i].item_bytes;
