@@ -1559,13 +1559,16 @@ void launch_mma4(int cpg, unsigned blocks, unsigned threads, hipStream_t st, con
 // instruction (gemv_mma, groups of at least two cells inside a step) or the 4 x 4 x 4 one
 // (gemv_mma4, groups of whole cells inside a step, and groups of whole steps at 2 and 3 bits).
 // Measured on the three layer sets over G = 32 ... K: at 2 and 3 bits gemv_mma4 is ahead of
-// both others nearly everywhere (by 5-13 %, level at the smallest groups); at 4 bits the
-// vector-ALU kernel is bound by memory anyway.
+// both others nearly everywhere (by 5-13 %, level at the smallest groups).  At 4 bits the
+// vector-ALU kernel is bound by memory on the largest launches, where it stays; below that
+// gemv_mma4 in few, long wavefronts is ahead (single 7B matrices 13-15 %, the 7B set 5 %, the
+// 13B set 10 %).
 enum Mul { MUL_VALU, MUL_MMA32, MUL_MMA4 };
-Mul multiplier(int bits, int cpg, Kind kind)
+constexpr size_t QG_VALU4_FROM = (size_t)256 << 20;      // code bytes of a launch
+Mul multiplier(int bits, int cpg, Kind kind, size_t code_bytes)
 {
     if (kind != KIND_STATIC && kind != KIND_RUNTIME) return MUL_VALU;
-    const int want = g_tune_kernel ? g_tune_kernel : (bits == 4 ? 1 : 3);
+    const int want = g_tune_kernel ? g_tune_kernel : (bits == 4 && code_bytes >= QG_VALU4_FROM ? 1 : 3);
     if (want == 3 && (kind == KIND_STATIC || bits != 4)) return MUL_MMA4;
     if (want == 2 && kind == KIND_STATIC && cpg >= 2) return MUL_MMA32;
     return MUL_VALU;
@@ -1597,18 +1600,21 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     }
     const Kind kind = pl[0].kind;
 
-    // Launch shape.  Every wavefront of the launch gets about the same, small amount of work
+    // Launch shape.  Every wavefront of the launch gets about the same amount of work
     // (`target` bytes of codes), so that all of them are resident at once and finish together.
     // A tile of 64 outputs is covered by a team of up to `cap` wavefronts inside one
     // workgroup (they meet in LDS); a tile whose K needs more wavefronts than that is cut
     // into 2, 4, ... workgroups that meet in the reduction tree.  Short teams are packed
     // several to a workgroup.  Launches with little work per wavefront slot use less than
     // `target` per wavefront so that the chip is still covered.
-    // wavefronts per team, at most (measured: 12 is best for the 4-bit kernels, 8 for the
-    // 2- and 3-bit ones, which hold more registers per wavefront)
-    const Mul mul = rows == 0 ? multiplier(L[0].bits, L[0].group / L[0].cell, kind) : MUL_VALU;
+    size_t code_bytes = 0;
+    for (int i = 0; i < count; ++i) code_bytes += (size_t)L[i].tiles * pl[i].items * pl[i].item_bytes;
+    const int bits_all = L[0].bits;
+    Mul mul = rows == 0 ? multiplier(bits_all, L[0].group / L[0].cell, kind, code_bytes) : MUL_VALU;
     const bool mma = mul != MUL_VALU;
-    int cap = g_tune_wpb > 0 ? g_tune_wpb : (L[0].bits == 4 ? 12 : 8);
+    // wavefronts per team, at most (measured: 12 is best for the 4-bit vector-ALU kernel with
+    // groups inside a step, 8 for the 2- and 3-bit ones, which hold more registers per wavefront)
+    int cap = g_tune_wpb > 0 ? g_tune_wpb : (bits_all == 4 ? 12 : 8);
     if (rows > 0 && cap > 8) cap = 8;          // gemm_rows16 is built for at most 8 wavefronts
     if (mma) {                                 // the matrix-core kernels are built for at most 8 wavefronts;
         if (cap > 8) cap = 8;                  // measured: teams of 4 are best for them ...
@@ -1618,13 +1624,26 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     // ... except for 3-bit groups of up to 64 weights on gemv_mma4: there teams of up to 8 with a
     // single step per wavefront are 8-12 % ahead on the 7B- and 13B-shaped sets (level on the
     // 65B-shaped one); larger groups lose with that shape
-    if (mul == MUL_MMA4 && L[0].bits == 3 && kind == KIND_STATIC && L[0].group <= 64) {
+    if (mul == MUL_MMA4 && bits_all == 3 && kind == KIND_STATIC && L[0].group <= 64) {
         if (g_tune_wpb == 0) cap = 8;
         if (target == 0) target = pl[0].item_bytes;
     }
+    // Few, long wavefronts (teams of up to 4, about 10 wavefronts per CU, up to 48-64 KB of codes
+    // each) for groups of whole steps at any width and for gemv_mma4 at 4 bits: measured 5-15 %
+    // ahead of many short ones there (at 2 and 3 bits with groups inside a step the short ones
+    // win, and so they do at 4 bits on the largest launches).
+    const bool few_long = rows == 0 && (bits_all == 4 ? code_bytes < QG_VALU4_FROM && (mul == MUL_MMA4 || kind == KIND_RUNTIME)
+                                                      : kind == KIND_RUNTIME);
+    if (few_long) {
+        const size_t share = code_bytes / (256 * 10);
+        // (the vector-ALU kernel keeps its wider teams while a wavefront has a single step)
+        if (g_tune_wpb == 0 && (mma || share > 4096)) cap = 4;
+        if (target == 0) {
+            const size_t most = bits_all == 4 ? 65536 : 49152;
+            target = share < 4096 ? 4096 : share > most ? most : share;
+        }
+    }
     if (target == 0) {
-        size_t code_bytes = 0;
-        for (int i = 0; i < count; ++i) code_bytes += (size_t)L[i].tiles * pl[i].items * pl[i].item_bytes;
         target = code_bytes / (256 * 24);                        // about 24 wavefronts per CU
         if (target < 4096) target = 4096;
         if (target > 16384) target = 16384;
@@ -1632,34 +1651,50 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
 
     int wpb = 1;
     int64_t spw_of[QG_MAX_GROUPED], team_of[QG_MAX_GROUPED], chunks_of[QG_MAX_GROUPED];
-    for (int i = 0; i < count; ++i) {
-        const Plan &q = pl[i];
-        int64_t want = (int64_t)((target + q.item_bytes / 2) / q.item_bytes);   // items per wavefront
-        if (want < 1) want = 1;
-        if (want > q.max_spw) want = q.max_spw;
-        // Among the ways to cover K with `chunks` (a power of two) non-empty workgroups of `team`
-        // <= cap wavefronts, take the one whose items per wavefront come closest to `want`;
-        // on a tie the fewest workgroups, then the smallest team.
-        bool found = false;
-        int64_t best_miss = 0;
-        // (the many-row kernel has no reduction across workgroups)
-        for (int64_t chunks = 1; chunks <= (rows > 0 ? 1 : QG_MAX_CHUNKS); chunks *= 2) {
-            for (int64_t team = 1; team <= cap; ++team) {
-                const int64_t spw = (q.items + chunks * team - 1) / (chunks * team);
-                if (spw > q.max_spw) continue;
-                if ((chunks - 1) * team * spw >= q.items) continue;       // an empty workgroup
-                const int64_t miss = spw > want ? spw - want : want - spw;
-                if (!found || miss < best_miss) {
-                    spw_of[i] = spw;
-                    team_of[i] = team;
-                    chunks_of[i] = chunks;
-                    best_miss = miss;
-                    found = true;
+    auto plan_all = [&](int limit) -> bool {
+        wpb = 1;
+        for (int i = 0; i < count; ++i) {
+            const Plan &q = pl[i];
+            int64_t want = (int64_t)((target + q.item_bytes / 2) / q.item_bytes);   // items per wavefront
+            if (want < 1) want = 1;
+            if (want > q.max_spw) want = q.max_spw;
+            // Among the ways to cover K with `chunks` (a power of two) non-empty workgroups of `team`
+            // <= cap wavefronts, take the one whose items per wavefront come closest to `want`;
+            // on a tie the fewest workgroups, then the smallest team.
+            bool found = false;
+            int64_t best_miss = 0;
+            // (the many-row kernel has no reduction across workgroups)
+            for (int64_t chunks = 1; chunks <= (rows > 0 ? 1 : QG_MAX_CHUNKS); chunks *= 2) {
+                for (int64_t team = 1; team <= limit; ++team) {
+                    const int64_t spw = (q.items + chunks * team - 1) / (chunks * team);
+                    if (spw > q.max_spw) continue;
+                    if ((chunks - 1) * team * spw >= q.items) continue;       // an empty workgroup
+                    const int64_t miss = spw > want ? spw - want : want - spw;
+                    if (!found || miss < best_miss) {
+                        spw_of[i] = spw;
+                        team_of[i] = team;
+                        chunks_of[i] = chunks;
+                        best_miss = miss;
+                        found = true;
+                    }
                 }
             }
+            if (!found) return false;
+            if (team_of[i] > wpb) wpb = (int)team_of[i];
         }
-        if (!found) return QG_ERR_UNSUPPORTED;
-        if (team_of[i] > wpb) wpb = (int)team_of[i];
+        return true;
+    };
+    // A long K with few items per wavefront allowed (small groups) may not fit the preferred
+    // team size: then the widest team the kernel is built for, then the vector-ALU kernel,
+    // whose teams go up to 16 wavefronts (make_plan has checked that those cover K).
+    if (!plan_all(cap)) {
+        const int widest = (mma || rows > 0) ? 8 : 16;
+        bool ok = cap < widest && plan_all(widest);
+        if (!ok && mma) {
+            mul = MUL_VALU;
+            ok = plan_all(16);
+        }
+        if (!ok) return QG_ERR_UNSUPPORTED;
     }
 
     int blocks = 0;
