@@ -1639,7 +1639,10 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         // (the vector-ALU kernel keeps its wider teams while a wavefront has a single step)
         if (g_tune_wpb == 0 && (mma || share > 4096)) cap = 4;
         if (target == 0) {
-            const size_t most = bits_all == 4 ? 65536 : 49152;
+            size_t most = bits_all == 4 ? 65536 : 49152;
+            // (groups of one or two cells: a wavefront holds at most 64 groups, and half of that
+            // measured faster than all of it)
+            if (kind == KIND_STATIC && pl[0].max_spw <= 8) most = (size_t)pl[0].max_spw * pl[0].item_bytes / 2;
             target = share < 4096 ? 4096 : share > most ? most : share;
         }
     }
