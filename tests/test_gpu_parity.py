@@ -258,6 +258,23 @@ def test_gemv_extreme_shapes(qg, oracle, N, K, bits, group):
     assert err <= TOL_FP32, err
 
 
+@pytest.mark.parametrize("N,K,bits,group,tuning", [
+    (70, 262144, 2, 16, (0, 0, 0)),      # 256 wavefronts per tile: the widest teams of the 4 x 4 x 4 kernel
+    (70, 294912, 2, 16, (0, 0, 0)),      # ... more than those cover: the vector-ALU kernel's teams of 16
+    (70, 262144, 4, 16, (0, 0, 0)),
+    (70, 294912, 4, 16, (0, 0, 0)),
+    (130, 13824, 2, 16, (2, 0, 3)),      # a forced team size that cannot cover K without an empty workgroup
+    (130, 13824, 2, 16, (1, 4096, 3)),
+    (130, 13824, 3, 32, (1, 4096, 2))])
+def test_gemv_team_size_fallback(qg, oracle, N, K, bits, group, tuning):
+    # small groups limit the steps of a wavefront; a long K then needs more wavefronts per tile
+    # than the preferred (or the forced) team size allows, and the launch widens the teams
+    _announce("gemv team fallback", N, K, bits, group, tuning)
+    W, x = synth.small_case(N + bits, N, K, 0.02, False)
+    err = _gemv_case(qg, oracle, W, x, bits, group, tuning)
+    assert err <= TOL_FP32, err
+
+
 def test_gemv_zero_input_and_unit_scale(qg, oracle):
     _announce("gemv x = 0, s = 1 z = 0")
     rng = np.random.default_rng(5)
@@ -433,7 +450,7 @@ def test_gemv_random_shapes_and_launch_shapes(qg, oracle, seed):
         K = group * ngroups
         N = int(rng.integers(1, 400))
         tuning = (int(rng.choice([0, 1, 2, 4, 7, 8, 12, 16])), int(rng.choice([0, 4096, 8192, 16384, 65536])),
-                  int(rng.choice([0, 1, 2])))
+                  int(rng.choice([0, 1, 2, 3])))
         _announce("gemv random", seed, case, N, K, bits, group, tuning)
         W, x = synth.small_case(seed * 100 + case, N, K, 0.02, bool(rng.integers(0, 2)))
         err = _gemv_case(qg, oracle, W, x, bits, group, tuning)
