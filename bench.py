@@ -27,8 +27,8 @@ import torch
 
 HBM_PEAK_GBS = 8000.0          # MI355X public peak
 # HBM bytes of one grouped launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
-# the same counters of a 256 MiB device copy (profiles/gemv_static_b4_g128_C2_layer_set.txt)
-MEASURED_TRAFFIC_BYTES = {"C2": 109.84e6}
+# the same counters of a 256 MiB device copy (profiles/gemv_mma4_b4_g128_C2_layer_set.txt)
+MEASURED_TRAFFIC_BYTES = {"C2": 110.09e6}
 ROTATE_BYTES = 1.3e9           # distinct packed bytes touched between two uses of one copy
 
 

@@ -156,7 +156,7 @@ int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel);
  * counterpart of the paper's parameter search (Section 3, Algorithm 4).  `descs` holds `sets`
  * copies of the launch back to back (set i at descs + i * count; same shapes, normally
  * different packed buffers, so that a cache cannot serve the weights; sets = 1 times one set
- * again and again).  Runs the launch `repeats` times, rotating over the sets, for each of 75
+ * again and again).  Runs the launch `repeats` times, rotating over the sets, for each of 126
  * candidates (team size x bytes per wavefront x vector-ALU or one of the two matrix-core kernels), WAITS for
  * the GPU (the only call that does), leaves the fastest installed as qg_set_gemv_tuning would,
  * and reports it (HOST pointers, each may be NULL; best_us = microseconds per launch).  The

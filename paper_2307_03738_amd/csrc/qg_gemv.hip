@@ -1953,13 +1953,14 @@ extern "C" int qg_gemv_autotune(const qg_gemv_desc *descs, int count, int sets, 
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess) return QG_ERR_DEVICE;
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return QG_ERR_DEVICE; }
-    static const int teams[] = {0, 4, 8, 12, 16};
-    static const int sizes[] = {0, 4096, 8192, 16384, 32768};
+    static const int teams[] = {0, 2, 4, 8, 12, 16};
+    static const int sizes[] = {0, 4096, 8192, 16384, 32768, 49152, 65536};
+    constexpr int n_teams = sizeof(teams) / sizeof(teams[0]), n_sizes = sizeof(sizes) / sizeof(sizes[0]);
     int best[3] = {0, 0, 0};
     float best_ms = -1.0f;
     for (int k = 1; k <= 3 && rc == QG_OK; ++k)
-        for (int a = 0; a < 5 && rc == QG_OK; ++a)
-            for (int b = 0; b < 5 && rc == QG_OK; ++b) {
+        for (int a = 0; a < n_teams && rc == QG_OK; ++a)
+            for (int b = 0; b < n_sizes && rc == QG_OK; ++b) {
                 g_tune_wpb = teams[a];
                 g_tune_bytes_per_wave = sizes[b];
                 g_tune_kernel = k;
