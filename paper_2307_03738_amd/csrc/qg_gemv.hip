@@ -1099,6 +1099,225 @@ __global__ __launch_bounds__(512) void gemv_mma4(QG_FIRST_BLOCKS, const GemvArgs
 }
 
 // ---------------------------------------------------------------------------------------
+// gemv_mma4i: the 4 x 4 x 4 matrix instruction on 8-bit integers (2- and 4-bit codes).  A
+// code needs no exponent around it to be an int8, so a word of 4-bit codes becomes two
+// operands with two ANDs and one shift (w & 0x0f0f0f0f holds codes 0, 2, 4, 6 as bytes,
+// (w >> 4) & 0x0f0f0f0f codes 1, 3, 5, 7), a word of 2-bit codes four operands with four ANDs
+// and one shift (the fields at bits 2 and 4 of a byte stay where they are and count 4 q and
+// 16 q; the x values they meet are stored divided by 4 and 16).  x goes in as 32-bit fixed
+// point relative to the largest |x| of the step (a power of two, so scaling is exact),
+// cut into four signed bytes that fill the four rows of the A operand: lane l receives
+// D_i = sum_k q_k digit_i(x_k) for its own output, and sum_i 256^i D_i / scale = sum_k q_k x_k
+// to 2^-30 of the step's largest |x| per term.  There is no 128 to take out again: the
+// closing of a group is eq. (2) as it stands, y += s (T - z xhat), with one xhat per group.
+template <int BITS>
+__device__ inline int mma4i_slot(int c)              // 4 * operand of the cell + byte, of code c of a cell
+{
+    constexpr int OPC = Fmt<BITS>::CELL / 4;
+    return (c % OPC) * 4 + c / OPC;
+}
+
+typedef int mma4i_acc __attribute__((ext_vector_type(4)));
+typedef uint8_t __attribute__((may_alias)) lds_u8;
+
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ inline float dpp_max(float v)             // for v >= 0: disabled rows see 0
+{
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false);
+    return fmaxf(v, __int_as_float(moved));
+}
+
+template <int BITS, int CPG>
+__global__ __launch_bounds__(512) void gemv_mma4i(QG_FIRST_BLOCKS, const GemvArgs A)
+{
+    static_assert(BITS == 2 || BITS == 4, "3-bit fields do not sit inside bytes");
+    static_assert(CPG == 0 || BITS == 2 || CPG % 2 == 0, "a 128-bit read of A covers two 4-bit cells");
+    using F = Fmt<BITS>;
+    constexpr int L = loads_per_step<BITS>();
+    constexpr int S = codes_per_step<BITS>();
+    constexpr int CELLS = cells_per_step<BITS>();
+    constexpr int GPS = CPG > 0 ? CELLS / CPG : 0;
+    constexpr int OPC = F::CELL / 4;                // matrix instructions (operands) per cell
+    constexpr int CPR = 4 / OPC;                    // cells per 128-bit read of A (16 k)
+    constexpr int NXV = S / 128;
+    constexpr int ZPER = 32 / F::ZBITS;
+    constexpr int PITCH = S + 16;                   // bytes per digit row: the four rows on different banks
+    using D = StepData<BITS, GPS>;
+    __shared__ float red[16][QG_WAVE];
+    // per wavefront and buffer: the four digit rows of the step's x in operand order
+    extern __shared__ __attribute__((aligned(16))) lds_u8 xs8_raw[];
+    lds_u8(*xs)[2][4][PITCH] = (lds_u8(*)[2][4][PITCH])xs8_raw;
+
+    const int pi = find_problem(fb_a, fb_b, fb_c, A, blockIdx.x);
+    const GemvProblem P = A.p[pi];
+    pin_problem(P);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const WaveJob job = locate(P, blockIdx.x - P.block_begin, P.steps, wave);
+    if (!job.work) return;                      // no work: leave before the barrier
+    const int tile = job.tile, s0 = job.item0, s1 = job.item1;
+
+    TileView T;
+    T.codes = P.codes + (size_t)tile * P.steps * L * QG_WAVE + lane;
+    T.scales = P.scales + (size_t)tile * P.ngroups * QG_WAVE + lane;
+    T.zeros = P.zeros + (size_t)tile * P.zwords * QG_WAVE + lane;
+    T.x = P.x;
+
+    // where this lane's x values go: x[128 i + 2 lane + e] of the step; and what the field of
+    // the code they meet counts (the same for every i: 128 is a multiple of the cell size)
+    int xpos[NXV][2];
+    float xdiv[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int o = ((2 * lane + e) % F::CELL) % OPC;
+        xdiv[e] = BITS == 2 && o == 1 ? 0.25f : BITS == 2 && o == 2 ? 0.0625f : 1.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < NXV; ++i)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int k = 128 * i + 2 * lane + e;
+            xpos[i][e] = (k / F::CELL) * F::CELL + mma4i_slot<BITS>(k % F::CELL);
+        }
+    const lds_u8 *abase[2] = {&xs[wave][0][lane & 3][0], &xs[wave][1][lane & 3][0]};
+
+    // Fixed point of the step: |x| scale < 2^30 for the largest |x| of the step.  Returns 1 / scale.
+    auto stage_x = [&](const D &d, int buf) -> float {
+        float m = 0.0f;
+#pragma unroll
+        for (int i = 0; i < NXV; ++i) m = fmaxf(m, fmaxf(fabsf(d.xv[i].x), fabsf(d.xv[i].y)));
+        m = dpp_max<QG_DPP_QUAD_XOR1>(m);
+        m = dpp_max<QG_DPP_QUAD_XOR2>(m);
+        m = dpp_max<QG_DPP_HALF_MIRROR>(m);
+        m = dpp_max<QG_DPP_ROW_MIRROR>(m);
+        m = dpp_max<QG_DPP_BCAST15, 0xa>(m);
+        m = dpp_max<QG_DPP_BCAST31, 0xc>(m);
+        uint32_t eb = (uint32_t)__builtin_amdgcn_readlane(__float_as_int(m), 63) >> 23;   // biased exponent
+        eb = eb < 30u ? 30u : eb > 254u ? 254u : eb;
+        const float scale = __uint_as_float((283u - eb) << 23);                             // 2^(156 - eb)
+#pragma unroll
+        for (int i = 0; i < NXV; ++i) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const float xv = e == 0 ? d.xv[i].x : d.xv[i].y;
+                const int fixed = (int)(xv * (scale * xdiv[e]));
+                // the four bytes of (fixed + 0x808080) ^ 0x808080, read as signed, are digits
+                // base 256 of `fixed`
+                const uint32_t pat = ((uint32_t)fixed + 0x00808080u) ^ 0x00808080u;
+                xs[wave][buf][0][xpos[i][e]] = (uint8_t)pat;
+                xs[wave][buf][1][xpos[i][e]] = (uint8_t)(pat >> 8);
+                xs[wave][buf][2][xpos[i][e]] = (uint8_t)(pat >> 16);
+                xs[wave][buf][3][xpos[i][e]] = (uint8_t)(pat >> 24);
+            }
+        }
+        return __uint_as_float((eb - 29u) << 23);                                           // 2^(eb - 156)
+    };
+
+    float yacc = 0.0f;
+    mma4i_acc acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+    float tacc = 0.0f, xacc = 0.0f;                 // CPG == 0: T and x of the running piece of a group
+
+    // the matrix instructions of CPR cells: one 128-bit read of A feeds four of them
+    auto cells_mfma = [&](const D &d, int first, int buf) {
+        MmaOperand a;
+        a.q = *(const lds_u128 *)(abase[buf] + first * F::CELL);
+        uint32_t b[4];
+#pragma unroll
+        for (int c = 0; c < CPR; ++c) {
+            const int cell = first + c;
+            const uint32_t w = word_of(d.v[cell >> 2], cell & 3);
+            if constexpr (BITS == 4) {
+                b[2 * c] = w & 0x0f0f0f0fu;
+                b[2 * c + 1] = (w >> 4) & 0x0f0f0f0fu;
+            } else {
+                b[0] = w & 0x03030303u;
+                b[1] = w & 0x0c0c0c0cu;
+                b[2] = w & 0x30303030u;
+                b[3] = (w >> 6) & 0x03030303u;
+            }
+        }
+        acc0 = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[0], (int)b[0], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[1], (int)b[1], acc1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[2], (int)b[2], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[3], (int)b[3], acc1, 0, 0, 0);
+    };
+    // sum_i 256^i D_i of the finished cells for this lane's output, in units of 1 / scale;
+    // clears the accumulators
+    auto take_sum = [&]() {
+        const int lo = ((acc0[1] + acc1[1]) << 8) + (acc0[0] + acc1[0]);
+        const int hi = ((acc0[3] + acc1[3]) << 8) + (acc0[2] + acc1[2]);
+        acc0 = mma4i_acc{0, 0, 0, 0};
+        acc1 = mma4i_acc{0, 0, 0, 0};
+        return fmaf((float)hi, 65536.0f, (float)lo);
+    };
+
+    auto compute = [&](const D &d, int step, int buf, float inv) {
+        if constexpr (CPG > 0) {
+            float xhat[GPS];
+            step_group_sums<BITS, GPS>(d, xhat);
+#pragma unroll
+            for (int first = 0; first < CELLS; first += CPR) {
+                cells_mfma(d, first, buf);
+                if ((first + CPR) % CPG == 0) {
+                    const int gs = (first + CPR) / CPG - 1;
+                    const int gabs = step * GPS + gs;
+                    const float tsum = take_sum() * inv;
+                    const uint32_t zword = d.zw[D::ZW > 1 ? gs / D::ZPER : 0];
+                    const uint32_t zq = (zword >> (F::ZBITS * (gabs % D::ZPER))) & ((1u << F::ZBITS) - 1u);
+                    yacc = fmaf(d.s[gs], fmaf(-(float)zq, xhat[gs], tsum), yacc);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NXV; ++i) xacc += d.xv[i].x + d.xv[i].y;
+#pragma unroll
+            for (int first = 0; first < CELLS; first += CPR) cells_mfma(d, first, buf);
+            tacc = fmaf(take_sum(), inv, tacc);     // every step has a scale of its own
+        }
+    };
+
+    // CPG == 0: closes the piece of group g this wavefront has seen, if step s ends the group or the range
+    const int spg = P.steps_per_group;
+    int g = CPG == 0 ? s0 / spg : 0;
+    int left = CPG == 0 ? (g + 1) * spg - s0 : 0;
+    auto close_group = [&](int s) {
+        if constexpr (CPG == 0) {
+            if (--left != 0 && s + 1 != s1) return;
+            float xhat;
+            segment_sums<64>(xacc, &xhat);
+            const float scale = T.scales[(size_t)g * QG_WAVE];
+            const uint32_t zword = T.zeros[(size_t)(g / ZPER) * QG_WAVE];
+            const uint32_t zq = (zword >> (F::ZBITS * (g % ZPER))) & ((1u << F::ZBITS) - 1u);
+            yacc = fmaf(scale, fmaf(-(float)zq, xhat, tacc), yacc);
+            tacc = 0.0f;
+            xacc = 0.0f;
+            ++g;
+            left = spg;
+        }
+    };
+
+    // two register buffers and two LDS buffers used alternately, as in gemv_static
+    const int last = s1 - 1;
+    D da, db;
+    fetch_step(da, T, s0, lane);
+    float inv_a = stage_x(da, 0), inv_b = 0.0f;
+    for (int s = s0; s < s1; s += 2) {
+        const int sb = s + 1 < last ? s + 1 : last;
+        const int sc = s + 2 < last ? s + 2 : last;
+        fetch_step(db, T, sb, lane);
+        compute(da, s, 0, inv_a);
+        close_group(s);
+        if (s + 1 >= s1) break;                       // odd number of steps
+        inv_b = stage_x(db, 1);
+        fetch_step(da, T, sc, lane);
+        compute(db, sb, 1, inv_b);
+        close_group(sb);
+        inv_a = stage_x(da, 0);
+    }
+    finish_tile(P, job, yacc, red);
+}
+
+// ---------------------------------------------------------------------------------------
 // Up to 16 activation rows at once (a few prompt tokens): Y = X What^T with the launch
 // structure of the GEMV -- one wavefront per 64 outputs and K range, no workgroup barrier in
 // the loop, K split over the wavefronts of a team -- and the arithmetic of gemv_mma: 4-bit
@@ -1555,6 +1774,24 @@ void launch_mma4(int cpg, unsigned blocks, unsigned threads, hipStream_t st, con
     }
 }
 
+template <int BITS>
+void launch_mma4i(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+{
+    const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 4 * (codes_per_step<BITS>() + 16);
+    const FirstBlocks f = first_blocks(A);
+    switch (cpg) {
+    case 0: hipLaunchKernelGGL((gemv_mma4i<BITS, 0>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
+    case 1:
+        if constexpr (BITS == 2)
+            hipLaunchKernelGGL((gemv_mma4i<BITS, 1>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A);
+        break;
+    case 2: hipLaunchKernelGGL((gemv_mma4i<BITS, 2>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
+    case 4: hipLaunchKernelGGL((gemv_mma4i<BITS, 4>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
+    case 8: hipLaunchKernelGGL((gemv_mma4i<BITS, 8>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
+    case 16: hipLaunchKernelGGL((gemv_mma4i<BITS, 16>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
+    }
+}
+
 // Which kernel multiplies: the vector ALU (gemv_static / gemv_runtime), the 32 x 32 x 16 matrix
 // instruction (gemv_mma, groups of at least two cells inside a step) or the 4 x 4 x 4 one
 // (gemv_mma4, groups of whole cells inside a step, and groups of whole steps at 2 and 3 bits).
@@ -1563,13 +1800,14 @@ void launch_mma4(int cpg, unsigned blocks, unsigned threads, hipStream_t st, con
 // vector-ALU kernel is bound by memory on the largest launches, where it stays; below that
 // gemv_mma4 in few, long wavefronts is ahead (single 7B matrices 13-15 %, the 7B set 5 %, the
 // 13B set 10 %).
-enum Mul { MUL_VALU, MUL_MMA32, MUL_MMA4 };
+enum Mul { MUL_VALU, MUL_MMA32, MUL_MMA4, MUL_MMA4I };
 constexpr size_t QG_VALU4_FROM = (size_t)256 << 20;      // code bytes of a launch
 Mul multiplier(int bits, int cpg, Kind kind, size_t code_bytes)
 {
     if (kind != KIND_STATIC && kind != KIND_RUNTIME) return MUL_VALU;
     const int want = g_tune_kernel ? g_tune_kernel : (bits == 4 && code_bytes >= QG_VALU4_FROM ? 1 : 3);
-    if (want == 3 && (kind == KIND_STATIC || bits != 4)) return MUL_MMA4;
+    if (want == 4 && bits != 3 && !(bits == 4 && kind == KIND_STATIC && cpg < 2)) return MUL_MMA4I;
+    if (want >= 3 && (kind == KIND_STATIC || bits != 4)) return MUL_MMA4;
     if (want == 2 && kind == KIND_STATIC && cpg >= 2) return MUL_MMA32;
     return MUL_VALU;
 }
@@ -1632,7 +1870,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     // each) for groups of whole steps at any width and for gemv_mma4 at 4 bits: measured 5-15 %
     // ahead of many short ones there (at 2 and 3 bits with groups inside a step the short ones
     // win, and so they do at 4 bits on the largest launches).
-    const bool few_long = rows == 0 && (bits_all == 4 ? code_bytes < QG_VALU4_FROM && (mul == MUL_MMA4 || kind == KIND_RUNTIME)
+    const bool few_long = rows == 0 && (bits_all == 4 ? code_bytes < QG_VALU4_FROM && (mul == MUL_MMA4 || mul == MUL_MMA4I || kind == KIND_RUNTIME)
                                                       : kind == KIND_RUNTIME);
     if (few_long) {
         const size_t share = code_bytes / (256 * 10);
@@ -1750,7 +1988,10 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         }
     } else if (kind == KIND_STATIC) {
         const int cpg = L[0].group / L[0].cell;
-        if (mul == MUL_MMA4) {
+        if (mul == MUL_MMA4I) {
+            if (bits == 4) launch_mma4i<4>(cpg, blocks, threads, st, A);
+            else launch_mma4i<2>(cpg, blocks, threads, st, A);
+        } else if (mul == MUL_MMA4) {
             if (bits == 4) launch_mma4<4>(cpg, blocks, threads, st, A);
             else if (bits == 2) launch_mma4<2>(cpg, blocks, threads, st, A);
             else launch_mma4<3>(cpg, blocks, threads, st, A);
@@ -1761,6 +2002,9 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         } else if (bits == 4) launch_static<4>(cpg, blocks, threads, st, A);
         else if (bits == 2) launch_static<2>(cpg, blocks, threads, st, A);
         else launch_static<3>(cpg, blocks, threads, st, A);
+    } else if (kind == KIND_RUNTIME && mul == MUL_MMA4I) {
+        if (bits == 2) launch_mma4i<2>(0, blocks, threads, st, A);
+        else launch_mma4i<4>(0, blocks, threads, st, A);
     } else if (kind == KIND_RUNTIME && mul == MUL_MMA4) {
         if (bits == 2) launch_mma4<2>(0, blocks, threads, st, A);
         else launch_mma4<3>(0, blocks, threads, st, A);
@@ -1780,7 +2024,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
 
 extern "C" int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel)
 {
-    if (waves_per_block < 0 || waves_per_block > 16 || bytes_per_wave < 0 || kernel < 0 || kernel > 3)
+    if (waves_per_block < 0 || waves_per_block > 16 || bytes_per_wave < 0 || kernel < 0 || kernel > 4)
         return QG_ERR_SHAPE;
     g_tune_wpb = waves_per_block;
     g_tune_bytes_per_wave = bytes_per_wave;
@@ -1958,7 +2202,7 @@ extern "C" int qg_gemv_autotune(const qg_gemv_desc *descs, int count, int sets, 
     constexpr int n_teams = sizeof(teams) / sizeof(teams[0]), n_sizes = sizeof(sizes) / sizeof(sizes[0]);
     int best[3] = {0, 0, 0};
     float best_ms = -1.0f;
-    for (int k = 1; k <= 3 && rc == QG_OK; ++k)
+    for (int k = 1; k <= 4 && rc == QG_OK; ++k)
         for (int a = 0; a < n_teams && rc == QG_OK; ++a)
             for (int b = 0; b < n_sizes && rc == QG_OK; ++b) {
                 g_tune_wpb = teams[a];

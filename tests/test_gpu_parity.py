@@ -219,11 +219,11 @@ def test_gemv_matches_oracle(qg, oracle, N, K, bits, group, kernel):
 @pytest.mark.parametrize("bits,group", [(4, 16), (4, 32), (4, 64), (4, 128), (2, 32), (2, 64), (2, 128), (2, 256),
                                         (3, 64), (3, 128), (3, 256),
                                         # groups of whole steps: the accumulators run across steps
-                                        (2, 512), (2, 2048), (3, 512), (3, 1024), (3, 2048)])
-@pytest.mark.parametrize("kernel", [2, 3])
+                                        (2, 512), (2, 2048), (3, 512), (3, 1024), (3, 2048), (4, 256), (4, 2048)])
+@pytest.mark.parametrize("kernel", [2, 3, 4])
 def test_gemv_matrix_core_kernel_every_group_size(qg, oracle, bits, group, kernel):
     # x with a wide range of magnitudes and both signs: its split into three bf16 parts must be exact
-    # (kernel 2: 32x32x16 matrix instruction, 3: 4x4x4)
+    # (kernel 2: 32x32x16 matrix instruction, 3: 4x4x4 on bf16, 4: 4x4x4 on int8 with x in 32-bit fixed point)
     _announce("gemv matrix cores", bits, group, kernel)
     N, K = 200, 2048
     W, x = synth.small_case(40 + bits + group, N, K, 0.02, True)
@@ -234,7 +234,8 @@ def test_gemv_matrix_core_kernel_every_group_size(qg, oracle, bits, group, kerne
 
 @pytest.mark.parametrize("tuning", [(1, 4096, 1), (2, 4096, 1), (4, 8192, 1), (8, 4096, 1), (16, 4096, 1), (4, 65536, 1),
                                     (1, 4096, 2), (3, 8192, 2), (8, 4096, 2), (16, 4096, 2), (4, 65536, 2),
-                                    (1, 4096, 3), (3, 8192, 3), (8, 4096, 3), (4, 65536, 3)])
+                                    (1, 4096, 3), (3, 8192, 3), (8, 4096, 3), (4, 65536, 3),
+                                    (1, 4096, 4), (3, 8192, 4), (8, 4096, 4), (4, 65536, 4)])
 @pytest.mark.parametrize("N,K,bits,group", [(200, 4096, 4, 128), (130, 3072, 3, 64), (130, 4096, 2, 32),
                                             (70, 4096, 4, 1024), (70, 5632, 4, 5632), (70, 3840, 3, 1280),
                                             (70, 5632, 2, 2816), (130, 11008, 3, 11008)])
@@ -383,7 +384,7 @@ def test_gemv_autotune_leaves_a_working_choice(qg, oracle):
     twin = qg.GroupedGemv([dict(p, packed=p["packed"].clone()) for p in problems], launch.workspace)
     try:
         wpb, bpw, kernel, us = qg.qg_gemv_autotune([launch, twin], repeats=6)
-        assert wpb in (0, 4, 8, 12, 16) and bpw in (0, 4096, 8192, 16384, 32768) and kernel in (1, 2, 3) and us > 0
+        assert wpb in (0, 2, 4, 8, 12, 16) and bpw in (0, 4096, 8192, 16384, 32768, 49152, 65536) and kernel in (1, 2, 3, 4) and us > 0
         for p in problems:
             p["y"].fill_(7.0)
         launch.launch()
@@ -450,7 +451,7 @@ def test_gemv_random_shapes_and_launch_shapes(qg, oracle, seed):
         K = group * ngroups
         N = int(rng.integers(1, 400))
         tuning = (int(rng.choice([0, 1, 2, 4, 7, 8, 12, 16])), int(rng.choice([0, 4096, 8192, 16384, 65536])),
-                  int(rng.choice([0, 1, 2, 3])))
+                  int(rng.choice([0, 1, 2, 3, 4])))
         _announce("gemv random", seed, case, N, K, bits, group, tuning)
         W, x = synth.small_case(seed * 100 + case, N, K, 0.02, bool(rng.integers(0, 2)))
         err = _gemv_case(qg, oracle, W, x, bits, group, tuning)

@@ -81,6 +81,6 @@ def test_bad_shapes_are_rejected_without_a_gpu(qg):
     assert L.qg_gemm_small(16, 64, 128, 4, 32, 64, 0, 16, 16, 1 << 20, None) == 2          # M <= 0
     assert L.qg_gemm_small(16, 64, 128, 4, 32, 64, 129, 16, 16, 1 << 20, None) == 2        # M > 128
     assert L.qg_set_gemm_tuning(9, 0) == 2 and L.qg_set_gemm_tuning(0, 13) == 2 and L.qg_set_gemm_tuning(0, 0) == 0
-    assert L.qg_set_gemv_tuning(99, 0, 0) == 2 and L.qg_set_gemv_tuning(0, 0, 4) == 2
+    assert L.qg_set_gemv_tuning(99, 0, 0) == 2 and L.qg_set_gemv_tuning(0, 0, 5) == 2
     assert L.qg_set_gemv_tuning(0, 0, 0) == 0
     assert b"aligned" in L.qg_status_string(4)
