@@ -1805,7 +1805,9 @@ constexpr size_t QG_VALU4_FROM = (size_t)256 << 20;      // code bytes of a laun
 Mul multiplier(int bits, int cpg, Kind kind, size_t code_bytes)
 {
     if (kind != KIND_STATIC && kind != KIND_RUNTIME) return MUL_VALU;
-    const int want = g_tune_kernel ? g_tune_kernel : (bits == 4 && code_bytes >= QG_VALU4_FROM ? 1 : 3);
+    const int want = g_tune_kernel ? g_tune_kernel
+                   : bits == 3 ? 3
+                   : bits == 4 && kind == KIND_STATIC && code_bytes >= QG_VALU4_FROM ? 1 : 4;
     if (want == 4 && bits != 3 && !(bits == 4 && kind == KIND_STATIC && cpg < 2)) return MUL_MMA4I;
     if (want >= 3 && (kind == KIND_STATIC || bits != 4)) return MUL_MMA4;
     if (want == 2 && kind == KIND_STATIC && cpg >= 2) return MUL_MMA32;
@@ -1863,6 +1865,12 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     // single step per wavefront are 8-12 % ahead on the 7B- and 13B-shaped sets (level on the
     // 65B-shaped one); larger groups lose with that shape
     if (mul == MUL_MMA4 && bits_all == 3 && kind == KIND_STATIC && L[0].group <= 64) {
+        if (g_tune_wpb == 0) cap = 8;
+        if (target == 0) target = pl[0].item_bytes;
+    }
+    // ... and for 2-bit groups inside a step on gemv_mma4i below 192 MB of codes: the same shape is
+    // 4-13 % ahead on the 7B- and 13B-shaped sets and 0-6 % behind on the 65B-shaped one
+    if (mul == MUL_MMA4I && bits_all == 2 && kind == KIND_STATIC && code_bytes < ((size_t)192 << 20)) {
         if (g_tune_wpb == 0) cap = 8;
         if (target == 0) target = pl[0].item_bytes;
     }
