@@ -27,8 +27,8 @@ import torch
 
 HBM_PEAK_GBS = 8000.0          # MI355X public peak
 # HBM bytes of one grouped launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
-# the same counters of a 256 MiB device copy (profiles/gemv_mma4_b4_g128_C2_layer_set.txt)
-MEASURED_TRAFFIC_BYTES = {"C2": 110.09e6}
+# the same counters of a 256 MiB device copy (profiles/gemv_mma4i_b4_g128_C2_layer_set.txt)
+MEASURED_TRAFFIC_BYTES = {"C2": 110.08e6}
 ROTATE_BYTES = 1.3e9           # distinct packed bytes touched between two uses of one copy
 
 
@@ -268,7 +268,7 @@ def main():
                     help="also run one plain device copy of 256 MiB (reference for HBM byte counters)")
     ap.add_argument("--wpb", type=int, default=0)
     ap.add_argument("--bytes-per-wave", type=int, default=0)
-    ap.add_argument("--kernel", type=int, default=0, help="0 built-in choice, 1 vector-ALU GEMV, 2 matrix-core GEMV (32x32x16), 3 matrix-core GEMV (4x4x4)")
+    ap.add_argument("--kernel", type=int, default=0, help="0 built-in choice, 1 vector-ALU GEMV, 2 matrix-core GEMV (32x32x16), 3 matrix-core GEMV (4x4x4, bf16), 4 matrix-core GEMV (4x4x4, int8)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: the path has no multi-GPU part (run with --gpus 1)",

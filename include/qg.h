@@ -100,7 +100,11 @@ int qg_unpack(const void *packed, int64_t N, int64_t K, int bits, int group, int
               uint8_t *q, float *s, uint8_t *z, void *stream);
 
 /* y[n] = sum_k s[n][k/G] * (q[n][k] - z[n][k/G]) * x[k]   (eq. (2); Algorithm 1)
- * evaluated per group as s * (sum q x - z * sum x), fp32 throughout, x kept in fp32.
+ * evaluated per group as s * (sum q x - z * sum x) in fp32.  The sums of q x are exact-product
+ * sums: on the vector ALU fp32 FMAs; on the matrix cores x goes in without loss of more than
+ * fp32 rounding -- as three bf16 parts that add up to x (3 bits), or as 32-bit fixed point
+ * relative to the largest |x| of each run of 128 or 256 k (2 and 4 bits: an error of at most
+ * 2^-30 of that largest |x| per term, below the rounding of the fp32 sum it enters).
  *   packed: QG_LAYOUT_DEVICE blob;  x [K] fp32, 64-byte aligned;  y [N] fp32 (overwritten).
  * workspace: qg_workspace_bytes(N, K, bits, group, 1) bytes, 16-byte aligned. */
 int qg_gemv(const void *packed, int64_t N, int64_t K, int bits, int group,
@@ -150,14 +154,15 @@ int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
  * kernel = 1: multiply-adds on the vector ALU; 2: on the matrix cores with the 32 x 32 x 16
  * instruction (where that kernel exists: groups of at least two cells and at most one step,
  * and, at 2 and 3 bits, groups of whole steps); 3: with the 4 x 4 x 4 instruction (groups of
- * whole cells up to one step, and, at 2 and 3 bits, groups of whole steps). */
+ * whole cells up to one step, and, at 2 and 3 bits, groups of whole steps) on bf16; 4: with
+ * the 4 x 4 x 4 instruction on int8 (2 and 4 bits; 4-bit groups of at least 16 weights). */
 int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel);
 /* Search for the fastest launch shape of one grouped launch by timing -- this machine's
  * counterpart of the paper's parameter search (Section 3, Algorithm 4).  `descs` holds `sets`
  * copies of the launch back to back (set i at descs + i * count; same shapes, normally
  * different packed buffers, so that a cache cannot serve the weights; sets = 1 times one set
- * again and again).  Runs the launch `repeats` times, rotating over the sets, for each of 126
- * candidates (team size x bytes per wavefront x vector-ALU or one of the two matrix-core kernels), WAITS for
+ * again and again).  Runs the launch `repeats` times, rotating over the sets, for each of 168
+ * candidates (team size x bytes per wavefront x vector-ALU or one of the three matrix-core kernels), WAITS for
  * the GPU (the only call that does), leaves the fastest installed as qg_set_gemv_tuning would,
  * and reports it (HOST pointers, each may be NULL; best_us = microseconds per launch).  The
  * outputs y are overwritten as by qg_gemv_grouped; all sets share the workspace. */
