@@ -1099,12 +1099,14 @@ __global__ __launch_bounds__(512) void gemv_mma4(QG_FIRST_BLOCKS, const GemvArgs
 }
 
 // ---------------------------------------------------------------------------------------
-// gemv_mma4i: the 4 x 4 x 4 matrix instruction on 8-bit integers (2- and 4-bit codes).  A
-// code needs no exponent around it to be an int8, so a word of 4-bit codes becomes two
-// operands with two ANDs and one shift (w & 0x0f0f0f0f holds codes 0, 2, 4, 6 as bytes,
-// (w >> 4) & 0x0f0f0f0f codes 1, 3, 5, 7), a word of 2-bit codes four operands with four ANDs
-// and one shift (the fields at bits 2 and 4 of a byte stay where they are and count 4 q and
-// 16 q; the x values they meet are stored divided by 4 and 16).  x goes in as 32-bit fixed
+// gemv_mma4i: the 4 x 4 x 4 matrix instruction on 8-bit integers.  A code needs no exponent
+// around it to be an int8, so a word of 4-bit codes becomes two operands with two ANDs and one
+// shift (w & 0x0f0f0f0f holds codes 0, 2, 4, 6 as bytes, (w >> 4) & 0x0f0f0f0f codes 1, 3, 5,
+// 7), a word of 2-bit codes four operands with four ANDs and one shift (the fields at bits 2
+// and 4 of a byte stay where they are and count 4 q and 16 q; the x values they meet are
+// stored divided by 4 and 16), and a word of the 3-bit cell -- every byte holds one code in
+// bits 0-2 and one in bits 3-5 -- two operands with two ANDs (q and 8 q; the fourth word of
+// the cell is put together from the spare bits 6-7 first).  x goes in as 32-bit fixed
 // point relative to the largest |x| of the step (a power of two, so scaling is exact),
 // cut into four signed bytes that fill the four rows of the A operand: lane l receives
 // D_i = sum_k q_k digit_i(x_k) for its own output, and sum_i 256^i D_i / scale = sum_k q_k x_k
@@ -1113,8 +1115,22 @@ __global__ __launch_bounds__(512) void gemv_mma4(QG_FIRST_BLOCKS, const GemvArgs
 template <int BITS>
 __device__ inline int mma4i_slot(int c)              // 4 * operand of the cell + byte, of code c of a cell
 {
-    constexpr int OPC = Fmt<BITS>::CELL / 4;
-    return (c % OPC) * 4 + c / OPC;
+    if constexpr (BITS == 3) {
+        const int w = c >> 3, r = c & 7;             // word (A, B, C, T); byte r & 3, low or high field
+        return (2 * w + (r >> 2)) * 4 + (r & 3);
+    } else {
+        constexpr int OPC = Fmt<BITS>::CELL / 4;
+        return (c % OPC) * 4 + c / OPC;
+    }
+}
+
+// what the field of code c of a cell counts, as the divisor applied to the x it meets
+template <int BITS>
+__device__ inline float mma4i_xdiv(int c)
+{
+    if constexpr (BITS == 3) return (c & 7) >= 4 ? 0.125f : 1.0f;
+    else if constexpr (BITS == 2) return (c & 3) == 1 ? 0.25f : (c & 3) == 2 ? 0.0625f : 1.0f;
+    else return 1.0f;
 }
 
 typedef int mma4i_acc __attribute__((ext_vector_type(4)));
@@ -1130,15 +1146,13 @@ __device__ inline float dpp_max(float v)             // for v >= 0: disabled row
 template <int BITS, int CPG>
 __global__ __launch_bounds__(512) void gemv_mma4i(QG_FIRST_BLOCKS, const GemvArgs A)
 {
-    static_assert(BITS == 2 || BITS == 4, "3-bit fields do not sit inside bytes");
-    static_assert(CPG == 0 || BITS == 2 || CPG % 2 == 0, "a 128-bit read of A covers two 4-bit cells");
+    static_assert(CPG == 0 || BITS != 4 || CPG % 2 == 0, "a 128-bit read of A covers two 4-bit cells");
     using F = Fmt<BITS>;
     constexpr int L = loads_per_step<BITS>();
     constexpr int S = codes_per_step<BITS>();
     constexpr int CELLS = cells_per_step<BITS>();
     constexpr int GPS = CPG > 0 ? CELLS / CPG : 0;
-    constexpr int OPC = F::CELL / 4;                // matrix instructions (operands) per cell
-    constexpr int CPR = 4 / OPC;                    // cells per 128-bit read of A (16 k)
+    constexpr int READS = S / 16;                   // 128-bit reads of A per step: 16 k, four matrix instructions each
     constexpr int NXV = S / 128;
     constexpr int ZPER = 32 / F::ZBITS;
     constexpr int PITCH = S + 16;                   // bytes per digit row: the four rows on different banks
@@ -1168,10 +1182,7 @@ __global__ __launch_bounds__(512) void gemv_mma4i(QG_FIRST_BLOCKS, const GemvArg
     int xpos[NXV][2];
     float xdiv[2];
 #pragma unroll
-    for (int e = 0; e < 2; ++e) {
-        const int o = ((2 * lane + e) % F::CELL) % OPC;
-        xdiv[e] = BITS == 2 && o == 1 ? 0.25f : BITS == 2 && o == 2 ? 0.0625f : 1.0f;
-    }
+    for (int e = 0; e < 2; ++e) xdiv[e] = mma4i_xdiv<BITS>((2 * lane + e) % F::CELL);
 #pragma unroll
     for (int i = 0; i < NXV; ++i)
 #pragma unroll
@@ -1217,23 +1228,42 @@ __global__ __launch_bounds__(512) void gemv_mma4i(QG_FIRST_BLOCKS, const GemvArg
     mma4i_acc acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
     float tacc = 0.0f, xacc = 0.0f;                 // CPG == 0: T and x of the running piece of a group
 
-    // the matrix instructions of CPR cells: one 128-bit read of A feeds four of them
-    auto cells_mfma = [&](const D &d, int first, int buf) {
+    // the four matrix instructions of one 128-bit read of A (16 k): two 4-bit cells, one 2-bit
+    // cell or half a 3-bit cell
+    uint32_t spare = 0;                             // 3 bits: the fourth word of the cell in hand
+    auto read_mfma = [&](const D &d, int rd, int buf) {
         MmaOperand a;
-        a.q = *(const lds_u128 *)(abase[buf] + first * F::CELL);
+        a.q = *(const lds_u128 *)(abase[buf] + rd * 16);
         uint32_t b[4];
+        if constexpr (BITS == 4) {
 #pragma unroll
-        for (int c = 0; c < CPR; ++c) {
-            const int cell = first + c;
-            const uint32_t w = word_of(d.v[cell >> 2], cell & 3);
-            if constexpr (BITS == 4) {
+            for (int c = 0; c < 2; ++c) {
+                const int cell = 2 * rd + c;
+                const uint32_t w = word_of(d.v[cell >> 2], cell & 3);
                 b[2 * c] = w & 0x0f0f0f0fu;
                 b[2 * c + 1] = (w >> 4) & 0x0f0f0f0fu;
+            }
+        } else if constexpr (BITS == 2) {
+            const uint32_t w = word_of(d.v[rd >> 2], rd & 3);
+            b[0] = w & 0x03030303u;
+            b[1] = w & 0x0c0c0c0cu;
+            b[2] = w & 0x30303030u;
+            b[3] = (w >> 6) & 0x03030303u;
+        } else {
+            const int cell = rd >> 1, u = cell >> 2, j = cell & 3;
+            if ((rd & 1) == 0) {
+                const uint32_t wa = word_of(d.v[u * 3], j), wb = word_of(d.v[u * 3 + 1], j), wc = word_of(d.v[u * 3 + 2], j);
+                spare = ((wa >> 6) & 0x03030303u) | ((wb >> 4) & 0x0c0c0c0cu) | ((wc >> 2) & 0x30303030u);
+                b[0] = wa & 0x07070707u;
+                b[1] = wa & 0x38383838u;
+                b[2] = wb & 0x07070707u;
+                b[3] = wb & 0x38383838u;
             } else {
-                b[0] = w & 0x03030303u;
-                b[1] = w & 0x0c0c0c0cu;
-                b[2] = w & 0x30303030u;
-                b[3] = (w >> 6) & 0x03030303u;
+                const uint32_t wc = word_of(d.v[u * 3 + 2], j);
+                b[0] = wc & 0x07070707u;
+                b[1] = wc & 0x38383838u;
+                b[2] = spare & 0x07070707u;
+                b[3] = spare & 0x38383838u;
             }
         }
         acc0 = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[0], (int)b[0], acc0, 0, 0, 0);
@@ -1255,11 +1285,12 @@ __global__ __launch_bounds__(512) void gemv_mma4i(QG_FIRST_BLOCKS, const GemvArg
         if constexpr (CPG > 0) {
             float xhat[GPS];
             step_group_sums<BITS, GPS>(d, xhat);
+            constexpr int RPG = CPG * F::CELL / 16;           // reads per group
 #pragma unroll
-            for (int first = 0; first < CELLS; first += CPR) {
-                cells_mfma(d, first, buf);
-                if ((first + CPR) % CPG == 0) {
-                    const int gs = (first + CPR) / CPG - 1;
+            for (int rd = 0; rd < READS; ++rd) {
+                read_mfma(d, rd, buf);
+                if ((rd + 1) % RPG == 0) {
+                    const int gs = (rd + 1) / RPG - 1;
                     const int gabs = step * GPS + gs;
                     const float tsum = take_sum() * inv;
                     const uint32_t zword = d.zw[D::ZW > 1 ? gs / D::ZPER : 0];
@@ -1271,7 +1302,7 @@ __global__ __launch_bounds__(512) void gemv_mma4i(QG_FIRST_BLOCKS, const GemvArg
 #pragma unroll
             for (int i = 0; i < NXV; ++i) xacc += d.xv[i].x + d.xv[i].y;
 #pragma unroll
-            for (int first = 0; first < CELLS; first += CPR) cells_mfma(d, first, buf);
+            for (int rd = 0; rd < READS; ++rd) read_mfma(d, rd, buf);
             tacc = fmaf(take_sum(), inv, tacc);     // every step has a scale of its own
         }
     };
@@ -1782,13 +1813,16 @@ void launch_mma4i(int cpg, unsigned blocks, unsigned threads, hipStream_t st, co
     switch (cpg) {
     case 0: hipLaunchKernelGGL((gemv_mma4i<BITS, 0>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
     case 1:
-        if constexpr (BITS == 2)
+        if constexpr (BITS != 4)
             hipLaunchKernelGGL((gemv_mma4i<BITS, 1>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A);
         break;
     case 2: hipLaunchKernelGGL((gemv_mma4i<BITS, 2>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
     case 4: hipLaunchKernelGGL((gemv_mma4i<BITS, 4>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
     case 8: hipLaunchKernelGGL((gemv_mma4i<BITS, 8>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
-    case 16: hipLaunchKernelGGL((gemv_mma4i<BITS, 16>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
+    case 16:
+        if constexpr (BITS != 3)
+            hipLaunchKernelGGL((gemv_mma4i<BITS, 16>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A);
+        break;
     }
 }
 
@@ -1806,9 +1840,8 @@ Mul multiplier(int bits, int cpg, Kind kind, size_t code_bytes)
 {
     if (kind != KIND_STATIC && kind != KIND_RUNTIME) return MUL_VALU;
     const int want = g_tune_kernel ? g_tune_kernel
-                   : bits == 3 ? 3
                    : bits == 4 && kind == KIND_STATIC && code_bytes >= QG_VALU4_FROM ? 1 : 4;
-    if (want == 4 && bits != 3 && !(bits == 4 && kind == KIND_STATIC && cpg < 2)) return MUL_MMA4I;
+    if (want == 4 && !(bits == 4 && kind == KIND_STATIC && cpg < 2)) return MUL_MMA4I;
     if (want >= 3 && (kind == KIND_STATIC || bits != 4)) return MUL_MMA4;
     if (want == 2 && kind == KIND_STATIC && cpg >= 2) return MUL_MMA32;
     return MUL_VALU;
@@ -1861,16 +1894,14 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         if (g_tune_wpb == 0) cap = 4;
     }
     size_t target = (size_t)g_tune_bytes_per_wave;               // code bytes per wavefront
-    // ... except for 3-bit groups of up to 64 weights on gemv_mma4: there teams of up to 8 with a
-    // single step per wavefront are 8-12 % ahead on the 7B- and 13B-shaped sets (level on the
-    // 65B-shaped one); larger groups lose with that shape
-    if (mul == MUL_MMA4 && bits_all == 3 && kind == KIND_STATIC && L[0].group <= 64) {
-        if (g_tune_wpb == 0) cap = 8;
-        if (target == 0) target = pl[0].item_bytes;
-    }
-    // ... and for 2-bit groups inside a step on gemv_mma4i below 192 MB of codes: the same shape is
-    // 4-13 % ahead on the 7B- and 13B-shaped sets and 0-6 % behind on the 65B-shaped one
-    if (mul == MUL_MMA4I && bits_all == 2 && kind == KIND_STATIC && code_bytes < ((size_t)192 << 20)) {
+    // ... except for 2- and 3-bit groups inside a step on gemv_mma4i below 192 MB of codes: there
+    // teams of up to 8 with a single step per wavefront are 4-13 % ahead (7B- and 13B-shaped
+    // sets; on the 65B-shaped one that shape is 0-6 % behind).  The same on gemv_mma4 for 3-bit
+    // groups of up to 64 weights (8-12 % ahead on the smaller sets, level on the large one).
+    const bool one_step = rows == 0 && kind == KIND_STATIC &&
+                          ((mul == MUL_MMA4I && bits_all != 4 && code_bytes < ((size_t)192 << 20)) ||
+                           (mul == MUL_MMA4 && bits_all == 3 && L[0].group <= 64));
+    if (one_step) {
         if (g_tune_wpb == 0) cap = 8;
         if (target == 0) target = pl[0].item_bytes;
     }
@@ -1998,7 +2029,8 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         const int cpg = L[0].group / L[0].cell;
         if (mul == MUL_MMA4I) {
             if (bits == 4) launch_mma4i<4>(cpg, blocks, threads, st, A);
-            else launch_mma4i<2>(cpg, blocks, threads, st, A);
+            else if (bits == 2) launch_mma4i<2>(cpg, blocks, threads, st, A);
+            else launch_mma4i<3>(cpg, blocks, threads, st, A);
         } else if (mul == MUL_MMA4) {
             if (bits == 4) launch_mma4<4>(cpg, blocks, threads, st, A);
             else if (bits == 2) launch_mma4<2>(cpg, blocks, threads, st, A);
@@ -2012,6 +2044,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         else launch_static<3>(cpg, blocks, threads, st, A);
     } else if (kind == KIND_RUNTIME && mul == MUL_MMA4I) {
         if (bits == 2) launch_mma4i<2>(0, blocks, threads, st, A);
+        else if (bits == 3) launch_mma4i<3>(0, blocks, threads, st, A);
         else launch_mma4i<4>(0, blocks, threads, st, A);
     } else if (kind == KIND_RUNTIME && mul == MUL_MMA4) {
         if (bits == 2) launch_mma4<2>(0, blocks, threads, st, A);
