@@ -102,9 +102,9 @@ int qg_unpack(const void *packed, int64_t N, int64_t K, int bits, int group, int
 /* y[n] = sum_k s[n][k/G] * (q[n][k] - z[n][k/G]) * x[k]   (eq. (2); Algorithm 1)
  * evaluated per group as s * (sum q x - z * sum x) in fp32.  The sums of q x are exact-product
  * sums: on the vector ALU fp32 FMAs; on the matrix cores x goes in without loss of more than
- * fp32 rounding -- as three bf16 parts that add up to x (3 bits), or as 32-bit fixed point
- * relative to the largest |x| of each run of 128 or 256 k (2 and 4 bits: an error of at most
- * 2^-30 of that largest |x| per term, below the rounding of the fp32 sum it enters).
+ * fp32 rounding -- as 32-bit fixed point relative to the largest |x| of each run of 128 (4
+ * bits) or 256 k (an error of at most 2^-30 of that largest |x| per term, below the rounding
+ * of the fp32 sum it enters; the built-in choice), or as three bf16 parts that add up to x.
  *   packed: QG_LAYOUT_DEVICE blob;  x [K] fp32, 64-byte aligned;  y [N] fp32 (overwritten).
  * workspace: qg_workspace_bytes(N, K, bits, group, 1) bytes, 16-byte aligned. */
 int qg_gemv(const void *packed, int64_t N, int64_t K, int bits, int group,
@@ -155,7 +155,7 @@ int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
  * instruction (where that kernel exists: groups of at least two cells and at most one step,
  * and, at 2 and 3 bits, groups of whole steps); 3: with the 4 x 4 x 4 instruction (groups of
  * whole cells up to one step, and, at 2 and 3 bits, groups of whole steps) on bf16; 4: with
- * the 4 x 4 x 4 instruction on int8 (2 and 4 bits; 4-bit groups of at least 16 weights). */
+ * the 4 x 4 x 4 instruction on int8 (4-bit groups of at least 16 weights). */
 int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel);
 /* Search for the fastest launch shape of one grouped launch by timing -- this machine's
  * counterpart of the paper's parameter search (Section 3, Algorithm 4).  `descs` holds `sets`
