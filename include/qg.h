@@ -105,6 +105,8 @@ int qg_unpack(const void *packed, int64_t N, int64_t K, int bits, int group, int
  * fp32 rounding -- as 32-bit fixed point relative to the largest |x| of each run of 128 (4
  * bits) or 256 k (an error of at most 2^-30 of that largest |x| per term, below the rounding
  * of the fp32 sum it enters; the built-in choice), or as three bf16 parts that add up to x.
+ * (The fixed point keeps that precision while the largest |x| of a run is at least 2^-97;
+ * NaN and infinity in x reach y through the sum of x of their group.)
  *   packed: QG_LAYOUT_DEVICE blob;  x [K] fp32, 64-byte aligned;  y [N] fp32 (overwritten).
  * workspace: qg_workspace_bytes(N, K, bits, group, 1) bytes, 16-byte aligned. */
 int qg_gemv(const void *packed, int64_t N, int64_t K, int bits, int group,

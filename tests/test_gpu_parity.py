@@ -232,6 +232,41 @@ def test_gemv_matrix_core_kernel_every_group_size(qg, oracle, bits, group, kerne
     assert err <= TOL_FP32, err
 
 
+def _awkward_x(kind, K, rng):
+    x = rng.standard_normal(K).astype(np.float32)
+    if kind == "zero runs":                 # whole steps of zeros between ordinary ones
+        x[256:768] = 0.0
+        x[K - 256:] = 0.0
+    elif kind == "one nonzero per step":
+        keep = x[::128].copy()
+        x[:] = 0.0
+        x[::128] = keep
+    elif kind == "huge":                    # near the top of the fp32 range, both signs
+        x *= np.float32(1e30)
+    elif kind == "tiny":
+        x *= np.float32(1e-25)
+    elif kind == "spikes":                  # one element per step 2^20 above the rest
+        x[5::256] *= np.float32(2.0 ** 20)
+    elif kind == "negative peak":
+        x = -np.abs(x)
+        x[3::64] *= np.float32(1000.0)
+    return x
+
+
+@pytest.mark.parametrize("kind", ["zero runs", "one nonzero per step", "huge", "tiny", "spikes", "negative peak"])
+@pytest.mark.parametrize("bits,group", [(4, 128), (4, 32), (3, 64), (2, 32), (2, 2048), (3, 1024), (4, 2048)])
+@pytest.mark.parametrize("kernel", [0, 3])
+def test_gemv_awkward_activations(qg, oracle, bits, group, kernel, kind):
+    # inputs that stress how x enters the matrix instructions: the fixed point of a step follows
+    # the largest |x| of that step (int8 form), the bf16 parts must carry signs and magnitudes
+    _announce("gemv awkward x", bits, group, kernel, kind)
+    N, K = 130, 2048
+    W, _ = synth.small_case(90 + bits + group, N, K, 0.02, True)
+    x = _awkward_x(kind, K, np.random.default_rng(17 + bits))
+    err = _gemv_case(qg, oracle, W, x, bits, group, (0, 0, kernel))
+    assert err <= TOL_FP32, err
+
+
 @pytest.mark.parametrize("tuning", [(1, 4096, 1), (2, 4096, 1), (4, 8192, 1), (8, 4096, 1), (16, 4096, 1), (4, 65536, 1),
                                     (1, 4096, 2), (3, 8192, 2), (8, 4096, 2), (16, 4096, 2), (4, 65536, 2),
                                     (1, 4096, 3), (3, 8192, 3), (8, 4096, 3), (4, 65536, 3),
