@@ -267,6 +267,26 @@ def test_gemv_awkward_activations(qg, oracle, bits, group, kernel, kind):
     assert err <= TOL_FP32, err
 
 
+@pytest.mark.parametrize("bits,group", [(4, 128), (3, 64), (2, 32), (4, 1024)])
+@pytest.mark.parametrize("kernel", [0, 1, 3])
+def test_gemv_non_finite_activations_reach_the_output(qg, bits, group, kernel):
+    # a NaN or an infinity in x must not vanish in the conversion of x for the matrix instructions
+    _announce("gemv non-finite x", bits, group, kernel)
+    N, K = 130, 1024
+    W, x = synth.small_case(3 + bits, N, K, 0.02, False)
+    q, s, z = qg.qg_quantize(dev(W), bits, group)
+    blob = qg.qg_pack(q, s, z, bits, group, qg.QG_LAYOUT_DEVICE)
+    qg.qg_set_gemv_tuning(0, 0, kernel)
+    try:
+        for bad in (np.nan, np.inf, -np.inf):
+            xb = x.copy()
+            xb[517] = bad
+            y = host(qg.qg_gemv(blob, N, K, bits, group, dev(xb)))
+            assert not np.isfinite(y).any(), (bad, int(np.isfinite(y).sum()))
+    finally:
+        qg.qg_set_gemv_tuning(0, 0, 0)
+
+
 @pytest.mark.parametrize("tuning", [(1, 4096, 1), (2, 4096, 1), (4, 8192, 1), (8, 4096, 1), (16, 4096, 1), (4, 65536, 1),
                                     (1, 4096, 2), (3, 8192, 2), (8, 4096, 2), (16, 4096, 2), (4, 65536, 2),
                                     (1, 4096, 3), (3, 8192, 3), (8, 4096, 3), (4, 65536, 3),
