@@ -24,9 +24,11 @@
 // maintenance is needed, and results do not depend on timing.
 //
 // Kernels: gemv_static (groups up to one step, the arithmetic above on the vector ALU),
-// gemv_mma (the same groups with the multiply-adds on the matrix cores, see there),
-// gemv_runtime (groups of whole steps up to one group per output, eq. (1)) and gemv_generic
-// (anything else).  All share the work distribution and the reductions.
+// gemv_runtime (groups of whole steps up to one group per output, eq. (1)), gemv_generic
+// (anything else), and three forms with the multiply-adds on the matrix cores, still one lane
+// per output: gemv_mma4i (4 x 4 x 4 instruction on int8, x in fixed point; the built-in choice
+// wherever it applies), gemv_mma4 (the same instruction on bf16, x in three bf16 parts) and
+// gemv_mma (32 x 32 x 16 on bf16).  All share the work distribution and the reductions.
 #include "qg_common.h"
 
 namespace {
