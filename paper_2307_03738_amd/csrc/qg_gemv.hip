@@ -1758,8 +1758,9 @@ FirstBlocks first_blocks(const GemvArgs &A)
 }
 
 template <int BITS>
-void launch_static(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+bool launch_static(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
 {
+    if (!(cpg == 1 || cpg == 2 || cpg == 4 || cpg == 8 || (cpg == 16 && BITS != 3))) return false;
     switch (cpg) {
     case 1: hipLaunchKernelGGL((gemv_static<BITS, 1>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
     case 2: hipLaunchKernelGGL((gemv_static<BITS, 2>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
@@ -1770,11 +1771,13 @@ void launch_static(int cpg, unsigned blocks, unsigned threads, hipStream_t st, c
             hipLaunchKernelGGL((gemv_static<BITS, 16>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
         break;
     }
+    return true;
 }
 
 template <int BITS>
-void launch_mma(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+bool launch_mma(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
 {
+    if (!(cpg == 2 || cpg == 4 || cpg == 8 || (cpg == 16 && BITS != 3))) return false;
     // x of one step in three bf16 parts, two buffers, per wavefront
     const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 3 * codes_per_step<BITS>() * sizeof(uint16_t);
     switch (cpg) {
@@ -1786,12 +1789,14 @@ void launch_mma(int cpg, unsigned blocks, unsigned threads, hipStream_t st, cons
             hipLaunchKernelGGL((gemv_mma<BITS, 16>), dim3(blocks), dim3(threads), lds, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
         break;
     }
+    return true;
 }
 
 // gemv_mma4: cpg = cells per group, 0 for groups of whole steps
 template <int BITS>
-void launch_mma4(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+bool launch_mma4(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
 {
+    if (!(cpg == 0 || cpg == 1 || cpg == 2 || cpg == 4 || cpg == 8 || (cpg == 16 && BITS != 3))) return false;
     const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 4 * (codes_per_step<BITS>() + 8) * sizeof(uint16_t);
     const FirstBlocks f = first_blocks(A);
     switch (cpg) {
@@ -1805,11 +1810,13 @@ void launch_mma4(int cpg, unsigned blocks, unsigned threads, hipStream_t st, con
             hipLaunchKernelGGL((gemv_mma4<BITS, 16>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A);
         break;
     }
+    return true;
 }
 
 template <int BITS>
-void launch_mma4i(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+bool launch_mma4i(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
 {
+    if (!(cpg == 0 || (cpg == 1 && BITS != 4) || cpg == 2 || cpg == 4 || cpg == 8 || (cpg == 16 && BITS != 3))) return false;
     const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 4 * (codes_per_step<BITS>() + 16);
     const FirstBlocks f = first_blocks(A);
     switch (cpg) {
@@ -1826,16 +1833,18 @@ void launch_mma4i(int cpg, unsigned blocks, unsigned threads, hipStream_t st, co
             hipLaunchKernelGGL((gemv_mma4i<BITS, 16>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A);
         break;
     }
+    return true;
 }
 
 // Which kernel multiplies: the vector ALU (gemv_static / gemv_runtime), the 32 x 32 x 16 matrix
-// instruction (gemv_mma, groups of at least two cells inside a step) or the 4 x 4 x 4 one
-// (gemv_mma4, groups of whole cells inside a step, and groups of whole steps at 2 and 3 bits).
-// Measured on the three layer sets over G = 32 ... K: at 2 and 3 bits gemv_mma4 is ahead of
-// both others nearly everywhere (by 5-13 %, level at the smallest groups).  At 4 bits the
-// vector-ALU kernel is bound by memory on the largest launches, where it stays; below that
-// gemv_mma4 in few, long wavefronts is ahead (single 7B matrices 13-15 %, the 7B set 5 %, the
-// 13B set 10 %).
+// instruction (gemv_mma, groups of at least two cells inside a step), or the 4 x 4 x 4 one on
+// bf16 (gemv_mma4) or int8 (gemv_mma4i), both for groups of whole cells inside a step and for
+// groups of whole steps (gemv_mma4 not at 4 bits there; gemv_mma4i not for 4-bit groups of a
+// single cell).  Measured on the three layer sets over G = 16 ... K: gemv_mma4i is ahead of
+// the others nearly everywhere (2-13 % over gemv_mma4, which was 5-13 % ahead of the vector ALU
+// at 2 and 3 bits).  At 4 bits with groups inside a step the vector-ALU kernel is bound by
+// memory on the largest launches and level with the others or ahead, depending on the machine;
+// it stays there.
 enum Mul { MUL_VALU, MUL_MMA32, MUL_MMA4, MUL_MMA4I };
 constexpr size_t QG_VALU4_FROM = (size_t)256 << 20;      // code bytes of a launch
 Mul multiplier(int bits, int cpg, Kind kind, size_t code_bytes)
@@ -2029,21 +2038,20 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         }
     } else if (kind == KIND_STATIC) {
         const int cpg = L[0].group / L[0].cell;
-        if (mul == MUL_MMA4I) {
-            if (bits == 4) launch_mma4i<4>(cpg, blocks, threads, st, A);
-            else if (bits == 2) launch_mma4i<2>(cpg, blocks, threads, st, A);
-            else launch_mma4i<3>(cpg, blocks, threads, st, A);
-        } else if (mul == MUL_MMA4) {
-            if (bits == 4) launch_mma4<4>(cpg, blocks, threads, st, A);
-            else if (bits == 2) launch_mma4<2>(cpg, blocks, threads, st, A);
-            else launch_mma4<3>(cpg, blocks, threads, st, A);
-        } else if (mul == MUL_MMA32) {
-            if (bits == 4) launch_mma<4>(cpg, blocks, threads, st, A);
-            else if (bits == 2) launch_mma<2>(cpg, blocks, threads, st, A);
-            else launch_mma<3>(cpg, blocks, threads, st, A);
-        } else if (bits == 4) launch_static<4>(cpg, blocks, threads, st, A);
-        else if (bits == 2) launch_static<2>(cpg, blocks, threads, st, A);
-        else launch_static<3>(cpg, blocks, threads, st, A);
+        bool launched;
+        if (mul == MUL_MMA4I)
+            launched = bits == 4 ? launch_mma4i<4>(cpg, blocks, threads, st, A)
+                     : bits == 2 ? launch_mma4i<2>(cpg, blocks, threads, st, A) : launch_mma4i<3>(cpg, blocks, threads, st, A);
+        else if (mul == MUL_MMA4)
+            launched = bits == 4 ? launch_mma4<4>(cpg, blocks, threads, st, A)
+                     : bits == 2 ? launch_mma4<2>(cpg, blocks, threads, st, A) : launch_mma4<3>(cpg, blocks, threads, st, A);
+        else if (mul == MUL_MMA32)
+            launched = bits == 4 ? launch_mma<4>(cpg, blocks, threads, st, A)
+                     : bits == 2 ? launch_mma<2>(cpg, blocks, threads, st, A) : launch_mma<3>(cpg, blocks, threads, st, A);
+        else
+            launched = bits == 4 ? launch_static<4>(cpg, blocks, threads, st, A)
+                     : bits == 2 ? launch_static<2>(cpg, blocks, threads, st, A) : launch_static<3>(cpg, blocks, threads, st, A);
+        if (!launched) return QG_ERR_UNSUPPORTED;      // no kernel was built for this group size
     } else if (kind == KIND_RUNTIME && mul == MUL_MMA4I) {
         if (bits == 2) launch_mma4i<2>(0, blocks, threads, st, A);
         else if (bits == 3) launch_mma4i<3>(0, blocks, threads, st, A);
