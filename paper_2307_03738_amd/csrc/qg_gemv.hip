@@ -1940,6 +1940,14 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         if (target > 16384) target = 16384;
     }
 
+    // The limit of 64 groups per wavefront belongs to the vector-ALU kernel (it keeps x-hat one
+    // group per lane); the 4 x 4 x 4 kernels form x-hat step by step and take any number of steps.
+    int64_t valu_max_spw[QG_MAX_GROUPED];
+    for (int i = 0; i < count; ++i) {
+        valu_max_spw[i] = pl[i].max_spw;
+        if (mul == MUL_MMA4 || mul == MUL_MMA4I) pl[i].max_spw = (int64_t)1 << 30;
+    }
+
     int wpb = 1;
     int64_t spw_of[QG_MAX_GROUPED], team_of[QG_MAX_GROUPED], chunks_of[QG_MAX_GROUPED];
     auto plan_all = [&](int limit) -> bool {
@@ -1983,6 +1991,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         bool ok = cap < widest && plan_all(widest);
         if (!ok && mma) {
             mul = MUL_VALU;
+            for (int i = 0; i < count; ++i) pl[i].max_spw = valu_max_spw[i];
             ok = plan_all(16);
         }
         if (!ok) return QG_ERR_UNSUPPORTED;

@@ -315,11 +315,13 @@ def test_gemv_extreme_shapes(qg, oracle, N, K, bits, group):
 
 
 @pytest.mark.parametrize("N,K,bits,group,tuning", [
-    (70, 262144, 2, 16, (0, 0, 0)),      # 256 wavefronts per tile: the widest teams of the 4 x 4 x 4 kernel
-    (70, 294912, 2, 16, (0, 0, 0)),      # ... more than those cover: the vector-ALU kernel's teams of 16
+    (70, 262144, 2, 16, (0, 0, 0)),      # a long K of tiny groups on the built-in choice
+    (70, 294912, 2, 16, (0, 0, 0)),
     (70, 262144, 4, 16, (0, 0, 0)),
-    (70, 294912, 4, 16, (0, 0, 0)),
-    (130, 13824, 2, 16, (2, 0, 3)),      # a forced team size that cannot cover K without an empty workgroup
+    (70, 294912, 4, 16, (0, 0, 1)),      # vector ALU: 64 groups per wavefront at most, 288 wavefronts per tile
+    (70, 262144, 2, 16, (4, 0, 2)),      # 32 x 32 x 16 kernel: teams of 4 cannot cover K, the widest (8) can
+    (70, 294912, 2, 16, (4, 0, 2)),      # ... nor can those: the vector-ALU kernel's teams of 16
+    (130, 13824, 2, 16, (2, 0, 2)),      # a forced team size that cannot cover K without an empty workgroup
     (130, 13824, 2, 16, (1, 4096, 3)),
     (130, 13824, 3, 32, (1, 4096, 2))])
 def test_gemv_team_size_fallback(qg, oracle, N, K, bits, group, tuning):
