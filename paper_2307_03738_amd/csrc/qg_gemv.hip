@@ -1276,8 +1276,9 @@ __global__ __launch_bounds__(512) void gemv_mma4i(QG_FIRST_BLOCKS, const GemvArg
     // sum_i 256^i D_i of the finished cells for this lane's output, in units of 1 / scale;
     // clears the accumulators
     auto take_sum = [&]() {
-        const int lo = ((acc0[1] + acc1[1]) << 8) + (acc0[0] + acc1[0]);
-        const int hi = ((acc0[3] + acc1[3]) << 8) + (acc0[2] + acc1[2]);
+        // (|D_i| of a step stays below 2^21, so the sums fit 32 bits)
+        const int lo = (acc0[1] + acc1[1]) * 256 + (acc0[0] + acc1[0]);
+        const int hi = (acc0[3] + acc1[3]) * 256 + (acc0[2] + acc1[2]);
         acc0 = mma4i_acc{0, 0, 0, 0};
         acc1 = mma4i_acc{0, 0, 0, 0};
         return fmaf((float)hi, 65536.0f, (float)lo);
