@@ -10,7 +10,11 @@ of traffic apart.
 
 Prints one JSON line.  `value` is microseconds per layer set; `roofline` prices the GEMV
 kernel against the 8 TB/s HBM peak with the algorithmic bytes of the set (codes + fp32 scale
-+ b-bit zero per group + x + y); `cpu_baseline` is the CPU oracle on the same packed data.
++ b-bit zero per group + x + y); `cpu_baseline` is the CPU oracle on the same packed data, and
+its result doubles as the check of what was timed: `parity_max_scaled_err` compares the y of
+the last timed launch with it and the run fails above 1e-4.  `other_workloads` carries the
+13B- and 65B-shaped layer sets (3-bit g64, 2-bit g32; timing only, weights drawn on the GPU)
+and the nine small-M GEMM problems, timed the same way.
 """
 import argparse
 import json
@@ -26,10 +30,26 @@ import numpy as np
 import torch
 
 HBM_PEAK_GBS = 8000.0          # MI355X public peak
-# HBM bytes of one grouped launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
-# the same counters of a 256 MiB device copy (profiles/gemv_mma4i_b4_g128_C2_layer_set.txt)
-MEASURED_TRAFFIC_BYTES = {"C2": 110.08e6}
+# HBM bytes of one grouped launch as rocprofv3 counted them (FETCH_SIZE + WRITE_SIZE, scaled by the
+# same counters of a 256 MiB device copy): kept in a tracked file with the kernel they were
+# measured on, and reported only while that kernel is still the one that runs
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 ROTATE_BYTES = 1.3e9           # distinct packed bytes touched between two uses of one copy
+TOL_FP32 = 1e-4                # bound on max |y - y*| / (|What[n,:]| |x|) of the GEMV
+
+
+def measured_traffic(name, kernel):
+    """(bytes, source) of the profiled HBM traffic of workload `name`, or (None, reason)."""
+    try:
+        with open(TRAFFIC_FILE) as fh:
+            rec = json.load(fh).get(name)
+    except (OSError, ValueError):
+        return None, "no profiles/hbm_traffic.json"
+    if not rec:
+        return None, f"no counter run recorded for {name}"
+    if rec["kernel"] != kernel:
+        return None, f"counters were taken on {rec['kernel']}, this run used {kernel}"
+    return rec["bytes"], f"{rec['source']} ({rec['date']}; rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, carried over)"
 
 
 def algorithmic_bytes(cfg) -> int:
@@ -61,28 +81,36 @@ def prepare_set(cfg, qg):
     return problems
 
 
-def cpu_baseline(cfg, problems, passes=5):
-    """The oracle's packed-format matvec over the whole layer set on the host cores."""
+def cpu_baseline(cfg, problems, timed_y, passes=5):
+    """The oracle's packed-format matvec over the whole layer set on the host cores, timed; its
+    result also checks the y of the last timed GPU launch (`timed_y`, host arrays).  Returns
+    (cpu_baseline record, max scaled error)."""
     from oracle import oracle
     packed = []
     for p in problems:
         q, s, z, x = p["host"]
         packed.append((oracle.pack_codes(q, cfg.bits), oracle.transpose_scales(s),
                        oracle.pack_zeros(z, cfg.bits), p["K"], x))
+    results = []
     def one_pass():
         t0 = time.perf_counter()
-        for P, St, Zp, K, x in packed:
-            oracle.matvec_packed(P, St, Zp, K, cfg.bits, cfg.group, x)
+        results[:] = [oracle.matvec_packed(P, St, Zp, K, cfg.bits, cfg.group, x) for P, St, Zp, K, x in packed]
         return time.perf_counter() - t0
-    cores = oracle.threads()
+    cores = len(os.sched_getaffinity(0))       # the host cores this process may use
+    oracle.set_threads(cores)
     times = [one_pass() for _ in range(passes)]
     oracle.set_threads(1)
     single = [one_pass() for _ in range(2)]
     oracle.set_threads(cores)
+    worst = 0.0
+    for p, y_ref, y in zip(problems, results, timed_y):
+        q, s, z, x = p["host"]
+        den = oracle.row_norms(q, s, z, cfg.group) * np.linalg.norm(x.astype(np.float64))
+        worst = max(worst, float(np.max(np.abs(y.astype(np.float64) - y_ref) / np.where(den == 0, 1.0, den))))
     return {"value": round(float(np.median(times)) * 1e6, 1), "unit": "us per layer set",
             "cores": cores, "kind": "oracle",
             "sample": f"full {cfg.name} layer set from the canonical packed format, median of {passes} passes",
-            "single_thread_us": round(float(min(single)) * 1e6, 1)}
+            "single_thread_us": round(float(min(single)) * 1e6, 1)}, worst
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X public dense bf16 peak
@@ -93,7 +121,7 @@ def bench_gemm(cfg, qg, args):
     copies rotated like the GEMV's.  A step is one pass over the nine problems."""
     from paper_2307_03738_amd import synth
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    stream_steps, warm = max(1, args.steps // 10), max(1, args.warmup // 10)
+    stream_steps, warm = max(20, args.steps // 10), max(5, args.warmup // 10)
     rows, total_us = [], 0.0
     for idx, (N, K) in enumerate(cfg.shapes):
         W, acts = synth.matrix(cfg, idx)
@@ -249,13 +277,77 @@ def bench_offline(qg, args):
             "rows": rows}
 
 
+def gpu_drawn_launches(qg, name):
+    """Rotated grouped launches of configuration `name` with Gaussian weights drawn on the GPU
+    (timing only: the kernels have no data-dependent control flow)."""
+    from paper_2307_03738_amd import synth
+    cfg = synth.CONFIGS[name]
+    gen = torch.Generator(device="cuda").manual_seed(100 + cfg.seed)
+    packed = {}
+    for n, k in set(cfg.shapes):
+        W = torch.randn((n, k), device="cuda", generator=gen) * cfg.std
+        q, s, z = qg.qg_quantize(W, cfg.bits, cfg.group)
+        packed[(n, k)] = qg.qg_pack(q, s, z, cfg.bits, cfg.group)
+        del W, q, s, z
+    xs = {k: torch.randn((k,), device="cuda", generator=gen) for k in {k for _, k in cfg.shapes}}
+    set_bytes = sum(packed[s_].numel() for s_ in cfg.shapes)
+    copies = max(2, int(np.ceil(ROTATE_BYTES / set_bytes)))
+    launches = []
+    for c in range(copies):
+        probs = [dict(packed=(packed[(n, k)] if c == 0 else packed[(n, k)].clone()), N=n, K=k, bits=cfg.bits,
+                      group=cfg.group, x=xs[k], y=torch.empty(n, dtype=torch.float32, device="cuda"))
+                 for n, k in cfg.shapes]
+        launches.append(qg.GroupedGemv(probs))
+    torch.cuda.synchronize()
+    return cfg, launches
+
+
+def time_launches(launches, steps, warmup):
+    """Microseconds per launch over `steps` launches that rotate over the prepared copies."""
+    stream = torch.cuda.current_stream().cuda_stream
+    copies = len(launches)
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(warmup):
+        launches[i % copies].launch(stream)
+    torch.cuda.synchronize()
+    start.record()
+    for i in range(steps):
+        launches[i % copies].launch(stream)
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / steps * 1e3
+
+
+def other_workloads(qg, args):
+    """The other layer sets and the small-M GEMM problems, each timed like the headline one."""
+    from paper_2307_03738_amd import synth
+    out = {}
+    for name in ("C3", "C4"):
+        cfg, launches = gpu_drawn_launches(qg, name)
+        us = time_launches(launches, max(20, args.steps // 4), max(5, args.warmup // 4))
+        alg = algorithmic_bytes(cfg)
+        out[name] = {"workload": f"{name}: decoder layer set {list(cfg.shapes)}, {cfg.bits}-bit, group {cfg.group}, "
+                                 "batch 1, one grouped launch per set (timing only, weights drawn on the GPU)",
+                     "kernel": qg.qg_last_gemv_kernel(), "us": round(us, 3), "algorithmic_bytes_per_set": alg,
+                     "GBps": round(alg / us / 1e3, 1), "frac_of_hbm_peak": round(alg / us / 1e3 / HBM_PEAK_GBS, 4),
+                     "packed_copies_rotated": len(launches)}
+        del launches
+    gemm = bench_gemm(synth.CONFIGS["C5"], qg, args)
+    out["C5"] = {"workload": gemm["config"]["workload"], "us_all_problems": gemm["value"],
+                 "problems": gemm["problems"]}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=1000)
     ap.add_argument("--config", default="C2", choices=["C2", "C3", "C4", "C5"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="skip the oracle leg (and with it the check of the timed result)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="time the headline workload only")
     ap.add_argument("--autotune", action="store_true",
                     help="let qg_gemv_autotune pick the launch shape (timed over the rotated copies) before the run")
     ap.add_argument("--sweep-groups", type=lambda s: [int(v) for v in s.split(",")], default=[16, 32, 64, 128, 0],
@@ -315,6 +407,7 @@ def main():
     for i in range(args.warmup):
         launches[i % copies].launch(stream)
     torch.cuda.synchronize()
+    kernel_name = qg.qg_last_gemv_kernel()
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     start.record()
@@ -324,38 +417,33 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ms_per_step = start.elapsed_time(stop) / args.steps
+    # what the last timed launch left in y (all copies share the y vectors of `base`)
+    timed_y = [p["y"].cpu().numpy() for p in base]
     # the same timed loop four more times: spread of the measurement (the first one is `value`)
     repeats = [ms_per_step * 1e3]
     for _ in range(4):
-        start.record()
-        for i in range(args.steps):
-            launches[i % copies].launch(stream)
-        stop.record()
-        torch.cuda.synchronize()
-        repeats.append(start.elapsed_time(stop) / args.steps * 1e3)
+        repeats.append(time_launches(launches, args.steps, 0))
 
     # the same launches on a single copy: weights served largely by the last-level cache
-    for i in range(20):
-        launches[0].launch(stream)
-    torch.cuda.synchronize()
-    start.record()
-    for i in range(args.steps):
-        launches[0].launch(stream)
-    stop.record()
-    torch.cuda.synchronize()
-    warm_ms = start.elapsed_time(stop) / args.steps
+    warm_ms = time_launches(launches[:1], args.steps, 20) / 1e3
 
     alg = algorithmic_bytes(cfg)
     achieved = alg / (ms_per_step * 1e-3) / 1e9
+    traffic, traffic_source = measured_traffic(cfg.name, kernel_name)
     out = {
         "metric": "us per LLaMA-7B-shaped 4-bit g128 GEMV layer set (batch 1); % of HBM peak"
                   if args.config == "C2" else f"us per {cfg.name} GEMV layer set (batch 1); % of HBM peak",
         "value": round(ms_per_step * 1e3, 3), "unit": "us",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 6), "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None,
+        # what the multiply-adds run in: 4-bit codes as int8 against the int8 digits of x in 32-bit
+        # fixed point (per step) on the 4x4x4 matrix instruction, int32 sums, fp32 per group and beyond
+        "dtype": "i8 mfma (x as 32-bit fixed point), f32 accumulate" if "mma4i" in kernel_name else "f32",
+        "data": "synthetic",
         "config": {"workload": f"{cfg.name}: decoder layer set {list(cfg.shapes)}, {cfg.bits}-bit, "
                                f"group {cfg.group}, batch 1, one grouped launch per set",
+                   "kernel": kernel_name,
                    "packed_copies_rotated": copies, "packed_bytes_per_set": set_bytes,
                    "algorithmic_bytes_per_set": alg},
         "effective_weight_GBps": round(achieved, 1),
@@ -366,14 +454,25 @@ def main():
         "host_wall_ms_per_step": round(wall_ms / args.steps, 6),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name)},
+                     "traffic": traffic, "traffic_source": traffic_source},
     }
     if tuned is not None:
         out["autotuned"] = {"waves_per_block": tuned[0], "bytes_per_wave": tuned[1], "kernel": tuned[2],
                             "us_while_tuning": round(tuned[3], 3)}
+    failed = False
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, base)
+        out["cpu_baseline"], err = cpu_baseline(cfg, base, timed_y)
+        out["parity_max_scaled_err"] = float(f"{err:.3e}")
+        out["parity_bound"] = TOL_FP32
+        failed = not (err <= TOL_FP32)
+    del launches, base
+    if not args.no_other_workloads:
+        qg.qg_set_gemv_tuning(0, 0, 0)
+        out["other_workloads"] = other_workloads(qg, args)
     print(json.dumps(out))
+    if failed:
+        print(f"the timed launch's y is off by {err:.3e} of |What[n,:]| |x| (bound {TOL_FP32})", file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

@@ -62,6 +62,10 @@ int qg_cell(int bits);
 
 const char *qg_status_string(int status);
 
+/* Identifier of the sources and flags this library was built from (a hash the build step
+ * passes in); a loader compares it with the sources it sees to refuse a stale library. */
+const char *qg_build_id(void);
+
 /* Size in bytes of a packed blob (codes, scales and zero-points) in the given layout;
  * 0 if the shape is not accepted. */
 size_t qg_packed_bytes(int64_t N, int64_t K, int bits, int group, int layout);
@@ -112,6 +116,22 @@ int qg_unpack(const void *packed, int64_t N, int64_t K, int bits, int group, int
 int qg_gemv(const void *packed, int64_t N, int64_t K, int bits, int group,
             const float *x, float *y, void *workspace, size_t workspace_bytes, void *stream);
 
+/* qg_gemv for callers that cannot allocate device memory or carry a workspace around: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * product, same kernels and the same bits in y as qg_gemv; the meeting slots of the K-split
+ * live in a scratch array inside the library (QG_NOALLOC_SCRATCH_BYTES per GPU, held from the
+ * library's load until the process ends) instead of a caller's workspace.  The call allocates
+ * and frees nothing and enqueues two kernels on `stream`: a fill that puts the slots it may
+ * use into their empty state (the array keeps what the last call on that GPU left), then the
+ * product.  Problems whose slots do not fit (more than QG_NOALLOC_MAX_N outputs) are refused
+ * with QG_ERR_WORKSPACE before anything is enqueued.  All calls on one GPU share that GPU's
+ * array: two calls that overlap in time on one GPU (different streams, or two host threads)
+ * race and give undefined results; calls on one stream, or otherwise ordered, are safe. */
+#define QG_NOALLOC_SCRATCH_BYTES (8u << 20)
+#define QG_NOALLOC_MAX_N 63488            /* 992 tiles of 64 outputs x 8448 bytes of slots */
+int qg_gemv_noalloc(const void *packed, int64_t N, int64_t K, int bits, int group,
+                    const float *x, float *y, void *stream);
+
 /* Several independent products in ONE kernel launch (the seven linear layers of a decoder
  * block at batch 1 are each only microseconds of memory traffic).  `descs` is a HOST array
  * of `count` <= QG_MAX_GROUPED problems; they may differ in shape, bits and group (one
@@ -159,6 +179,10 @@ int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
  * whole cells up to one step, and, at 2 and 3 bits, groups of whole steps) on bf16; 4: with
  * the 4 x 4 x 4 instruction on int8 (4-bit groups of at least 16 weights). */
 int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel);
+/* Name of the kernel instance the last qg_gemv / qg_gemv_grouped / qg_gemv_swiglu launch of this
+ * process used (its last launch, if the call made several), e.g. "gemv_mma4i<4, 16>"; "" before
+ * the first launch.  HOST string owned by the library.  For benchmark reports. */
+const char *qg_last_gemv_kernel(void);
 /* Search for the fastest launch shape of one grouped launch by timing -- this machine's
  * counterpart of the paper's parameter search (Section 3, Algorithm 4).  `descs` holds `sets`
  * copies of the launch back to back (set i at descs + i * count; same shapes, normally

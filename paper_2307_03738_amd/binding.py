@@ -26,16 +26,27 @@ class _Desc(ctypes.Structure):
 
 
 def lib():
-    """Load libqg.so, building it first only if no built library is present."""
+    """Load libqg.so, building it first only if no built library is present; a library that
+    was built from other sources than the ones in csrc/ is refused (RuntimeError)."""
     global _LIB
     if _LIB is None:
-        path = os.environ.get("QG_LIBRARY", _build.OUT)     # override: a library built elsewhere
+        override = os.environ.get("QG_LIBRARY")             # a library built elsewhere: used as it is
+        path = override or _build.OUT
         if not os.path.exists(path):
             path = _build.build(force=True)
         L = ctypes.CDLL(path)
+        if not override:
+            # a library built from other sources than the ones beside it is not used silently
+            L.qg_build_id.restype = ctypes.c_char_p
+            built_from = L.qg_build_id().decode() if hasattr(L, "qg_build_id") else "none"
+            if built_from != _build.source_id():
+                raise RuntimeError(f"{path} is stale (built from {built_from}, sources are "
+                                   f"{_build.source_id()}): run `python -m paper_2307_03738_amd.build`")
         i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
         L.qg_cell.restype = i32
         L.qg_cell.argtypes = [i32]
+        L.qg_build_id.restype = ctypes.c_char_p
+        L.qg_build_id.argtypes = []
         L.qg_status_string.restype = ctypes.c_char_p
         L.qg_status_string.argtypes = [i32]
         L.qg_packed_bytes.restype = sz
@@ -52,6 +63,10 @@ def lib():
         L.qg_unpack.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
         L.qg_gemv.restype = i32
         L.qg_gemv.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, sz, vp]
+        L.qg_gemv_noalloc.restype = i32
+        L.qg_gemv_noalloc.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
+        L.qg_last_gemv_kernel.restype = ctypes.c_char_p
+        L.qg_last_gemv_kernel.argtypes = []
         L.qg_gemv_grouped.restype = i32
         L.qg_gemv_grouped.argtypes = [ctypes.POINTER(_Desc), i32, vp, sz, vp]
         L.qg_gemv_swiglu.restype = i32
@@ -160,6 +175,22 @@ def qg_gemv(packed: torch.Tensor, N: int, K: int, bits: int, group: int, x: torc
     _check(lib().qg_gemv(packed.data_ptr(), N, K, bits, group, x.data_ptr(), y.data_ptr(),
                          workspace.data_ptr(), workspace.numel(), _stream()), "qg_gemv")
     return y
+
+
+def qg_gemv_noalloc(packed: torch.Tensor, N: int, K: int, bits: int, group: int, x: torch.Tensor,
+                    y: torch.Tensor) -> torch.Tensor:
+    """qg_gemv with the library's own scratch array: no workspace argument, nothing allocated
+    by the call (y is the caller's)."""
+    _dev(packed, torch.uint8, "packed"); _dev(x, torch.float32, "x"); _dev(y, torch.float32, "y")
+    if x.numel() != K or y.numel() != N or packed.numel() < qg_packed_bytes(N, K, bits, group, QG_LAYOUT_DEVICE):
+        _check(2, "qg_gemv_noalloc")
+    _check(lib().qg_gemv_noalloc(packed.data_ptr(), N, K, bits, group, x.data_ptr(), y.data_ptr(), _stream()),
+           "qg_gemv_noalloc")
+    return y
+
+
+def qg_last_gemv_kernel() -> str:
+    return lib().qg_last_gemv_kernel().decode()
 
 
 class GroupedGemv:

@@ -111,6 +111,21 @@ static inline int qg_make_canonical(int64_t N, int64_t K, int bits, int group, Q
     return QG_OK;
 }
 
+// Compute units of the current device (launch planning: wavefronts per CU).  Asked once per
+// device; 256 (MI355X) if the runtime cannot say.
+static inline int qg_compute_units()
+{
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
 static inline bool qg_aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 // Launch check: hipGetLastError after a launch, mapped to the library's status.

@@ -763,7 +763,8 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     const int quantum = kw / gcd(kw, steps_per_group) * steps_per_group;
     const int quanta = (int)((L.steps + quantum - 1) / quantum);
     // about one workgroup per compute unit, each with at least one quantum of work
-    int splits = g_tune_splits ? g_tune_splits : (256 + blocks_x * zblocks - 1) / (blocks_x * zblocks);
+    const int cus = qg_compute_units();
+    int splits = g_tune_splits ? g_tune_splits : (cus + blocks_x * zblocks - 1) / (blocks_x * zblocks);
     if (splits > MAX_SPLITS) splits = MAX_SPLITS;
     if (splits > quanta) splits = quanta;
     const int sps = (quanta + splits - 1) / splits * quantum;

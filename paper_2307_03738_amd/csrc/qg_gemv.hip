@@ -29,6 +29,9 @@
 // per output: gemv_mma4i (4 x 4 x 4 instruction on int8, x in fixed point; the built-in choice
 // wherever it applies), gemv_mma4 (the same instruction on bf16, x in three bf16 parts) and
 // gemv_mma (32 x 32 x 16 on bf16).  All share the work distribution and the reductions.
+#include <cstdio>
+#include <mutex>
+
 #include "qg_common.h"
 
 namespace {
@@ -69,6 +72,16 @@ __device__ inline void pin_problem(const GemvProblem &P)
 }
 
 #define QG_SLOT_EMPTY 0xffffffffu
+
+// The bit pattern of a partial result as it enters a meeting slot.  The "empty" marker is itself
+// a NaN pattern, and arithmetic passes a NaN operand's payload through, so an x holding exactly
+// that pattern could hand it to a sum; such a sum is entered as the default quiet NaN instead
+// (still a NaN, so it reaches y as one).
+__device__ inline uint32_t slot_bits(float v)
+{
+    const uint32_t b = __float_as_uint(v);
+    return b == QG_SLOT_EMPTY ? 0x7fc00000u : b;
+}
 
 struct GemvArgs {
     int count;
@@ -305,7 +318,7 @@ __device__ inline void emit_output(const GemvProblem &P, int tile, int lane, flo
     const int t = is_up ? tile - P.pair_tiles : tile;
     // the pair slots follow the tree slots of all tiles
     uint32_t *slot = P.slots + (size_t)P.tiles * QG_MAX_CHUNKS * QG_WAVE + (size_t)t * QG_WAVE + lane;
-    const uint32_t other = __hip_atomic_exchange(slot, __float_as_uint(v), __ATOMIC_RELAXED,
+    const uint32_t other = __hip_atomic_exchange(slot, slot_bits(v), __ATOMIC_RELAXED,
                                                  __HIP_MEMORY_SCOPE_AGENT);
     if (other == QG_SLOT_EMPTY) return;
     __hip_atomic_store(slot, QG_SLOT_EMPTY, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -317,7 +330,7 @@ __device__ inline void emit_output(const GemvProblem &P, int tile, int lane, flo
 // K-split epilogue.  The wavefronts of a team pass their 64 partial outputs through LDS
 // (wavefronts without work have already ended; a barrier only waits for wavefronts that are
 // still alive); the team's lead adds them in wavefront order and either stores y or enters
-// the tile's reduction tree.  An empty slot holds a NaN pattern no partial sum can have.
+// the tile's reduction tree.  An empty slot holds a NaN pattern no partial sum enters it with (slot_bits).
 __device__ inline void finish_tile(const GemvProblem &P, const WaveJob &j, float yacc,
                                    float (*red)[QG_WAVE])
 {
@@ -339,7 +352,7 @@ __device__ inline void finish_tile(const GemvProblem &P, const WaveJob &j, float
     float v = t;
     while (width > 1) {
         uint32_t *slot = slots + (size_t)(base + (node >> 1)) * QG_WAVE;
-        const uint32_t other = __hip_atomic_exchange(slot, __float_as_uint(v), __ATOMIC_RELAXED,
+        const uint32_t other = __hip_atomic_exchange(slot, slot_bits(v), __ATOMIC_RELAXED,
                                                      __HIP_MEMORY_SCOPE_AGENT);
         if (other == QG_SLOT_EMPTY) return;               // first of the pair: the partner carries on
         v += __uint_as_float(other);
@@ -1695,6 +1708,10 @@ int g_tune_kernel = 0;       // 0 = built-in choice, 1 = vector-ALU kernels, 2 =
 
 enum Kind { KIND_STATIC, KIND_RUNTIME, KIND_GENERIC };
 
+// What the last launch of this thread's process ran (for bench reports): kernel family and
+// template arguments.
+char g_last_kernel[64] = "";
+
 // The K-split of one problem: work items along K are steps for the two fast kernels and
 // groups for the generic one; a wavefront takes `spw` consecutive items.
 struct Plan {
@@ -1759,9 +1776,10 @@ FirstBlocks first_blocks(const GemvArgs &A)
 }
 
 template <int BITS>
-bool launch_static(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+bool launch_static(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A, bool dry)
 {
     if (!(cpg == 1 || cpg == 2 || cpg == 4 || cpg == 8 || (cpg == 16 && BITS != 3))) return false;
+    if (dry) return true;
     switch (cpg) {
     case 1: hipLaunchKernelGGL((gemv_static<BITS, 1>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
     case 2: hipLaunchKernelGGL((gemv_static<BITS, 2>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
@@ -1776,9 +1794,10 @@ bool launch_static(int cpg, unsigned blocks, unsigned threads, hipStream_t st, c
 }
 
 template <int BITS>
-bool launch_mma(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+bool launch_mma(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A, bool dry)
 {
     if (!(cpg == 2 || cpg == 4 || cpg == 8 || (cpg == 16 && BITS != 3))) return false;
+    if (dry) return true;
     // x of one step in three bf16 parts, two buffers, per wavefront
     const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 3 * codes_per_step<BITS>() * sizeof(uint16_t);
     switch (cpg) {
@@ -1795,9 +1814,10 @@ bool launch_mma(int cpg, unsigned blocks, unsigned threads, hipStream_t st, cons
 
 // gemv_mma4: cpg = cells per group, 0 for groups of whole steps
 template <int BITS>
-bool launch_mma4(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+bool launch_mma4(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A, bool dry)
 {
     if (!(cpg == 0 || cpg == 1 || cpg == 2 || cpg == 4 || cpg == 8 || (cpg == 16 && BITS != 3))) return false;
+    if (dry) return true;
     const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 4 * (codes_per_step<BITS>() + 8) * sizeof(uint16_t);
     const FirstBlocks f = first_blocks(A);
     switch (cpg) {
@@ -1815,9 +1835,10 @@ bool launch_mma4(int cpg, unsigned blocks, unsigned threads, hipStream_t st, con
 }
 
 template <int BITS>
-bool launch_mma4i(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
+bool launch_mma4i(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A, bool dry)
 {
     if (!(cpg == 0 || (cpg == 1 && BITS != 4) || cpg == 2 || cpg == 4 || cpg == 8 || (cpg == 16 && BITS != 3))) return false;
+    if (dry) return true;
     const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 4 * (codes_per_step<BITS>() + 16);
     const FirstBlocks f = first_blocks(A);
     switch (cpg) {
@@ -1869,9 +1890,11 @@ void launch_rows16(unsigned blocks, unsigned threads, hipStream_t st, const Gemv
 
 // rows > 0: the problems are products with `rows` <= 16 activation rows (x = X [rows][K],
 // y = Y [rows][N]) for gemm_rows16; the caller has checked that the kernel applies.
+// dry: plan and check only -- returns the status the launch would have up to the point where
+// the kernel is enqueued, and enqueues nothing.
 int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const size_t *ws_off,
                  char *workspace, hipStream_t st, const int64_t *gate_rows, float *const *gated,
-                 int rows = 0)
+                 int rows = 0, bool dry = false)
 {
     GemvArgs A;
     A.count = count;
@@ -1924,7 +1947,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     const bool few_long = rows == 0 && (bits_all == 4 ? code_bytes < QG_VALU4_FROM && (mul == MUL_MMA4 || mul == MUL_MMA4I || kind == KIND_RUNTIME)
                                                       : kind == KIND_RUNTIME);
     if (few_long) {
-        const size_t share = code_bytes / (256 * 10);
+        const size_t share = code_bytes / ((size_t)qg_compute_units() * 10);
         // (the vector-ALU kernel keeps its wider teams while a wavefront has a single step)
         if (g_tune_wpb == 0 && (mma || share > 4096)) cap = 4;
         if (target == 0) {
@@ -1936,7 +1959,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         }
     }
     if (target == 0) {
-        target = code_bytes / (256 * 24);                        // about 24 wavefronts per CU
+        target = code_bytes / ((size_t)qg_compute_units() * 24);    // about 24 wavefronts per CU
         if (target < 4096) target = 4096;
         if (target > 16384) target = 16384;
     }
@@ -2039,7 +2062,17 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
 
     const unsigned threads = (unsigned)wpb * QG_WAVE;
     const int bits = L[0].bits;
+    if (!dry) {
+        const int cpg = L[0].group / L[0].cell;
+        const char *family = rows > 0 ? "gemm_rows16" : kind == KIND_GENERIC ? "gemv_generic"
+                           : mul == MUL_MMA4I ? "gemv_mma4i" : mul == MUL_MMA4 ? "gemv_mma4"
+                           : mul == MUL_MMA32 ? "gemv_mma" : kind == KIND_STATIC ? "gemv_static" : "gemv_runtime";
+        if (kind == KIND_STATIC || rows > 0) snprintf(g_last_kernel, sizeof g_last_kernel, "%s<%d, %d>", family, bits, cpg);
+        else if (kind == KIND_RUNTIME && mul != MUL_VALU) snprintf(g_last_kernel, sizeof g_last_kernel, "%s<%d, 0>", family, bits);
+        else snprintf(g_last_kernel, sizeof g_last_kernel, "%s<%d>", family, bits);
+    }
     if (rows > 0) {
+        if (dry) return QG_OK;
         switch (L[0].group / L[0].cell) {
         case 2: launch_rows16<2>(blocks, threads, st, A); break;
         case 4: launch_rows16<4>(blocks, threads, st, A); break;
@@ -2050,25 +2083,28 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
         const int cpg = L[0].group / L[0].cell;
         bool launched;
         if (mul == MUL_MMA4I)
-            launched = bits == 4 ? launch_mma4i<4>(cpg, blocks, threads, st, A)
-                     : bits == 2 ? launch_mma4i<2>(cpg, blocks, threads, st, A) : launch_mma4i<3>(cpg, blocks, threads, st, A);
+            launched = bits == 4 ? launch_mma4i<4>(cpg, blocks, threads, st, A, dry)
+                     : bits == 2 ? launch_mma4i<2>(cpg, blocks, threads, st, A, dry) : launch_mma4i<3>(cpg, blocks, threads, st, A, dry);
         else if (mul == MUL_MMA4)
-            launched = bits == 4 ? launch_mma4<4>(cpg, blocks, threads, st, A)
-                     : bits == 2 ? launch_mma4<2>(cpg, blocks, threads, st, A) : launch_mma4<3>(cpg, blocks, threads, st, A);
+            launched = bits == 4 ? launch_mma4<4>(cpg, blocks, threads, st, A, dry)
+                     : bits == 2 ? launch_mma4<2>(cpg, blocks, threads, st, A, dry) : launch_mma4<3>(cpg, blocks, threads, st, A, dry);
         else if (mul == MUL_MMA32)
-            launched = bits == 4 ? launch_mma<4>(cpg, blocks, threads, st, A)
-                     : bits == 2 ? launch_mma<2>(cpg, blocks, threads, st, A) : launch_mma<3>(cpg, blocks, threads, st, A);
+            launched = bits == 4 ? launch_mma<4>(cpg, blocks, threads, st, A, dry)
+                     : bits == 2 ? launch_mma<2>(cpg, blocks, threads, st, A, dry) : launch_mma<3>(cpg, blocks, threads, st, A, dry);
         else
-            launched = bits == 4 ? launch_static<4>(cpg, blocks, threads, st, A)
-                     : bits == 2 ? launch_static<2>(cpg, blocks, threads, st, A) : launch_static<3>(cpg, blocks, threads, st, A);
+            launched = bits == 4 ? launch_static<4>(cpg, blocks, threads, st, A, dry)
+                     : bits == 2 ? launch_static<2>(cpg, blocks, threads, st, A, dry) : launch_static<3>(cpg, blocks, threads, st, A, dry);
         if (!launched) return QG_ERR_UNSUPPORTED;      // no kernel was built for this group size
+        if (dry) return QG_OK;
+    } else if (dry) {
+        return QG_OK;
     } else if (kind == KIND_RUNTIME && mul == MUL_MMA4I) {
-        if (bits == 2) launch_mma4i<2>(0, blocks, threads, st, A);
-        else if (bits == 3) launch_mma4i<3>(0, blocks, threads, st, A);
-        else launch_mma4i<4>(0, blocks, threads, st, A);
+        if (bits == 2) launch_mma4i<2>(0, blocks, threads, st, A, false);
+        else if (bits == 3) launch_mma4i<3>(0, blocks, threads, st, A, false);
+        else launch_mma4i<4>(0, blocks, threads, st, A, false);
     } else if (kind == KIND_RUNTIME && mul == MUL_MMA4) {
-        if (bits == 2) launch_mma4<2>(0, blocks, threads, st, A);
-        else launch_mma4<3>(0, blocks, threads, st, A);
+        if (bits == 2) launch_mma4<2>(0, blocks, threads, st, A, false);
+        else launch_mma4<3>(0, blocks, threads, st, A, false);
     } else if (kind == KIND_RUNTIME) {
         if (bits == 4) hipLaunchKernelGGL(gemv_runtime<4>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
         else if (bits == 2) hipLaunchKernelGGL(gemv_runtime<2>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
@@ -2082,6 +2118,8 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
 }
 
 }  // namespace
+
+extern "C" const char *qg_last_gemv_kernel(void) { return g_last_kernel; }
 
 extern "C" int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel)
 {
@@ -2115,8 +2153,9 @@ extern "C" int qg_workspace_init(void *workspace, size_t bytes, void *stream)
 
 // gate_rows / gated: per problem, the number of gate outputs and the result vector of a gated
 // pair (0 / unused for a plain product); both NULL for plain launches.
+// check_only: argument checks and planning, nothing enqueued.
 static int gemv_grouped(const qg_gemv_desc *descs, int count, void *workspace, size_t workspace_bytes,
-                        void *stream, const int64_t *gate_rows, float *const *gated)
+                        void *stream, const int64_t *gate_rows, float *const *gated, bool check_only = false)
 {
     if (!descs) return QG_ERR_NULL;
     if (count <= 0) return QG_ERR_SHAPE;
@@ -2139,31 +2178,34 @@ static int gemv_grouped(const qg_gemv_desc *descs, int count, void *workspace, s
     if (!qg_aligned16(workspace)) return QG_ERR_ALIGN;
 
     // one launch per distinct (bits, kernel kind), and per group size where the kernel has it
-    // as a compile-time constant
-    bool done[QG_MAX_GROUPED] = {false};
-    for (int i = 0; i < count; ++i) {
-        if (done[i]) continue;
-        QgLayout Li;
-        qg_make_layout(descs[i].N, descs[i].K, descs[i].bits, descs[i].group, &Li);
-        int idx[QG_MAX_GROUPED], n = 0;
-        for (int j = i; j < count; ++j) {
-            if (done[j]) continue;
-            QgLayout Lj;
-            qg_make_layout(descs[j].N, descs[j].K, descs[j].bits, descs[j].group, &Lj);
-            const Kind ki = make_plan(Li).kind;
-            if (Lj.bits == Li.bits && make_plan(Lj).kind == ki && (ki != KIND_STATIC || Lj.group == Li.group)) {
-                idx[n++] = j;
-                done[j] = true;
+    // as a compile-time constant.  Two passes: the first plans every class and launches
+    // nothing, so that an error leaves nothing enqueued; the second launches.
+    for (int pass = 0; pass < (check_only ? 1 : 2); ++pass) {
+        bool done[QG_MAX_GROUPED] = {false};
+        for (int i = 0; i < count; ++i) {
+            if (done[i]) continue;
+            QgLayout Li;
+            qg_make_layout(descs[i].N, descs[i].K, descs[i].bits, descs[i].group, &Li);
+            int idx[QG_MAX_GROUPED], n = 0;
+            for (int j = i; j < count; ++j) {
+                if (done[j]) continue;
+                QgLayout Lj;
+                qg_make_layout(descs[j].N, descs[j].K, descs[j].bits, descs[j].group, &Lj);
+                const Kind ki = make_plan(Li).kind;
+                if (Lj.bits == Li.bits && make_plan(Lj).kind == ki && (ki != KIND_STATIC || Lj.group == Li.group)) {
+                    idx[n++] = j;
+                    done[j] = true;
+                }
             }
+            // longest K first: its wavefronts run longest, so they should start first
+            for (int a = 1; a < n; ++a)
+                for (int b = a; b > 0 && descs[idx[b]].K > descs[idx[b - 1]].K; --b) {
+                    const int t = idx[b]; idx[b] = idx[b - 1]; idx[b - 1] = t;
+                }
+            const int rc = launch_class(descs, idx, n, ws_off, (char *)workspace, (hipStream_t)stream,
+                                        gate_rows, gated, 0, pass == 0);
+            if (rc != QG_OK) return rc;
         }
-        // longest K first: its wavefronts run longest, so they should start first
-        for (int a = 1; a < n; ++a)
-            for (int b = a; b > 0 && descs[idx[b]].K > descs[idx[b - 1]].K; --b) {
-                const int t = idx[b]; idx[b] = idx[b - 1]; idx[b - 1] = t;
-            }
-        const int rc = launch_class(descs, idx, n, ws_off, (char *)workspace, (hipStream_t)stream,
-                                    gate_rows, gated);
-        if (rc != QG_OK) return rc;
     }
     return QG_OK;
 }
@@ -2215,6 +2257,67 @@ extern "C" int qg_gemv_swiglu(const void *packed, int64_t I, int64_t K, int bits
     const int64_t gate_rows = I;
     float *const gated = h;
     return gemv_grouped(&d, 1, workspace, workspace_bytes, stream, &gate_rows, &gated);
+}
+
+// ---- qg_gemv for callers that cannot allocate -------------------------------------------
+// The meeting slots of the K-split live in a file-scope device array instead of a caller's
+// workspace.  Each GPU holds its own copy of the array at its own address: the address is
+// asked from the runtime once per device, with that device current, and only that pointer is
+// ever handed to kernels (the array's name is a host-side stand-in, not a device address).
+static __device__ __align__(256) uint32_t scratch[QG_NOALLOC_SCRATCH_BYTES / sizeof(uint32_t)];
+
+namespace {
+std::mutex g_scratch_lock;
+uint32_t *g_scratch_ptr[64];          // per device; nullptr until asked
+
+// Device address of `scratch` on the current device, or nullptr with *status set.
+uint32_t *scratch_of_current_device(int *status)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { *status = QG_ERR_DEVICE; return nullptr; }
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        uint32_t *ptr = nullptr;
+        if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            *status = QG_ERR_DEVICE;
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" int qg_gemv_noalloc(const void *packed, int64_t N, int64_t K, int bits, int group,
+                               const float *x, float *y, void *stream)
+{
+    QgLayout L;
+    const int rc = qg_make_layout(N, K, bits, group, &L);
+    if (rc != QG_OK) return rc;
+    const size_t need = workspace_for(L);
+    if (need > QG_NOALLOC_SCRATCH_BYTES) return QG_ERR_WORKSPACE;      // more outputs than the scratch has slots for
+    qg_gemv_desc d;
+    d.packed = packed;
+    d.N = N;
+    d.K = K;
+    d.bits = bits;
+    d.group = group;
+    d.x = x;
+    d.y = y;
+    int status = QG_OK;
+    uint32_t *ptr = scratch_of_current_device(&status);
+    if (!ptr) return status;
+    // argument checks and planning first, so that an error leaves nothing enqueued
+    const int checked = gemv_grouped(&d, 1, ptr, need, stream, nullptr, nullptr, true);
+    if (checked != QG_OK) return checked;
+    // The array keeps whatever the last call on this GPU left: the slots this call may use are
+    // put into the "empty" state by a fill kernel (not a memset node, so a caller may capture it).
+    const size_t words = need / sizeof(uint32_t);
+    hipLaunchKernelGGL(fill_u32, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       ptr, words, QG_SLOT_EMPTY);
+    if (qg_launch_status() != QG_OK) return QG_ERR_DEVICE;
+    return gemv_grouped(&d, 1, ptr, need, stream, nullptr, nullptr);
 }
 
 extern "C" int qg_gemv(const void *packed, int64_t N, int64_t K, int bits, int group,

@@ -519,6 +519,11 @@ int convert(bool pack, const void *q, const void *s, const void *z, int64_t N, i
 
 extern "C" int qg_cell(int bits) { return qg_cell_of(bits); }
 
+#ifndef QG_BUILD_ID
+#define QG_BUILD_ID "unknown"
+#endif
+extern "C" const char *qg_build_id(void) { return QG_BUILD_ID; }
+
 extern "C" const char *qg_status_string(int status)
 {
     switch (status) {

@@ -207,7 +207,7 @@ GEMV_CASES = [  # N, K, bits, group   -- (kernel flavour)
 ]
 
 
-@pytest.mark.parametrize("kernel", [1, 2])       # multiply-adds on the vector ALU / on the matrix cores
+@pytest.mark.parametrize("kernel", [0, 1, 2])    # the built-in choice / the vector ALU / the 32 x 32 x 16 matrix instruction
 @pytest.mark.parametrize("N,K,bits,group", GEMV_CASES)
 def test_gemv_matches_oracle(qg, oracle, N, K, bits, group, kernel):
     _announce("gemv", N, K, bits, group, kernel)
@@ -285,6 +285,61 @@ def test_gemv_non_finite_activations_reach_the_output(qg, bits, group, kernel):
             assert not np.isfinite(y).any(), (bad, int(np.isfinite(y).sum()))
     finally:
         qg.qg_set_gemv_tuning(0, 0, 0)
+
+
+@pytest.mark.parametrize("kernel", [0, 1, 3])
+@pytest.mark.parametrize("bits,group", [(4, 128), (2, 32), (3, 1024)])
+def test_gemv_nan_with_the_empty_slot_pattern(qg, bits, group, kernel):
+    # The meeting slots of the K-split mark "empty" with the bit pattern 0xffffffff, itself a NaN.
+    # An x element with exactly that pattern travels through the sums as a payload; the partial
+    # result must still be taken for a value (and y written, as NaN), not for an empty slot.
+    _announce("gemv NaN = slot marker", bits, group, kernel)
+    N, K = 130, 4096
+    W, x = synth.small_case(11 + bits, N, K, 0.02, False)
+    q, s, z = qg.qg_quantize(dev(W), bits, group)
+    blob = qg.qg_pack(q, s, z, bits, group, qg.QG_LAYOUT_DEVICE)
+    xb = x.copy()
+    xb.view(np.uint32)[1234] = 0xFFFFFFFF
+    for tuning in ((2, 4096, kernel), (1, 8192, kernel), (0, 0, kernel)):      # K cut over 2 ... 16 workgroups, and the built-in shape
+        qg.qg_set_gemv_tuning(*tuning)
+        try:
+            ws = qg.new_workspace(qg.qg_workspace_bytes(N, K, bits, group, 1))
+            y = torch.full((N,), 7.0, dtype=torch.float32, device="cuda")
+            qg.qg_gemv(blob, N, K, bits, group, dev(xb), y, ws)
+            y_clean = qg.qg_gemv(blob, N, K, bits, group, dev(x), None, ws)    # the workspace is still usable
+            torch.cuda.synchronize()
+        finally:
+            qg.qg_set_gemv_tuning(0, 0, 0)
+        assert np.isnan(host(y)).all(), (tuning, int((host(y) == 7.0).sum()))
+        assert np.all(host(ws) == 0xFF), "workspace not left in its prepared state"
+        assert np.isfinite(host(y_clean)).all()
+
+
+@pytest.mark.parametrize("H,K,bits,group", [(320, 1024, 4, 128), (4096, 4096, 4, 128), (192, 1536, 3, 64)])
+def test_gemv_stacked_projections_equal_separate_ones(qg, oracle, H, K, bits, group):
+    # q, k and v of a block as ONE 3H x K product (one launch, one x): quantization is per output
+    # and group, so the stacked matrix packs the same codes, and its y is the three y one after
+    # the other -- against the oracle, and against the three products as problems of a grouped launch
+    _announce("gemv stacked q/k/v", H, K, bits, group)
+    Ws = [synth.small_case(600 + i, H, K, 0.02, True)[0] for i in range(3)]
+    _, x = synth.small_case(650, H, K, 0.02, False)
+    W3 = np.concatenate(Ws, axis=0)
+    q0, s0, z0 = oracle.quantize(W3, bits, group)
+    y_ref = oracle.matvec(q0, s0, z0, group, x)
+    norms = oracle.row_norms(q0, s0, z0, group)
+    q, s, z = qg.qg_quantize(dev(W3), bits, group)
+    assert np.array_equal(host(q), q0)
+    y3 = host(qg.qg_gemv(qg.qg_pack(q, s, z, bits, group), 3 * H, K, bits, group, dev(x)))
+    assert scaled_error(y3, y_ref, norms, x) <= TOL_FP32
+    problems = []
+    for i in range(3):
+        qi, si, zi = qg.qg_quantize(dev(Ws[i]), bits, group)
+        assert np.array_equal(host(qi), q0[i * H:(i + 1) * H])                 # same codes as in the stack
+        problems.append(dict(packed=qg.qg_pack(qi, si, zi, bits, group), N=H, K=K, bits=bits, group=group,
+                             x=dev(x), y=torch.empty(H, dtype=torch.float32, device="cuda")))
+    ys = np.concatenate([host(y) for y in qg.qg_gemv_grouped(problems)])
+    assert scaled_error(ys, y_ref, norms, x) <= TOL_FP32
+    assert scaled_error(ys, y3.astype(np.float64), norms, x) <= 2e-6           # two fp32 summation orders apart at most
 
 
 @pytest.mark.parametrize("tuning", [(1, 4096, 1), (2, 4096, 1), (4, 8192, 1), (8, 4096, 1), (16, 4096, 1), (4, 65536, 1),
@@ -520,6 +575,18 @@ def test_gemv_random_shapes_and_launch_shapes(qg, oracle, seed):
 TOL_BF16 = 1e-2
 
 
+def gemm_model_bound(K):
+    """What the rounding of both operands to bf16 may cost, as a multiple of |What[n,:]| |X[m,:]|.
+    Round-to-nearest to 8 significant bits errs by at most 2^-8 relative, 0.42 * 2^-8 rms for a
+    log-uniform significand; two rounded operands per product: 2.3e-3 rms per term; the terms'
+    errors are independent, so the sum errs by 2.3e-3 * sqrt(sum (x w)^2) = 2.3e-3 / sqrt(K) of
+    |w| |x| for activations that are independent of the weights; the largest of up to a million
+    outputs lies near 5 sigma: 1.2e-2 / sqrt(K) = 6.1 * 2^-9 / sqrt(K).  The bound is that with a
+    margin of 2.6: c = 16.  (A kernel that keeps the codes exact and rounds only X stays a factor
+    sqrt(2) further inside.)  fp32 accumulation adds sqrt(K) * 2^-24, far below."""
+    return 16.0 * 2.0 ** -9 / np.sqrt(K)
+
+
 def _gemm_case(qg, oracle, W, X, bits, group):
     N, K = W.shape
     M = X.shape[0]
@@ -536,7 +603,10 @@ def _gemm_case(qg, oracle, W, X, bits, group):
     Yh = host(Y)
     assert np.all(Yh[M * N:] == 7.0), "write past the end of Y"
     assert np.array_equal(Yh[:M * N].reshape(M, N), host(Y2)), "not deterministic"
-    return scaled_error(Yh[:M * N].reshape(M, N), Y_ref, norms, X)
+    err = scaled_error(Yh[:M * N].reshape(M, N), Y_ref, norms, X)
+    # next to the caller's 1e-2: the level the rounding model allows at this K (Gaussian X)
+    assert err <= gemm_model_bound(K), (err, gemm_model_bound(K))
+    return err
 
 
 GEMM_CASES = [  # N, K, bits, group, M
@@ -587,6 +657,42 @@ def test_gemm_small_up_to_16_rows(qg, oracle, N, K, group, M, tuning):
         qg.qg_set_gemv_tuning(0, 0, 0)
         qg.qg_set_gemm_tuning(0, 0)
     assert err <= TOL_BF16, err
+
+
+@pytest.mark.parametrize("bits,group,cell", [(4, 128, 8), (4, 32, 8), (3, 64, 32), (2, 32, 16)])
+@pytest.mark.parametrize("M", [1, 16, 40, 128])
+def test_gemm_small_single_cell_difference(qg, oracle, bits, group, cell, M):
+    # Two outputs whose codes agree everywhere except in ONE cell (the smallest granule the kernels
+    # decode): the difference of their results is that cell's contribution alone, far below the
+    # 1e-2 bound on either result.  A cell that is dropped, doubled or paired with the wrong x
+    # shows up here at full size.  Cells at the start, inside and at the end of K, in the first
+    # and in a later tile.
+    _announce("gemm single cell", bits, group, M)
+    N, K = 200, 2048
+    rng = np.random.default_rng(77 + bits + M)
+    base = rng.integers(0, 1 << bits, K, dtype=np.uint8)
+    q = np.tile(base, (N, 1))
+    s = np.full((N, K // group), 0.03125, np.float32)
+    z = np.full((N, K // group), (1 << bits) // 2, np.uint8)
+    spots = [(1, 0), (5, K // cell - 1), (70, 3), (131, K // cell // 2 + 1), (199, K // cell - 2)]   # (output, cell)
+    for n, c in spots:
+        q[n, c * cell:(c + 1) * cell] = ((1 << bits) - 1) - q[n, c * cell:(c + 1) * cell]
+    X = rng.standard_normal((max(M, 2), K)).astype(np.float32)[:M]
+    blob = qg.qg_pack(dev(q), dev(s), dev(z), bits, group)
+    Y = host(qg.qg_gemm_small(blob, N, K, bits, group, dev(X))).astype(np.float64)
+    Y_ref = oracle.matmul_small(q, s, z, group, X)
+    assert scaled_error(Y, Y_ref, oracle.row_norms(q, s, z, group), X) <= gemm_model_bound(K)
+    xn = np.linalg.norm(X.astype(np.float64), axis=1)
+    wn = float(oracle.row_norms(q, s, z, group)[0])
+    for n, c in spots:
+        d = Y[:, n] - Y[:, 0]                       # output 0 carries the unchanged codes
+        d_ref = Y_ref[:, n] - Y_ref[:, 0]
+        dq = q[n, c * cell:(c + 1) * cell].astype(np.float64) - base[c * cell:(c + 1) * cell]
+        size = 0.03125 * np.linalg.norm(dq) * np.linalg.norm(X[:, c * cell:(c + 1) * cell].astype(np.float64), axis=1)
+        # the cell's own terms rounded to bf16 (2^-8 each, two operands) plus fp32 accumulation of two long sums
+        slack = 2.0 ** -7 * size + 8 * np.sqrt(K) * 2.0 ** -24 * wn * xn
+        assert np.all(np.abs(d - d_ref) <= slack), (n, c, float(np.max(np.abs(d - d_ref) / slack)))
+        assert np.all(np.abs(d_ref) > 0)
 
 
 def test_gemm_small_longest_k_of_the_matrix_core_path(qg, oracle):
