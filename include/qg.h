@@ -163,9 +163,22 @@ int qg_gemv_swiglu(const void *packed, int64_t I, int64_t K, int bits, int group
 
 /* Prompt-phase form for M <= 128 tokens:
  *   Y[m][n] = sum_k X[m][k] * s[n][k/G] * (q[n][k] - z[n][k/G])
- * with X and the dequantized weights rounded to bf16 and accumulated in fp32 on the matrix
- * cores.  X [M][K] fp32 row-major;  Y [M][N] fp32 row-major (overwritten).
- * workspace: qg_workspace_bytes(N, K, bits, group, M) bytes. */
+ * on the matrix cores (bf16 operands, fp32 accumulation), one of two ways by layout:
+ *   - 4-bit codes, G a multiple of 32 that divides or is a multiple of 128, K % 128 == 0: the
+ *     weights are dequantized to bf16(s (q - z)) on their way into the matrix instruction, X is
+ *     rounded to bf16;
+ *   - any width, G a whole number of pairs of cells up to one step (4 bits: 16 ... 128; 2 bits:
+ *     32 ... 256; 3 bits: 64 ... 256) or a multiple of a step, K % 16 == 0: the codes enter the
+ *     matrix instruction as exact bf16 integers, X is rounded to bf16, and scale and zero-point
+ *     are applied in fp32 once per group and element of Y (eq. (2)); X is converted by a
+ *     kernel of its own first, so a call enqueues two or three kernels.
+ * Every other layout (odd numbers of cells per group, K % 16 != 0 only with M == 1) runs
+ * qg_gemv once per row in fp32, 16 rows per launch; with K % 16 != 0 and M > 1 the call returns
+ * QG_ERR_UNSUPPORTED.  M == 1 is qg_gemv.
+ *   X [M][K] fp32 row-major, 64-byte aligned;  Y [M][N] fp32 row-major (overwritten).
+ * workspace: qg_workspace_bytes(N, K, bits, group, M) bytes (converted activations and partial
+ * results of a K split; for the row-by-row form, qg_gemv's meeting slots, to be prepared with
+ * qg_workspace_init). */
 int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
                   const float *X, int M, float *Y,
                   void *workspace, size_t workspace_bytes, void *stream);
@@ -200,7 +213,8 @@ int qg_gemv_autotune(const qg_gemv_desc *descs /* HOST */, int count, int sets,
  * workgroups (clamped to what the shape allows); shape in 1..12 = workgroup shape (how many
  * rows, tiles and K slices the wavefronts of a workgroup cover, and which of the two kernels;
  * ignored if it does not fit M),
- * shape = -1: the kernel for up to 16 rows whatever the number of tiles.
+ * shape = -1: the kernel for up to 16 rows whatever the number of tiles; shape = 13: the
+ * raw-code kernel wherever it takes the layout.
  * 0 restores the built-in choice. */
 int qg_set_gemm_tuning(int splits, int shape);
 

@@ -32,10 +32,12 @@
 #include <type_traits>
 
 #include "qg_common.h"
+#include "qg_mma.h"
 
 size_t qg_gemm_workspace_bytes(const QgLayout &L, int M);
 int qg_gemm_rows16(const void *packed, int64_t N, int64_t K, int bits, int group, const float *X,
                    int M, float *Y, void *workspace, void *stream);   // qg_gemv.hip
+int qg_gemv_grouped_check(const qg_gemv_desc *descs, int count, void *workspace, size_t workspace_bytes);
 
 namespace {
 
@@ -602,6 +604,506 @@ __global__ __launch_bounds__(TN * 64, MB == 2 ? 2 : 1) void gemm_wide_b4(const G
         }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// gemm_codes: the same product with the weights entering the matrix instruction as RAW CODES.
+//
+// Nothing is dequantized per weight.  A code q becomes the exact bf16 integer 128 + q with a mask
+// and an OR (mma_unpack, as in the matrix-core GEMV), the matrix instruction accumulates
+//     T[m][n] = sum_{k in group} xb[m][k] (128 + q[n][k]),      xb = X rounded to bf16,
+// in fp32 (the products are exact), and scale and zero-point are applied once per group and
+// accumulator element, which is eq. (2) per element of Y:
+//     Y[m][n] += s[n][g] * ( T[m][n] - (128 + z[n][g]) * xhat[m][g] ),   xhat[m][g] = sum_k xb[m][k].
+// The subtraction rides on the matrix cores as well: xhat, cut into three bf16 parts (exact), is one
+// more A operand per group and -(128 + z) one more B operand, so a group costs one fused
+// multiply-add per accumulator element and nothing else on the vector ALU.
+// (3 bits: the high field of a byte stays where it is, so half of the codes enter as 128 + 8 q
+// against activations stored divided by 8; those have an xhat of their own and the offset 16.)
+//
+// Two kernels.  prepare_x converts X once per call: bf16 in the order the unpacked codes have
+// inside an operand, rows padded with zeros to whole blocks of 32, K to whole steps, plus the
+// xhat operands -- so that the product kernel moves activations into LDS with plain copies and
+// spends its vector instructions on the weights alone.  gemm_codes: a wavefront owns a tile of
+// 64 outputs (device layout, lane = output); one v_permlane32_swap per pair of code words turns
+// "lane = output" into the operand layout (lanes l and l + 32 hold two neighbouring cells of the
+// same output).  A workgroup is 8 wavefronts = TN tiles x KW k-slices that share the activation
+// chunk of an iteration (KW steps) in LDS, double buffered; the k-slices add their results
+// through LDS at the end.  A wavefront holds MB blocks of 32 activation rows; more rows run as
+// further workgroups (grid z), and K may be cut into ranges handled by different workgroups
+// whose partial results add_splits sums.
+// CPG: cells per group (groups inside a step), or 0 for groups of whole steps (any number; a
+// group cut by a k-slice or a K range is closed piecewise, the sums being linear).
+// ---------------------------------------------------------------------------------------
+struct CodesArgs {
+    const uint4 *codes;
+    const float *scales;
+    const uint32_t *zeros;
+    const uint16_t *Xop;       // [rows_padded][steps * S] bf16, operand order (prepare_x)
+    const uint16_t *Corr;      // [xhat entries][rows_padded][16] bf16 (prepare_x)
+    float *out;                // Y, or partial results [split][M][N]
+    int M, N, tiles, steps, ngroups, zwords;
+    int rows_padded;           // M rounded up to whole row blocks of the launch
+    int steps_padded;          // steps rounded up to a multiple of 4: what prepare_x has written (zeros past K)
+    int steps_per_group;       // CPG == 0: steps one group spans
+    int steps_per_split;       // a multiple of KW
+};
+
+struct PrepArgs {
+    const float *X;            // [M][K] fp32
+    uint16_t *Xop, *Corr;
+    int M, K, rows_padded, kpad;   // kpad = padded steps * S: every element of it is written
+    int groupk;                // k one xhat covers: the group, or a step for groups of whole steps
+};
+
+// One item = OCT consecutive k of one row (a cell at 2 bits, a word of a cell otherwise).
+// Consecutive threads take consecutive items of a row, so the items of one xhat sit in
+// neighbouring lanes.
+template <int BITS>
+__global__ __launch_bounds__(256) void prepare_x(const PrepArgs A)
+{
+    using F = Fmt<BITS>;
+    constexpr int S = codes_per_step<BITS>();
+    constexpr int OPS = mma_ops<BITS>();
+    constexpr int OCT = BITS == 2 ? 16 : 8;
+    const int m = blockIdx.y;
+    const int item = blockIdx.x * 256 + threadIdx.x;
+    const int items = A.kpad / OCT;
+    const bool live = item < items;                         // the last block of a row may overhang
+    const int k0 = (live ? item : items - 1) * OCT;
+    const bool real = live && m < A.M && k0 < A.K;
+    float val[OCT];
+    if (real) {
+        const float4 *src = (const float4 *)(A.X + (size_t)m * A.K + k0);
+#pragma unroll
+        for (int q = 0; q < OCT / 4; ++q) {
+            const float4 v = src[q];
+            val[4 * q + 0] = v.x; val[4 * q + 1] = v.y; val[4 * q + 2] = v.z; val[4 * q + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < OCT; ++e) val[e] = 0.0f;
+    }
+    const int in_step = k0 % S, step = k0 / S;
+    const int cell = in_step / F::CELL;
+    const int op0 = BITS == 3 ? (in_step % F::CELL) / 8 : 0;          // 3 bits: an item is one word of a cell
+    uint16_t h[OCT];                    // bf16 patterns in operand order: [operand][element]
+    float sum0 = 0.0f, sum1 = 0.0f;
+#pragma unroll
+    for (int e = 0; e < OCT; e += 2) {
+        // (3 bits) codes 4 ... 7 of a word are taken three bits up and enter as 128 + 8 q
+        const bool up = BITS == 3 && (e & 7) >= 4;
+        mma_floatx2 t2 = {val[e] * (up ? 0.125f : 1.0f), val[e + 1] * (up ? 0.125f : 1.0f)};
+        const mma_bf16x2 hb = __builtin_convertvector(t2, mma_bf16x2);            // round to nearest even
+        const uint32_t bits = *(const uint32_t *)&hb;
+        h[mma_slot<BITS>(e)] = (uint16_t)bits;
+        h[mma_slot<BITS>(e + 1)] = (uint16_t)(bits >> 16);
+        const float back = __uint_as_float(bits << 16) + __uint_as_float(bits & 0xffff0000u);
+        if (up) sum1 += back * 8.0f; else sum0 += back;
+    }
+    if (live) {
+        uint16_t *row = A.Xop + (size_t)m * A.kpad + (size_t)step * S;
+#pragma unroll
+        for (int o = 0; o < OCT / 8; ++o) {
+            uint4 piece;
+            piece.x = h[8 * o + 0] | ((uint32_t)h[8 * o + 1] << 16);
+            piece.y = h[8 * o + 2] | ((uint32_t)h[8 * o + 3] << 16);
+            piece.z = h[8 * o + 4] | ((uint32_t)h[8 * o + 5] << 16);
+            piece.w = h[8 * o + 6] | ((uint32_t)h[8 * o + 7] << 16);
+            *(uint4 *)(row + ((cell >> 1) * OPS + op0 + o) * 16 + (cell & 1) * 8) = piece;
+        }
+    }
+    // xhat: the groupk / OCT neighbouring lanes hold its items (every lane takes part)
+    const int wr = A.groupk / OCT;
+    for (int off = 1; off < wr; off *= 2) {
+        sum0 += __shfl_xor(sum0, off, 64);
+        sum1 += __shfl_xor(sum1, off, 64);
+    }
+    if (live && item % wr == 0) {
+        uint32_t part[2][3];            // three bf16 parts that add up to the sum exactly
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            float rest = c == 0 ? sum0 : sum1;
+#pragma unroll
+            for (int p3 = 0; p3 < 3; ++p3) {
+                mma_floatx2 t2 = {rest, 0.0f};
+                const mma_bf16x2 hb = __builtin_convertvector(t2, mma_bf16x2);
+                part[c][p3] = *(const uint32_t *)&hb & 0xffffu;
+                rest -= __uint_as_float(part[c][p3] << 16);
+            }
+        }
+        uint16_t *ce = A.Corr + ((size_t)(k0 / A.groupk) * A.rows_padded + m) * 16;
+        *(uint4 *)ce = make_uint4(part[0][0] | (part[0][1] << 16), part[0][2], 0u, 0u);
+        *(uint4 *)(ce + 8) = make_uint4(part[1][0] | (part[1][1] << 16), part[1][2], 0u, 0u);
+    }
+}
+
+template <int BITS, int CPG, int MB, int KW>
+__global__ __launch_bounds__(512) void gemm_codes(const CodesArgs A)
+{
+    using F = Fmt<BITS>;
+    constexpr int THREADS = 512;
+    constexpr int TN = 8 / KW;
+    constexpr int L = loads_per_step<BITS>();
+    constexpr int S = codes_per_step<BITS>();
+    constexpr int CELLS = cells_per_step<BITS>();
+    constexpr int GPS = CPG > 0 ? CELLS / CPG : 1;       // xhat entries per step (CPG == 0: one, the step's)
+    constexpr int OPS = mma_ops<BITS>();                  // B operands per cell
+    constexpr int ROWS = 32 * MB;
+    constexpr int CK = KW * S;                            // k per workgroup iteration
+    constexpr int PITCH = CK + 8;                         // bf16 per LDS row: conflict-free 128-bit reads
+    constexpr int CG = KW * GPS;                          // xhat entries per iteration
+    constexpr int XP = ROWS * CK / 8 / THREADS;           // 16-byte pieces of activations per thread and iteration
+    constexpr int CP = (ROWS * CG * 2 + THREADS - 1) / THREADS;   // ... of xhat operands
+    constexpr int ZPER = 32 / F::ZBITS;
+    constexpr int ACC = MB * 2 * 16;
+    static_assert(CPG == 0 || (CPG % 2 == 0 && CELLS % CPG == 0), "a group holds whole pairs of cells");
+    static_assert(ROWS * CK / 8 % THREADS == 0, "copy layout");
+    constexpr int XBYTES = 2 * ROWS * PITCH * 2;
+    extern __shared__ __attribute__((aligned(16))) char smem[];       // max(activations + xhat operands, reduction)
+    lds_u16 *Xs = (lds_u16 *)smem;                                    // [2][ROWS][PITCH]
+    lds_u16 *Cs = (lds_u16 *)(smem + XBYTES);                         // [2][CG][ROWS][16]
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tn = wave % TN, kw = wave / TN;
+    const int tile = blockIdx.x * TN + tn;
+    const bool have_tile = tile < A.tiles;
+    const int m0 = blockIdx.z * ROWS;
+    const int st0 = blockIdx.y * A.steps_per_split;
+    int st1 = st0 + A.steps_per_split;
+    if (st1 > A.steps) st1 = A.steps;
+    const int iters = (st1 - st0 + KW - 1) / KW;
+    const int kpad = A.steps_padded * S;
+
+    const int tclamp = have_tile ? tile : A.tiles - 1;
+    const uint4 *codes = A.codes + (size_t)tclamp * A.steps * L * QG_WAVE + lane;
+    const float *sc = A.scales + (size_t)tclamp * A.ngroups * QG_WAVE + lane;
+    const uint32_t *zr = A.zeros + (size_t)tclamp * A.zwords * QG_WAVE + lane;
+
+    struct StepRegs {
+        uint4 v[L];
+        float s[GPS];
+        uint32_t zw;
+    };
+    // group of xhat entry `gs` of a step, clamped to the groups that exist (K is padded to whole
+    // steps with zero codes; what the padding adds up to is zero whatever scale it meets)
+    auto group_of = [&](int step, int gs) {
+        int g = CPG > 0 ? step * GPS + gs : step / A.steps_per_group;
+        return g < A.ngroups ? g : A.ngroups - 1;
+    };
+    auto fetch = [&](int step, StepRegs &r) {
+        step = step < st1 ? step : st1 - 1;            // past the range: loaded again, not used
+#pragma unroll
+        for (int i = 0; i < L; ++i) r.v[i] = codes[((size_t)step * L + i) * QG_WAVE];
+#pragma unroll
+        for (int g = 0; g < GPS; ++g) r.s[g] = sc[(size_t)group_of(step, g) * QG_WAVE];
+        r.zw = zr[(size_t)(group_of(step, 0) / ZPER) * QG_WAVE];       // a step's groups share one zero word
+    };
+
+    // ---- activations and xhat operands of one iteration: plain 16-byte copies into LDS ----
+    // (a chunk that begins past the last step is read from the last chunk again and never used)
+    typedef uint32_t copy128 __attribute__((ext_vector_type(4)));       // a plain vector: stays in registers
+    typedef copy128 __attribute__((may_alias)) copy128_lds;
+    copy128 xq[XP], cq[CP];
+    auto load_x = [&](int first_step) {
+        const int fs = first_step + KW <= A.steps_padded ? first_step : A.steps_padded - KW;
+#pragma unroll
+        for (int j = 0; j < XP; ++j) {
+            const int p = j * THREADS + threadIdx.x;          // piece: row p / (CK / 8), 8 k at p % (CK / 8)
+            const int r = p / (CK / 8), c = p % (CK / 8);
+            xq[j] = *(const copy128 *)(A.Xop + (size_t)(m0 + r) * kpad + (size_t)fs * S + c * 8);
+        }
+#pragma unroll
+        for (int j = 0; j < CP; ++j) {
+            int p = j * THREADS + threadIdx.x;                // piece: entry p / (ROWS * 2), 16 bytes of row (p / 2) % ROWS
+            p = p < ROWS * CG * 2 ? p : ROWS * CG * 2 - 1;
+            const int e = p / (ROWS * 2), rr = p % (ROWS * 2);
+            cq[j] = *(const copy128 *)(A.Corr + ((size_t)(fs * GPS + e) * A.rows_padded + m0) * 16 + rr * 8);
+        }
+    };
+    auto store_x = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < XP; ++j) {
+            const int p = j * THREADS + threadIdx.x;
+            const int r = p / (CK / 8), c = p % (CK / 8);
+            *(copy128_lds *)(Xs + ((size_t)buf * ROWS + r) * PITCH + c * 8) = xq[j];
+        }
+#pragma unroll
+        for (int j = 0; j < CP; ++j) {
+            const int p = j * THREADS + threadIdx.x;
+            if (p < ROWS * CG * 2) *(copy128_lds *)(Cs + (size_t)buf * CG * ROWS * 16 + (size_t)p * 8) = cq[j];
+        }
+    };
+
+    // ---- accumulators ----
+    mma_floatx16 accP[MB], accQ[MB];          // T of the running group: outputs 0-31 (P) and 32-63 (Q) of the tile
+    float yP[MB][16], yQ[MB][16];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { accP[mb][i] = 0.0f; accQ[mb][i] = 0.0f; yP[mb][i] = 0.0f; yQ[mb][i] = 0.0f; }
+    const int half = lane >> 5, row = lane & 31;
+    const MmaConst mc = mma_constants<BITS>();
+    // Y += s * T, with the scales of outputs lane % 32 (P) and 32 + lane % 32 (Q)
+    auto fold = [&](float sP, float sQ) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                yP[mb][i] = fmaf(sP, accP[mb][i], yP[mb][i]);
+                yQ[mb][i] = fmaf(sQ, accQ[mb][i], yQ[mb][i]);
+            }
+    };
+    // the B operand of the zero-point term: -(128 + z) against the parts of xhat in lanes 0-31,
+    // -(16 + z) against the parts of the other xhat in lanes 32-63 (3 bits only; else zeros there)
+    auto corr_operand = [&](uint32_t zq) {
+        const float c = half == 0 ? -(float)(zq + 128u) : BITS == 3 ? -(float)(zq + 16u) : 0.0f;
+        const uint32_t cb = __float_as_uint(c) >> 16;                  // small integers are exact in bf16
+        MmaOperand b;
+        b.r[0] = cb | (cb << 16);
+        b.r[1] = cb;
+        b.r[2] = 0u;
+        b.r[3] = 0u;
+        return b;
+    };
+    float heldP = 0.0f, heldQ = 0.0f;         // CPG == 0: scale of the group the accumulators belong to
+    int held_g = -1;
+    bool fresh = true;                        // CPG == 0: no step has been computed yet
+
+    auto compute = [&](const StepRegs &r, int step, int buf) {
+        const lds_u16 *xs = Xs + ((size_t)buf * ROWS + row) * PITCH + kw * S + half * 8;
+        const lds_u16 *cs = Cs + ((size_t)buf * CG + kw * GPS) * ROWS * 16 + row * 16 + half * 8;
+        const auto zsw = __builtin_amdgcn_permlane32_swap(r.zw, r.zw, false, false);
+        const uint32_t zwP = zsw[0], zwQ = zsw[1];
+        const mma_floatx16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        if constexpr (CPG == 0) {
+            const int g = group_of(step, 0);
+            if (g != held_g) {                       // uniform: the running group ended before this step
+                if (!fresh) fold(heldP, heldQ);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    accP[mb] = zero16;
+                    accQ[mb] = zero16;
+                }
+                const auto ssw = __builtin_amdgcn_permlane32_swap(__float_as_uint(r.s[0]), __float_as_uint(r.s[0]), false, false);
+                heldP = __uint_as_float(ssw[0]);
+                heldQ = __uint_as_float(ssw[1]);
+                held_g = g;
+            }
+        }
+        // what closes a group after pair cp: the zero-point term on the matrix cores, then Y += s T
+        auto close_group = [&](int cp) {
+            const bool group_ends = CPG > 0 ? (2 * cp + 2) % CPG == 0 : cp == CELLS / 2 - 1;
+            if (group_ends) {
+                const int gs = CPG > 0 ? (2 * cp + 2) / CPG - 1 : 0;
+                const int gabs = group_of(step, gs);
+                const uint32_t zP = (zwP >> (F::ZBITS * (gabs % ZPER))) & ((1u << F::ZBITS) - 1u);
+                const uint32_t zQ = (zwQ >> (F::ZBITS * (gabs % ZPER))) & ((1u << F::ZBITS) - 1u);
+                const MmaOperand cP = corr_operand(zP), cQ = corr_operand(zQ);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    MmaOperand a;
+                    a.q = *(const lds_u128 *)(cs + ((size_t)gs * ROWS + mb * 32) * 16);
+                    accP[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, cP.v, accP[mb], 0, 0, 0);
+                    accQ[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, cQ.v, accQ[mb], 0, 0, 0);
+                }
+                if constexpr (CPG > 0) {
+                    const auto ssw = __builtin_amdgcn_permlane32_swap(__float_as_uint(r.s[gs]), __float_as_uint(r.s[gs]), false, false);
+                    fold(__uint_as_float(ssw[0]), __uint_as_float(ssw[1]));
+                }
+            }
+        };
+        if constexpr (BITS == 4) {
+            // 4 bits: a software pipeline.  The matrix instructions of pair cp alternate with the
+            // pieces of the unpacking of pair cp + 1 (and with its lane exchange and LDS reads), every
+            // slot fenced, so that a wavefront keeps the matrix core and the vector ALU busy at the
+            // same time instead of in turns (two wavefronts of a SIMD that leave a barrier together
+            // would otherwise take those turns in step).
+            constexpr int NP = CELLS / 2;
+            MmaOperand bP, bQ, nP, nQ, aC[MB], aN[MB];
+            uint32_t wP = 0, wQ = 0;
+            auto swap_words = [&](int cp) {
+                const int c0 = 2 * cp, u = c0 >> 2, j = c0 & 3;
+                const auto sw = __builtin_amdgcn_permlane32_swap(word_of(r.v[u], j), word_of(r.v[u], j + 1), false, false);
+                wP = sw[0];           // outputs 0-31: cell 2 cp in lanes 0-31, cell 2 cp + 1 in lanes 32-63
+                wQ = sw[1];           // outputs 32-63
+            };
+            auto piece = [&](int i) {       // quarter i of the unpacking of (wP, wQ) into (nP, nQ)
+                const uint32_t w = i < 2 ? wP : wQ;
+                MmaOperand &b = i < 2 ? nP : nQ;
+                const int j0 = 2 * (i & 1);
+                b.r[j0] = and_or(w >> (4 * j0), mc.mask, mc.magic);
+                b.r[j0 + 1] = and_or(w >> (4 * (j0 + 1)), mc.mask, mc.magic);
+                asm volatile("" : "+v"(b.r[j0]), "+v"(b.r[j0 + 1]));      // keeps the piece in its slot
+            };
+            auto read_a = [&](int cp, MmaOperand *a) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) a[mb].q = *(const lds_u128 *)(xs + (size_t)mb * 32 * PITCH + cp * 16);
+            };
+            swap_words(0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) piece(i);
+            bP = nP;
+            bQ = nQ;
+            read_a(0, aC);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int cp = 0; cp < NP; ++cp) {
+                const bool more = cp + 1 < NP;
+                const bool starts = CPG > 0 && (2 * cp) % CPG == 0;       // a group starts from zero
+#pragma unroll
+                for (int k = 0; k < 2 * MB; ++k) {
+                    const int mb = k >> 1;
+                    if ((k & 1) == 0)
+                        accP[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aC[mb].v, bP.v, starts ? zero16 : accP[mb], 0, 0, 0);
+                    else
+                        accQ[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aC[mb].v, bQ.v, starts ? zero16 : accQ[mb], 0, 0, 0);
+                    if (more) {
+                        if (k == 0) {
+                            swap_words(cp + 1);
+                            read_a(cp + 1, aN);
+                        }
+                        if constexpr (MB == 1) {
+                            piece(2 * k);
+                            piece(2 * k + 1);
+                        } else {
+                            piece(k);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                close_group(cp);
+                if (more) {
+                    bP = nP;
+                    bQ = nQ;
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) aC[mb] = aN[mb];
+                }
+            }
+        } else {
+#pragma unroll
+        for (int cp = 0; cp < CELLS / 2; ++cp) {
+            uint32_t wp[F::PLANES], wq[F::PLANES];
+            const int c0 = 2 * cp, u = c0 >> 2, j = c0 & 3;
+#pragma unroll
+            for (int pl = 0; pl < F::PLANES; ++pl) {
+                const auto sw = __builtin_amdgcn_permlane32_swap(word_of(r.v[u * F::PLANES + pl], j),
+                                                                 word_of(r.v[u * F::PLANES + pl], j + 1), false, false);
+                wp[pl] = sw[0];       // outputs 0-31: cell 2 cp in lanes 0-31, cell 2 cp + 1 in lanes 32-63
+                wq[pl] = sw[1];       // outputs 32-63
+            }
+            MmaOperand bp[OPS], bq[OPS];
+            mma_unpack<BITS>(wp, mc, bp);
+            mma_unpack<BITS>(wq, mc, bq);
+            // the first matrix instruction of a group starts from zero instead of the old sums
+            const bool starts = CPG > 0 ? (2 * cp) % CPG == 0 : false;
+#pragma unroll
+            for (int op = 0; op < OPS; ++op) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    MmaOperand a;
+                    a.q = *(const lds_u128 *)(xs + (size_t)mb * 32 * PITCH + (cp * OPS + op) * 16);
+                    if (CPG > 0 && starts && op == 0) {
+                        accP[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bp[op].v, zero16, 0, 0, 0);
+                        accQ[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bq[op].v, zero16, 0, 0, 0);
+                    } else {
+                        accP[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bp[op].v, accP[mb], 0, 0, 0);
+                        accQ[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bq[op].v, accQ[mb], 0, 0, 0);
+                    }
+                }
+            }
+            close_group(cp);
+        }
+        }
+        fresh = false;
+    };
+
+    // Every iteration is straight-line code: request the activations of iteration it + 1 and then
+    // its weights (clamped past the end), compute iteration it from registers and LDS, then move
+    // the new activations into place.  The activation copies are requested BEFORE the weights:
+    // loads return in order, and the copies are waited for at the end of the same iteration,
+    // while the weights are not needed before the next one.  Two register sets take turns, so
+    // that no iteration moves (and so waits for) the weights it has just requested.
+    StepRegs ra, rb;
+    if (iters > 0) {
+        load_x(st0);
+        fetch(st0 + kw, ra);
+        store_x(0);
+    }
+    __syncthreads();
+    int buf = 0;
+    auto iteration = [&](int it, const StepRegs &use, StepRegs &request) {
+        const int step = st0 + it * KW + kw;
+        load_x(st0 + (it + 1) * KW);
+        fetch(step + KW, request);
+        __builtin_amdgcn_sched_barrier(0);
+        if (step < st1) compute(use, step, buf);
+        __builtin_amdgcn_sched_barrier(0);
+        store_x(buf ^ 1);
+        __syncthreads();          // next chunk written, this chunk's readers done
+        buf ^= 1;
+    };
+    for (int it = 0; it < iters; it += 2) {
+        iteration(it, ra, rb);
+        if (it + 1 >= iters) break;
+        iteration(it + 1, rb, ra);
+    }
+    if constexpr (CPG == 0) {
+        if (!fresh) fold(heldP, heldQ);
+    }
+
+    if constexpr (KW > 1) {
+        // k-slices 1 .. KW-1 hand their results to slice 0 of the same tile, which adds them in
+        // slice order; the activation buffers are reused (every reader is past the last barrier)
+        float *red = (float *)smem;
+        if (kw > 0) {
+            float *dst = red + ((size_t)((kw - 1) * TN + tn) * ACC) * 64 + lane;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    dst[((mb * 2 + 0) * 16 + i) * 64] = yP[mb][i];
+                    dst[((mb * 2 + 1) * 16 + i) * 64] = yQ[mb][i];
+                }
+        }
+        __syncthreads();
+        if (kw > 0) return;
+#pragma unroll
+        for (int k = 1; k < KW; ++k) {
+            const float *src = red + ((size_t)((k - 1) * TN + tn) * ACC) * 64 + lane;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    yP[mb][i] += src[((mb * 2 + 0) * 16 + i) * 64];
+                    yQ[mb][i] += src[((mb * 2 + 1) * 16 + i) * 64];
+                }
+        }
+    }
+
+    if (!have_tile) return;
+    float *out = A.out + (size_t)blockIdx.y * A.M * A.N;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int m = m0 + mb * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+            const int nP = tile * QG_WAVE + row, nQ = nP + 32;
+            if (m < A.M && nP < A.N) out[(size_t)m * A.N + nP] = yP[mb][i];
+            if (m < A.M && nQ < A.N) out[(size_t)m * A.N + nQ] = yQ[mb][i];
+        }
+}
+
+template <int BITS, int CPG, int MB, int KW>
+constexpr size_t gemm_codes_lds()
+{
+    constexpr int S = codes_per_step<BITS>();
+    constexpr int GPS = CPG > 0 ? cells_per_step<BITS>() / CPG : 1;
+    constexpr size_t x = 2 * (32 * MB) * (KW * S + 8) * 2, c = 2 * (32 * MB) * (KW * GPS) * 16 * 2;
+    constexpr size_t r = (size_t)(KW - 1) * (8 / KW) * (MB * 2 * 16) * 64 * 4;
+    return x + c > r ? x + c : r;
+}
+
 // Y = sum of the K-split partial results, in split order.  All (up to 8) loads of a thread
 // are issued before the first addition; a loop over a run-time split count would wait for
 // each load in turn.
@@ -679,6 +1181,73 @@ void launch_shape(int i, const GemmArgs &A, dim3 grid, hipStream_t st)
     }
 }
 
+
+// ---- gemm_codes: which layouts it takes, and its launch ----
+int codes_cpg(const QgLayout &L)       // cells per group, 0 for groups of whole steps, -1: not taken
+{
+    const int S = L.unit * L.step_units, cells = 4 * L.step_units;
+    if (L.K % 16 != 0 || L.K > (1 << 22)) return -1;
+    if (L.group % S == 0) return 0;
+    const int cpg = L.group / L.cell;
+    if (L.group > S || cpg < 2 || cpg % 2 != 0 || cells % cpg != 0) return -1;
+    return cpg;
+}
+
+// Workspace of the raw-code path: converted activations, xhat operands, K-split partial results.
+struct CodesSpace {
+    size_t xop_off, corr_off, partial_off, total;
+    int rows_padded, steps_padded, groupk;
+};
+CodesSpace codes_space(const QgLayout &L, int M)
+{
+    CodesSpace W;
+    const int S = L.unit * L.step_units;
+    const int rows_per_block = M <= 32 ? 32 : 64;
+    W.rows_padded = (M + rows_per_block - 1) / rows_per_block * rows_per_block;
+    W.steps_padded = (int)((L.steps + 3) / 4 * 4);
+    W.groupk = L.group % S == 0 ? S : L.group;
+    const size_t kpad = (size_t)W.steps_padded * S;
+    W.xop_off = 0;
+    W.corr_off = qg_round_up(W.xop_off + (size_t)W.rows_padded * kpad * 2, QG_SECTION_ALIGN);
+    W.partial_off = qg_round_up(W.corr_off + kpad / W.groupk * W.rows_padded * 32, QG_SECTION_ALIGN);
+    W.total = qg_round_up(W.partial_off + (size_t)MAX_SPLITS * M * L.N * sizeof(float), QG_SECTION_ALIGN);
+    return W;
+}
+
+template <int BITS, int CPG, int MB>
+int launch_codes(const CodesArgs &A, dim3 grid, hipStream_t st)
+{
+    constexpr int KW = BITS == 4 ? (MB == 1 ? 4 : 2) : (MB == 1 ? 2 : 1);
+    constexpr size_t lds = gemm_codes_lds<BITS, CPG, MB, KW>();
+    static bool prepared = false;              // dynamic LDS above 64 KB has to be asked for once
+    if (!prepared) {
+        if (hipFuncSetAttribute((const void *)gemm_codes<BITS, CPG, MB, KW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess) {
+            (void)hipGetLastError();
+            return QG_ERR_DEVICE;
+        }
+        prepared = true;
+    }
+    hipLaunchKernelGGL((gemm_codes<BITS, CPG, MB, KW>), grid, dim3(512), lds, st, A);
+    return QG_OK;
+}
+
+template <int BITS, int MB>
+int launch_codes_cpg(int cpg, const CodesArgs &A, dim3 grid, hipStream_t st)
+{
+    switch (cpg) {
+    case 0: return launch_codes<BITS, 0, MB>(A, grid, st);
+    case 2: return launch_codes<BITS, 2, MB>(A, grid, st);
+    case 4: return launch_codes<BITS, 4, MB>(A, grid, st);
+    case 8: return launch_codes<BITS, 8, MB>(A, grid, st);
+    case 16:
+        if constexpr (BITS != 3) return launch_codes<BITS, 16, MB>(A, grid, st);
+        return QG_ERR_UNSUPPORTED;
+    default: return QG_ERR_UNSUPPORTED;
+    }
+}
+
+constexpr int codes_kw(int bits, int mb) { return bits == 4 ? (mb == 1 ? 4 : 2) : (mb == 1 ? 2 : 1); }
 }  // namespace
 
 size_t qg_gemm_workspace_bytes(const QgLayout &L, int M)
@@ -688,12 +1257,14 @@ size_t qg_gemm_workspace_bytes(const QgLayout &L, int M)
     const size_t gemv = qg_round_up((size_t)L.tiles * (QG_MAX_CHUNKS + 1) * QG_WAVE * sizeof(uint32_t),
                                     QG_SECTION_ALIGN);                                    // as qg_gemv asks
     const int rows = M < QG_MAX_GROUPED ? M : QG_MAX_GROUPED;
-    return qg_round_up(fast_path(L) ? partial : gemv * rows, QG_SECTION_ALIGN);
+    size_t need = fast_path(L) && partial > gemv * rows ? partial : gemv * rows;
+    if (M > 1 && codes_cpg(L) >= 0 && codes_space(L, M).total > need) need = codes_space(L, M).total;
+    return qg_round_up(need, QG_SECTION_ALIGN);
 }
 
 extern "C" int qg_set_gemm_tuning(int splits, int shape)
 {
-    if (splits < 0 || splits > MAX_SPLITS || shape < -1 || shape > NSHAPES) return QG_ERR_SHAPE;
+    if (splits < 0 || splits > MAX_SPLITS || shape < -1 || shape > NSHAPES + 1) return QG_ERR_SHAPE;
     g_tune_splits = splits;
     g_tune_shape = shape;
     return QG_OK;
@@ -713,6 +1284,76 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     if (!qg_aligned16(workspace)) return QG_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
 
+    // The raw-code kernel: every layout it takes that the 4-bit kernels below do not (2 and 3
+    // bits, 4-bit groups of 16), and whatever shape 13 sends it.  (Measured on the 7B shapes at 4
+    // bits, group 128: within 0-20 % of the dequantizing kernels, behind mostly by the launch of
+    // prepare_x; at 2 and 3 bits 2-15 times ahead of one GEMV per row.)
+    const int cpg = codes_cpg(L);
+    if (cpg >= 0 && M > 1 && (g_tune_shape == NSHAPES + 1 || (g_tune_shape == 0 && !fast_path(L)))) {
+        const int mb = M <= 32 ? 1 : 2;
+        const int kw = codes_kw(bits, mb), tn = 8 / kw;
+        const int rows_per_block = 32 * mb;
+        const int zblocks = (M + rows_per_block - 1) / rows_per_block;
+        const int blocks_x = (int)((L.tiles + tn - 1) / tn);
+        const int quanta = (int)((L.steps + kw - 1) / kw);
+        const int cus = qg_compute_units();
+        // as many K ranges as keep the launch within one workgroup per compute unit (a workgroup
+        // fills a unit's LDS, so one more would wait for a second round)
+        int splits = g_tune_splits ? g_tune_splits : cus / (blocks_x * zblocks);
+        if (splits < 1) splits = 1;
+        if (splits > MAX_SPLITS) splits = MAX_SPLITS;
+        if (splits > quanta) splits = quanta;
+        const int sps = (quanta + splits - 1) / splits * kw;
+        splits = (int)((L.steps + sps - 1) / sps);
+        const CodesSpace W = codes_space(L, M);
+        char *ws = (char *)workspace;
+        PrepArgs P;
+        P.X = X;
+        P.Xop = (uint16_t *)(ws + W.xop_off);
+        P.Corr = (uint16_t *)(ws + W.corr_off);
+        P.M = M;
+        P.K = (int)K;
+        P.rows_padded = W.rows_padded;
+        P.kpad = W.steps_padded * L.unit * L.step_units;
+        P.groupk = W.groupk;
+        const dim3 pgrid((unsigned)((P.kpad / (bits == 2 ? 16 : 8) + 255) / 256), (unsigned)W.rows_padded);
+        if (bits == 4) hipLaunchKernelGGL(prepare_x<4>, pgrid, dim3(256), 0, st, P);
+        else if (bits == 2) hipLaunchKernelGGL(prepare_x<2>, pgrid, dim3(256), 0, st, P);
+        else hipLaunchKernelGGL(prepare_x<3>, pgrid, dim3(256), 0, st, P);
+        if (qg_launch_status() != QG_OK) return QG_ERR_DEVICE;
+        CodesArgs A;
+        const char *base = (const char *)packed;
+        A.codes = (const uint4 *)(base + L.codes_off);
+        A.scales = (const float *)(base + L.scales_off);
+        A.zeros = (const uint32_t *)(base + L.zeros_off);
+        A.Xop = P.Xop;
+        A.Corr = P.Corr;
+        A.out = splits > 1 ? (float *)(ws + W.partial_off) : Y;
+        A.M = M;
+        A.N = (int)N;
+        A.tiles = (int)L.tiles;
+        A.steps = (int)L.steps;
+        A.ngroups = (int)L.ngroups;
+        A.zwords = (int)L.zwords;
+        A.rows_padded = W.rows_padded;
+        A.steps_padded = W.steps_padded;
+        A.steps_per_group = cpg == 0 ? group / (L.unit * L.step_units) : 1;
+        A.steps_per_split = sps;
+        const dim3 grid((unsigned)blocks_x, (unsigned)splits, (unsigned)zblocks);
+        int r;
+        if (bits == 4) r = mb == 1 ? launch_codes_cpg<4, 1>(cpg, A, grid, st) : launch_codes_cpg<4, 2>(cpg, A, grid, st);
+        else if (bits == 2) r = mb == 1 ? launch_codes_cpg<2, 1>(cpg, A, grid, st) : launch_codes_cpg<2, 2>(cpg, A, grid, st);
+        else r = mb == 1 ? launch_codes_cpg<3, 1>(cpg, A, grid, st) : launch_codes_cpg<3, 2>(cpg, A, grid, st);
+        if (r != QG_OK) return r;
+        if (qg_launch_status() != QG_OK) return QG_ERR_DEVICE;
+        if (splits > 1) {
+            const size_t count = (size_t)M * N;
+            hipLaunchKernelGGL(add_splits, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st,
+                               (const float *)(ws + W.partial_off), splits, count, Y);
+        }
+        return qg_launch_status();
+    }
+
     // Up to 16 rows: the barrier-free kernel on the GEMV's launch structure, where it applies.
     // It has one workgroup per tile and no split of K over workgroups, so it needs enough tiles
     // to cover the chip (measured: ahead from about 128 tiles; shape -1 forces it).
@@ -725,21 +1366,25 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
         // the fp32 GEMV once per activation row, up to 16 rows per launch (rows of X stay
         // 64-byte aligned only if K % 16 == 0)
         if (K % 16 != 0 && M > 1) return QG_ERR_UNSUPPORTED;
-        for (int m0 = 0; m0 < M; m0 += QG_MAX_GROUPED) {
-            qg_gemv_desc d[QG_MAX_GROUPED];
-            const int rows = M - m0 < QG_MAX_GROUPED ? M - m0 : QG_MAX_GROUPED;
-            for (int i = 0; i < rows; ++i) {
-                d[i].packed = packed;
-                d[i].N = N;
-                d[i].K = K;
-                d[i].bits = bits;
-                d[i].group = group;
-                d[i].x = X + (size_t)(m0 + i) * K;
-                d[i].y = Y + (size_t)(m0 + i) * N;
+        // two passes over the launches of 16 rows: the first only checks and plans, so that an
+        // error leaves nothing enqueued
+        for (int pass = 0; pass < 2; ++pass)
+            for (int m0 = 0; m0 < M; m0 += QG_MAX_GROUPED) {
+                qg_gemv_desc d[QG_MAX_GROUPED];
+                const int rows = M - m0 < QG_MAX_GROUPED ? M - m0 : QG_MAX_GROUPED;
+                for (int i = 0; i < rows; ++i) {
+                    d[i].packed = packed;
+                    d[i].N = N;
+                    d[i].K = K;
+                    d[i].bits = bits;
+                    d[i].group = group;
+                    d[i].x = X + (size_t)(m0 + i) * K;
+                    d[i].y = Y + (size_t)(m0 + i) * N;
+                }
+                const int r = pass == 0 ? qg_gemv_grouped_check(d, rows, workspace, workspace_bytes)
+                                        : qg_gemv_grouped(d, rows, workspace, workspace_bytes, stream);
+                if (r != QG_OK) return r;
             }
-            const int r = qg_gemv_grouped(d, rows, workspace, workspace_bytes, stream);
-            if (r != QG_OK) return r;
-        }
         return QG_OK;
     }
 
@@ -750,7 +1395,7 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     // k-slices (two blocks double the wavefronts of a launch at the price of dequantizing
     // twice, which pays as long as the launch cannot fill the chip).
     int shape = M <= 32 ? 1 : M <= 64 ? 7 : L.tiles >= 128 ? 9 : 5;
-    if (g_tune_shape > 0) {
+    if (g_tune_shape > 0 && g_tune_shape <= NSHAPES) {
         const Shape &s = SHAPES[g_tune_shape - 1];
         if (s.wide ? (M > 32 && M <= s.mb * 32) : ((s.mb == 1) == (M <= 32))) shape = g_tune_shape - 1;
     }

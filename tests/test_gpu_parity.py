@@ -631,12 +631,45 @@ GEMM_CASES = [  # N, K, bits, group, M
 ]
 
 
+@pytest.mark.parametrize("shape", [0, 13])       # the built-in choice / the raw-code kernel wherever it applies
 @pytest.mark.parametrize("N,K,bits,group,M", GEMM_CASES)
-def test_gemm_small_matches_oracle(qg, oracle, N, K, bits, group, M):
-    _announce("gemm_small", N, K, bits, group, M)
+def test_gemm_small_matches_oracle(qg, oracle, N, K, bits, group, M, shape):
+    _announce("gemm_small", N, K, bits, group, M, shape)
     W, X = synth.small_case(N + K + M, N, K, 0.02, True, m=max(M, 2))
     X = X[:M]
-    err = _gemm_case(qg, oracle, W, X, bits, group)
+    qg.qg_set_gemm_tuning(0, shape)
+    try:
+        err = _gemm_case(qg, oracle, W, X, bits, group)
+    finally:
+        qg.qg_set_gemm_tuning(0, 0)
+    assert err <= TOL_BF16, err
+
+
+CODES_CASES = [  # N, K, bits, group, M   -- the raw-code kernel: every group pattern of every width
+    (200, 1024, 2, 32, 16), (130, 1024, 2, 64, 33), (96, 768, 2, 128, 7), (70, 1024, 2, 256, 100),
+    (200, 1024, 2, 512, 64), (130, 1536, 2, 1536, 128),             # groups of whole steps, one group per output
+    (200, 1024, 3, 64, 16), (130, 1536, 3, 128, 70), (96, 768, 3, 256, 5), (70, 2048, 3, 512, 128),
+    (130, 1280, 3, 1280, 40),
+    (200, 1024, 4, 16, 16), (130, 768, 4, 32, 50), (64, 512, 4, 64, 128), (300, 1024, 4, 128, 33),
+    (128, 2048, 4, 2048, 128), (330, 1152, 4, 384, 20),
+    (190, 1312, 3, 32 * 41, 9),      # K not a whole number of steps (padded), one group per output: row-by-row path
+    (190, 1312, 2, 32, 9),           # K = 5 steps + 32: the last step is mostly padding
+    (100, 416, 4, 32, 60),           # 3 steps + 32
+    (1100, 512, 2, 32, 128), (1100, 512, 3, 64, 128),                # many tiles, two blocks of rows
+]
+
+
+@pytest.mark.parametrize("splits", [0, 1, 3])
+@pytest.mark.parametrize("N,K,bits,group,M", CODES_CASES)
+def test_gemm_small_raw_code_kernel(qg, oracle, N, K, bits, group, M, splits):
+    _announce("gemm raw codes", N, K, bits, group, M, splits)
+    W, X = synth.small_case(4000 + N + K + M, N, K, 0.02, True, m=max(M, 2))
+    X = X[:M]
+    qg.qg_set_gemm_tuning(splits, 13)
+    try:
+        err = _gemm_case(qg, oracle, W, X, bits, group)
+    finally:
+        qg.qg_set_gemm_tuning(0, 0)
     assert err <= TOL_BF16, err
 
 
@@ -774,18 +807,37 @@ def test_gemm_small_random_shapes(qg, oracle, seed):
         assert err <= TOL_BF16, (N, K, group, M, splits, shape, err)
 
 
+@pytest.mark.parametrize("shape", [0, 13])
 @pytest.mark.parametrize("index", [0, 1, 2])
 @pytest.mark.parametrize("mi", [0, 1, 2])
-def test_gemm_small_full_size(qg, oracle, index, mi):
-    # configuration 5: LLaMA-7B shapes, 4-bit group 128, M = 16, 64, 128; all outputs compared
+def test_gemm_small_full_size(qg, oracle, index, mi, shape):
+    # configuration 5: LLaMA-7B shapes, 4-bit group 128, M = 16, 64, 128; all outputs compared;
+    # on the built-in choice of kernel and on the raw-code kernel
     cfg = synth.CONFIGS["C5"]
     N, K = cfg.shapes[index]
     M = cfg.batch[mi]
-    _announce("gemm full size", N, K, M)
+    _announce("gemm full size", N, K, M, shape)
     W, acts = synth.matrix(cfg, index)
     X = acts[mi]
+    qg.qg_set_gemm_tuning(0, shape)
+    try:
+        err = _gemm_case(qg, oracle, W, X, cfg.bits, cfg.group)
+    finally:
+        qg.qg_set_gemm_tuning(0, 0)
+    print(f"[full] C5[{index}] M={M} shape {shape} scaled error {err:.3e}", flush=True)
+    assert err <= TOL_BF16, err
+
+
+@pytest.mark.parametrize("name,index,M", [("C3", 0, 16), ("C3", 6, 128), ("C4", 0, 64), ("C4", 4, 16)])
+def test_gemm_small_full_size_other_widths(qg, oracle, name, index, M):
+    # 3-bit group 64 and 2-bit group 32 at the sizes of the 13B- and 65B-shaped layer sets
+    cfg = synth.CONFIGS[name]
+    N, K = cfg.shapes[index]
+    _announce("gemm full size", name, N, K, M)
+    W, _ = synth.matrix(cfg, index)
+    X = np.random.Generator(np.random.Philox(77 + M)).standard_normal((M, K), dtype=np.float32)
     err = _gemm_case(qg, oracle, W, X, cfg.bits, cfg.group)
-    print(f"[full] C5[{index}] M={M} scaled error {err:.3e}", flush=True)
+    print(f"[full] {name}[{index}] M={M} scaled error {err:.3e}", flush=True)
     assert err <= TOL_BF16, err
 
 

@@ -81,7 +81,7 @@ def test_bad_shapes_are_rejected_without_a_gpu(qg):
     assert L.qg_gemv_autotune(None, 1, 1, None, 0, None, 0, None, None, None, None) == 2   # repeats <= 0
     assert L.qg_gemm_small(16, 64, 128, 4, 32, 64, 0, 16, 16, 1 << 20, None) == 2          # M <= 0
     assert L.qg_gemm_small(16, 64, 128, 4, 32, 64, 129, 16, 16, 1 << 20, None) == 2        # M > 128
-    assert L.qg_set_gemm_tuning(9, 0) == 2 and L.qg_set_gemm_tuning(0, 13) == 2 and L.qg_set_gemm_tuning(0, 0) == 0
+    assert L.qg_set_gemm_tuning(9, 0) == 2 and L.qg_set_gemm_tuning(0, 14) == 2 and L.qg_set_gemm_tuning(0, 0) == 0
     assert L.qg_set_gemv_tuning(99, 0, 0) == 2 and L.qg_set_gemv_tuning(0, 0, 5) == 2
     assert L.qg_set_gemv_tuning(0, 0, 0) == 0
     assert b"aligned" in L.qg_status_string(4)
