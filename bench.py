@@ -335,7 +335,70 @@ def other_workloads(qg, args):
     gemm = bench_gemm(synth.CONFIGS["C5"], qg, args)
     out["C5"] = {"workload": gemm["config"]["workload"], "us_all_problems": gemm["value"],
                  "problems": gemm["problems"]}
+    out["gemm_other_widths_M16"] = bench_gemm_other_widths(qg, args)
+    out["stacked_qkv"] = bench_stacked_qkv(qg, args)
     return out
+
+
+def bench_gemm_other_widths(qg, args):
+    """The small-M product at 3 and 2 bits: M = 16 on the three shapes of the 13B- and 65B-shaped
+    layer sets (timing only, weights drawn on the GPU), packed copies rotated."""
+    from paper_2307_03738_amd import synth
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    steps, warm = max(20, args.steps // 10), max(5, args.warmup // 10)
+    rows, M = [], 16
+    for name in ("C3", "C4"):
+        cfg = synth.CONFIGS[name]
+        gen = torch.Generator(device="cuda").manual_seed(200 + cfg.seed)
+        for N, K in sorted(set(cfg.shapes)):
+            W = torch.randn((N, K), device="cuda", generator=gen) * cfg.std
+            q, s, z = qg.qg_quantize(W, cfg.bits, cfg.group)
+            blob = qg.qg_pack(q, s, z, cfg.bits, cfg.group)
+            del W, q, s, z
+            copies = max(2, int(np.ceil(ROTATE_BYTES / blob.numel())))
+            blobs = [blob] + [blob.clone() for _ in range(copies - 1)]
+            X = torch.randn((M, K), device="cuda", generator=gen)
+            Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+            ws = qg.new_workspace(qg.qg_workspace_bytes(N, K, cfg.bits, cfg.group, M))
+            for i in range(warm):
+                qg.qg_gemm_small(blobs[i % copies], N, K, cfg.bits, cfg.group, X, Y, ws)
+            torch.cuda.synchronize()
+            start.record()
+            for i in range(steps):
+                qg.qg_gemm_small(blobs[i % copies], N, K, cfg.bits, cfg.group, X, Y, ws)
+            stop.record()
+            torch.cuda.synchronize()
+            us = start.elapsed_time(stop) / steps * 1e3
+            byts = (cfg.bits * N * K + (32 + cfg.bits) * N * (K // cfg.group)) // 8 + 4 * M * K + 4 * M * N
+            rows.append({"N": N, "K": K, "bits": cfg.bits, "group": cfg.group, "M": M, "us": round(us, 2),
+                         "GBps": round(byts / us / 1e3, 1), "frac_of_hbm_peak": round(byts / us / 1e3 / HBM_PEAK_GBS, 4)})
+            del blobs, blob
+    return rows
+
+
+def bench_stacked_qkv(qg, args):
+    """q, k and v of a 7B-shaped block (4-bit, group 128) as ONE 3H x H product against the same
+    three products as problems of one grouped launch (timing only), packed copies rotated."""
+    H, bits, group = 4096, 4, 128
+    gen = torch.Generator(device="cuda").manual_seed(300)
+    W3 = torch.randn((3 * H, H), device="cuda", generator=gen) * 0.02
+    x = torch.randn((H,), device="cuda", generator=gen)
+    q, s, z = qg.qg_quantize(W3, bits, group)
+    stacked = qg.qg_pack(q, s, z, bits, group)
+    parts = [qg.qg_pack(q[i * H:(i + 1) * H].contiguous(), s[i * H:(i + 1) * H].contiguous(),
+                        z[i * H:(i + 1) * H].contiguous(), bits, group) for i in range(3)]
+    del W3, q, s, z
+    copies = max(2, int(np.ceil(ROTATE_BYTES / stacked.numel())))
+    one, three = [], []
+    for c in range(copies):
+        one.append(qg.GroupedGemv([dict(packed=stacked.clone(), N=3 * H, K=H, bits=bits, group=group, x=x,
+                                        y=torch.empty(3 * H, dtype=torch.float32, device="cuda"))]))
+        three.append(qg.GroupedGemv([dict(packed=p.clone(), N=H, K=H, bits=bits, group=group, x=x,
+                                          y=torch.empty(H, dtype=torch.float32, device="cuda")) for p in parts]))
+    steps, warm = max(20, args.steps // 4), max(5, args.warmup // 4)
+    return {"workload": "q/k/v of a 7B-shaped block, 4-bit group 128: one 12288 x 4096 product / three 4096 x 4096 problems in one launch",
+            "one_stacked_product_us": round(time_launches(one, steps, warm), 3),
+            "three_grouped_problems_us": round(time_launches(three, steps, warm), 3)}
 
 
 def main():
@@ -457,8 +520,10 @@ def main():
                      "traffic": traffic, "traffic_source": traffic_source},
     }
     if tuned is not None:
+        _, timed, dropped = qg.qg_gemv_autotune_report()
         out["autotuned"] = {"waves_per_block": tuned[0], "bytes_per_wave": tuned[1], "kernel": tuned[2],
-                            "us_while_tuning": round(tuned[3], 3)}
+                            "us_while_tuning": round(tuned[3], 3), "candidates_timed": timed,
+                            "candidates_dropped_by_the_resource_budget": dropped}
     failed = False
     if not args.no_cpu_baseline:
         out["cpu_baseline"], err = cpu_baseline(cfg, base, timed_y)

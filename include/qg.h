@@ -196,18 +196,28 @@ int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel);
  * process used (its last launch, if the call made several), e.g. "gemv_mma4i<4, 16>"; "" before
  * the first launch.  HOST string owned by the library.  For benchmark reports. */
 const char *qg_last_gemv_kernel(void);
-/* Search for the fastest launch shape of one grouped launch by timing -- this machine's
- * counterpart of the paper's parameter search (Section 3, Algorithm 4).  `descs` holds `sets`
- * copies of the launch back to back (set i at descs + i * count; same shapes, normally
- * different packed buffers, so that a cache cannot serve the weights; sets = 1 times one set
- * again and again).  Runs the launch `repeats` times, rotating over the sets, for each of 168
- * candidates (team size x bytes per wavefront x vector-ALU or one of the three matrix-core kernels), WAITS for
- * the GPU (the only call that does), leaves the fastest installed as qg_set_gemv_tuning would,
- * and reports it (HOST pointers, each may be NULL; best_us = microseconds per launch).  The
- * outputs y are overwritten as by qg_gemv_grouped; all sets share the workspace. */
+/* Search for the fastest launch shape of one grouped launch -- this machine's counterpart of the
+ * paper's parameter search (Section 3, Algorithm 4 with the resource model of eqs. (3)-(5)).
+ * `descs` holds `sets` copies of the launch back to back (set i at descs + i * count; same
+ * shapes, normally different packed buffers, so that a cache cannot serve the weights; sets = 1
+ * times one set again and again).  Each of the 168 candidates (team size x bytes per wavefront x
+ * vector-ALU or one of the three matrix-core kernels) is first priced against the machine's
+ * budget: registers per lane and LDS per workgroup of its kernel instance bound the wavefronts a
+ * compute unit holds, and those times the bytes a wavefront keeps requested must cover the
+ * memory system's round trip (8 TB/s x 1.5 us / compute units; for launches too small to get
+ * there, half of what the best candidate reaches).  Candidates below that are dropped; the
+ * others run the launch `repeats` times, rotating over the sets.  The call WAITS for the GPU
+ * (the only one that does), leaves the fastest installed as qg_set_gemv_tuning would, and
+ * reports it (HOST pointers, each may be NULL; best_us = microseconds per launch).  The outputs
+ * y are overwritten as by qg_gemv_grouped; all sets share the workspace. */
 int qg_gemv_autotune(const qg_gemv_desc *descs /* HOST */, int count, int sets,
                      void *workspace, size_t workspace_bytes, void *stream, int repeats,
                      int *waves_per_block, int *bytes_per_wave, int *kernel, float *best_us);
+/* What the last qg_gemv_autotune did: us[c] (HOST, `capacity` >= 168 entries, may be NULL) =
+ * microseconds per launch of candidate c, or -1 if the budget dropped it, with
+ * c = ((kernel - 1) * 6 + team index) * 7 + size index over teams {0, 2, 4, 8, 12, 16} and
+ * bytes per wavefront {0, 4096, 8192, 16384, 32768, 49152, 65536}; and the two counts. */
+int qg_gemv_autotune_report(float *us /* HOST */, int capacity, int *timed, int *dropped);
 
 /* Same for qg_gemm_small: splits in 1..8 = number of K ranges handled by different
  * workgroups (clamped to what the shape allows); shape in 1..12 = workgroup shape (how many

@@ -79,6 +79,8 @@ def lib():
         L.qg_gemv_autotune.argtypes = [ctypes.POINTER(_Desc), i32, i32, vp, sz, vp, i32,
                                        ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32),
                                        ctypes.POINTER(ctypes.c_float)]
+        L.qg_gemv_autotune_report.restype = i32
+        L.qg_gemv_autotune_report.argtypes = [ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.qg_set_gemm_tuning.restype = i32
         L.qg_set_gemm_tuning.argtypes = [i32, i32]
         _LIB = L
@@ -278,6 +280,19 @@ def qg_gemv_autotune(launches, repeats: int = 20):
                                   ctypes.byref(w), ctypes.byref(b), ctypes.byref(k), ctypes.byref(us)),
            "qg_gemv_autotune")
     return w.value, b.value, k.value, us.value
+
+
+AUTOTUNE_TEAMS = (0, 2, 4, 8, 12, 16)
+AUTOTUNE_SIZES = (0, 4096, 8192, 16384, 32768, 49152, 65536)
+
+
+def qg_gemv_autotune_report():
+    """(microseconds per candidate, -1 where the budget dropped it; number timed; number dropped)
+    of the last qg_gemv_autotune.  Candidate ((kernel - 1) * 6 + team index) * 7 + size index."""
+    us = (ctypes.c_float * 168)()
+    timed, dropped = ctypes.c_int(), ctypes.c_int()
+    _check(lib().qg_gemv_autotune_report(us, 168, ctypes.byref(timed), ctypes.byref(dropped)), "qg_gemv_autotune_report")
+    return list(us), timed.value, dropped.value
 
 
 def qg_set_gemm_tuning(splits: int = 0, shape: int = 0):

@@ -1665,88 +1665,110 @@ FirstBlocks first_blocks(const GemvArgs &A)
     return f;
 }
 
-template <int BITS>
-bool launch_static(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A, bool dry)
-{
-    if (!(cpg == 1 || cpg == 2 || cpg == 4 || cpg == 8 || (cpg == 16 && BITS != 3))) return false;
-    if (dry) return true;
-    switch (cpg) {
-    case 1: hipLaunchKernelGGL((gemv_static<BITS, 1>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
-    case 2: hipLaunchKernelGGL((gemv_static<BITS, 2>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
-    case 4: hipLaunchKernelGGL((gemv_static<BITS, 4>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
-    case 8: hipLaunchKernelGGL((gemv_static<BITS, 8>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
-    case 16:
-        if constexpr (BITS != 3)
-            hipLaunchKernelGGL((gemv_static<BITS, 16>), dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
-        break;
-    }
-    return true;
-}
+// Every GEMV kernel has the same signature; the host picks an instance and launches it through
+// a pointer, so that the planner can also ask the runtime what the instance needs (registers,
+// LDS) without launching it.
+typedef void (*GemvKernel)(qg_v4i, qg_v4i, qg_v4i, GemvArgs);
 
-template <int BITS>
-bool launch_mma(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A, bool dry)
+void launch_kernel(GemvKernel fn, unsigned blocks, unsigned threads, size_t lds, hipStream_t st, const GemvArgs &A)
 {
-    if (!(cpg == 2 || cpg == 4 || cpg == 8 || (cpg == 16 && BITS != 3))) return false;
-    if (dry) return true;
-    // x of one step in three bf16 parts, two buffers, per wavefront
-    const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 3 * codes_per_step<BITS>() * sizeof(uint16_t);
-    switch (cpg) {
-    case 2: hipLaunchKernelGGL((gemv_mma<BITS, 2>), dim3(blocks), dim3(threads), lds, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
-    case 4: hipLaunchKernelGGL((gemv_mma<BITS, 4>), dim3(blocks), dim3(threads), lds, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
-    case 8: hipLaunchKernelGGL((gemv_mma<BITS, 8>), dim3(blocks), dim3(threads), lds, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A); break;
-    case 16:
-        if constexpr (BITS != 3)
-            hipLaunchKernelGGL((gemv_mma<BITS, 16>), dim3(blocks), dim3(threads), lds, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
-        break;
-    }
-    return true;
-}
-
-// gemv_mma4: cpg = cells per group, 0 for groups of whole steps
-template <int BITS>
-bool launch_mma4(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A, bool dry)
-{
-    if (!(cpg == 0 || cpg == 1 || cpg == 2 || cpg == 4 || cpg == 8 || (cpg == 16 && BITS != 3))) return false;
-    if (dry) return true;
-    const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 4 * (codes_per_step<BITS>() + 8) * sizeof(uint16_t);
     const FirstBlocks f = first_blocks(A);
-    switch (cpg) {
-    case 0: hipLaunchKernelGGL((gemv_mma4<BITS, 0>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
-    case 1: hipLaunchKernelGGL((gemv_mma4<BITS, 1>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
-    case 2: hipLaunchKernelGGL((gemv_mma4<BITS, 2>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
-    case 4: hipLaunchKernelGGL((gemv_mma4<BITS, 4>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
-    case 8: hipLaunchKernelGGL((gemv_mma4<BITS, 8>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
-    case 16:
-        if constexpr (BITS != 3)
-            hipLaunchKernelGGL((gemv_mma4<BITS, 16>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A);
-        break;
-    }
-    return true;
+    hipLaunchKernelGGL(fn, dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A);
 }
 
 template <int BITS>
-bool launch_mma4i(int cpg, unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A, bool dry)
+GemvKernel pick_static(int cpg)
 {
-    if (!(cpg == 0 || (cpg == 1 && BITS != 4) || cpg == 2 || cpg == 4 || cpg == 8 || (cpg == 16 && BITS != 3))) return false;
-    if (dry) return true;
-    const size_t lds = (size_t)(threads / QG_WAVE) * 2 * 4 * (codes_per_step<BITS>() + 16);
-    const FirstBlocks f = first_blocks(A);
     switch (cpg) {
-    case 0: hipLaunchKernelGGL((gemv_mma4i<BITS, 0>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
+    case 1: return gemv_static<BITS, 1>;
+    case 2: return gemv_static<BITS, 2>;
+    case 4: return gemv_static<BITS, 4>;
+    case 8: return gemv_static<BITS, 8>;
+    case 16:
+        if constexpr (BITS != 3) return gemv_static<BITS, 16>;
+        return nullptr;
+    default: return nullptr;
+    }
+}
+
+template <int BITS>
+GemvKernel pick_mma(int cpg)
+{
+    switch (cpg) {
+    case 2: return gemv_mma<BITS, 2>;
+    case 4: return gemv_mma<BITS, 4>;
+    case 8: return gemv_mma<BITS, 8>;
+    case 16:
+        if constexpr (BITS != 3) return gemv_mma<BITS, 16>;
+        return nullptr;
+    default: return nullptr;
+    }
+}
+
+// gemv_mma4 / gemv_mma4i: cpg = cells per group, 0 for groups of whole steps
+template <int BITS>
+GemvKernel pick_mma4(int cpg)
+{
+    switch (cpg) {
+    case 0: return gemv_mma4<BITS, 0>;
+    case 1: return gemv_mma4<BITS, 1>;
+    case 2: return gemv_mma4<BITS, 2>;
+    case 4: return gemv_mma4<BITS, 4>;
+    case 8: return gemv_mma4<BITS, 8>;
+    case 16:
+        if constexpr (BITS != 3) return gemv_mma4<BITS, 16>;
+        return nullptr;
+    default: return nullptr;
+    }
+}
+
+template <int BITS>
+GemvKernel pick_mma4i(int cpg)
+{
+    switch (cpg) {
+    case 0: return gemv_mma4i<BITS, 0>;
     case 1:
-        if constexpr (BITS != 4)
-            hipLaunchKernelGGL((gemv_mma4i<BITS, 1>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A);
-        break;
-    case 2: hipLaunchKernelGGL((gemv_mma4i<BITS, 2>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
-    case 4: hipLaunchKernelGGL((gemv_mma4i<BITS, 4>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
-    case 8: hipLaunchKernelGGL((gemv_mma4i<BITS, 8>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A); break;
+        if constexpr (BITS != 4) return gemv_mma4i<BITS, 1>;
+        return nullptr;
+    case 2: return gemv_mma4i<BITS, 2>;
+    case 4: return gemv_mma4i<BITS, 4>;
+    case 8: return gemv_mma4i<BITS, 8>;
     case 16:
-        if constexpr (BITS != 3)
-            hipLaunchKernelGGL((gemv_mma4i<BITS, 16>), dim3(blocks), dim3(threads), lds, st, f.a, f.b, f.c, A);
-        break;
+        if constexpr (BITS != 3) return gemv_mma4i<BITS, 16>;
+        return nullptr;
+    default: return nullptr;
     }
-    return true;
 }
+
+template <int CPG> GemvKernel pick_rows16() { return gemm_rows16<CPG>; }
+
+// dynamic LDS of the matrix-core kernels: the x of a step per wavefront and buffer
+size_t lds_mma(int bits, unsigned threads)      // three bf16 parts
+{
+    const size_t S = bits == 4 ? 128 : 256;
+    return (size_t)(threads / QG_WAVE) * 2 * 3 * S * sizeof(uint16_t);
+}
+size_t lds_mma4(int bits, unsigned threads)     // three bf16 parts and a part of zeros
+{
+    const size_t S = bits == 4 ? 128 : 256;
+    return (size_t)(threads / QG_WAVE) * 2 * 4 * (S + 8) * sizeof(uint16_t);
+}
+size_t lds_mma4i(int bits, unsigned threads)    // four rows of int8 digits
+{
+    const size_t S = bits == 4 ? 128 : 256;
+    return (size_t)(threads / QG_WAVE) * 2 * 4 * (S + 16);
+}
+size_t lds_rows16(unsigned threads) { return (size_t)(threads / QG_WAVE) * 16 * (128 + 8) * sizeof(uint16_t); }
+
+// What a planned launch looks like to the machine: filled by launch_class for the search over
+// launch shapes, which prices candidates before it times them.
+struct LaunchShape {
+    const void *kernel;
+    unsigned threads, blocks;
+    size_t lds_dynamic;
+    long waves;                 // wavefronts with work
+    size_t bytes_in_flight;     // packed bytes one wavefront has requested while it computes
+};
 
 // Which kernel multiplies: the vector ALU (gemv_static / gemv_runtime), the 32 x 32 x 16 matrix
 // instruction (gemv_mma, groups of at least two cells inside a step), or the 4 x 4 x 4 one on
@@ -1771,20 +1793,13 @@ Mul multiplier(int bits, int cpg, Kind kind, size_t code_bytes)
 }
 
 // One launch for problems that share (bits, group, kernel kind).
-template <int CPG>
-void launch_rows16(unsigned blocks, unsigned threads, hipStream_t st, const GemvArgs &A)
-{
-    const size_t lds = (size_t)(threads / QG_WAVE) * 16 * (codes_per_step<4>() + 8) * sizeof(uint16_t);
-    hipLaunchKernelGGL((gemm_rows16<CPG>), dim3(blocks), dim3(threads), lds, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
-}
-
 // rows > 0: the problems are products with `rows` <= 16 activation rows (x = X [rows][K],
 // y = Y [rows][N]) for gemm_rows16; the caller has checked that the kernel applies.
 // dry: plan and check only -- returns the status the launch would have up to the point where
 // the kernel is enqueued, and enqueues nothing.
 int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const size_t *ws_off,
                  char *workspace, hipStream_t st, const int64_t *gate_rows, float *const *gated,
-                 int rows = 0, bool dry = false)
+                 int rows = 0, bool dry = false, LaunchShape *report = nullptr)
 {
     GemvArgs A;
     A.count = count;
@@ -1952,58 +1967,73 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
 
     const unsigned threads = (unsigned)wpb * QG_WAVE;
     const int bits = L[0].bits;
-    if (!dry) {
-        const int cpg = L[0].group / L[0].cell;
-        const char *family = rows > 0 ? "gemm_rows16" : kind == KIND_GENERIC ? "gemv_generic"
-                           : mul == MUL_MMA4I ? "gemv_mma4i" : mul == MUL_MMA4 ? "gemv_mma4"
-                           : mul == MUL_MMA32 ? "gemv_mma" : kind == KIND_STATIC ? "gemv_static" : "gemv_runtime";
-        if (kind == KIND_STATIC || rows > 0) snprintf(g_last_kernel, sizeof g_last_kernel, "%s<%d, %d>", family, bits, cpg);
-        else if (kind == KIND_RUNTIME && mul != MUL_VALU) snprintf(g_last_kernel, sizeof g_last_kernel, "%s<%d, 0>", family, bits);
-        else snprintf(g_last_kernel, sizeof g_last_kernel, "%s<%d>", family, bits);
-    }
+    const int cpg = L[0].group / L[0].cell;
+    GemvKernel fn = nullptr;
+    size_t lds = 0;
+    const char *family;
+    int shown_cpg = cpg;
     if (rows > 0) {
-        if (dry) return QG_OK;
-        switch (L[0].group / L[0].cell) {
-        case 2: launch_rows16<2>(blocks, threads, st, A); break;
-        case 4: launch_rows16<4>(blocks, threads, st, A); break;
-        case 8: launch_rows16<8>(blocks, threads, st, A); break;
-        default: launch_rows16<16>(blocks, threads, st, A); break;
-        }
+        family = "gemm_rows16";
+        fn = cpg == 2 ? pick_rows16<2>() : cpg == 4 ? pick_rows16<4>() : cpg == 8 ? pick_rows16<8>() : pick_rows16<16>();
+        lds = lds_rows16(threads);
     } else if (kind == KIND_STATIC) {
-        const int cpg = L[0].group / L[0].cell;
-        bool launched;
-        if (mul == MUL_MMA4I)
-            launched = bits == 4 ? launch_mma4i<4>(cpg, blocks, threads, st, A, dry)
-                     : bits == 2 ? launch_mma4i<2>(cpg, blocks, threads, st, A, dry) : launch_mma4i<3>(cpg, blocks, threads, st, A, dry);
-        else if (mul == MUL_MMA4)
-            launched = bits == 4 ? launch_mma4<4>(cpg, blocks, threads, st, A, dry)
-                     : bits == 2 ? launch_mma4<2>(cpg, blocks, threads, st, A, dry) : launch_mma4<3>(cpg, blocks, threads, st, A, dry);
-        else if (mul == MUL_MMA32)
-            launched = bits == 4 ? launch_mma<4>(cpg, blocks, threads, st, A, dry)
-                     : bits == 2 ? launch_mma<2>(cpg, blocks, threads, st, A, dry) : launch_mma<3>(cpg, blocks, threads, st, A, dry);
-        else
-            launched = bits == 4 ? launch_static<4>(cpg, blocks, threads, st, A, dry)
-                     : bits == 2 ? launch_static<2>(cpg, blocks, threads, st, A, dry) : launch_static<3>(cpg, blocks, threads, st, A, dry);
-        if (!launched) return QG_ERR_UNSUPPORTED;      // no kernel was built for this group size
-        if (dry) return QG_OK;
-    } else if (dry) {
-        return QG_OK;
+        if (mul == MUL_MMA4I) {
+            family = "gemv_mma4i";
+            fn = bits == 4 ? pick_mma4i<4>(cpg) : bits == 2 ? pick_mma4i<2>(cpg) : pick_mma4i<3>(cpg);
+            lds = lds_mma4i(bits, threads);
+        } else if (mul == MUL_MMA4) {
+            family = "gemv_mma4";
+            fn = bits == 4 ? pick_mma4<4>(cpg) : bits == 2 ? pick_mma4<2>(cpg) : pick_mma4<3>(cpg);
+            lds = lds_mma4(bits, threads);
+        } else if (mul == MUL_MMA32) {
+            family = "gemv_mma";
+            fn = bits == 4 ? pick_mma<4>(cpg) : bits == 2 ? pick_mma<2>(cpg) : pick_mma<3>(cpg);
+            lds = lds_mma(bits, threads);
+        } else {
+            family = "gemv_static";
+            fn = bits == 4 ? pick_static<4>(cpg) : bits == 2 ? pick_static<2>(cpg) : pick_static<3>(cpg);
+        }
+        if (!fn) return QG_ERR_UNSUPPORTED;            // no kernel was built for this group size
     } else if (kind == KIND_RUNTIME && mul == MUL_MMA4I) {
-        if (bits == 2) launch_mma4i<2>(0, blocks, threads, st, A, false);
-        else if (bits == 3) launch_mma4i<3>(0, blocks, threads, st, A, false);
-        else launch_mma4i<4>(0, blocks, threads, st, A, false);
+        family = "gemv_mma4i";
+        shown_cpg = 0;
+        fn = bits == 2 ? pick_mma4i<2>(0) : bits == 3 ? pick_mma4i<3>(0) : pick_mma4i<4>(0);
+        lds = lds_mma4i(bits, threads);
     } else if (kind == KIND_RUNTIME && mul == MUL_MMA4) {
-        if (bits == 2) launch_mma4<2>(0, blocks, threads, st, A, false);
-        else launch_mma4<3>(0, blocks, threads, st, A, false);
+        family = "gemv_mma4";
+        shown_cpg = 0;
+        fn = bits == 2 ? pick_mma4<2>(0) : pick_mma4<3>(0);
+        lds = lds_mma4(bits, threads);
     } else if (kind == KIND_RUNTIME) {
-        if (bits == 4) hipLaunchKernelGGL(gemv_runtime<4>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
-        else if (bits == 2) hipLaunchKernelGGL(gemv_runtime<2>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
-        else hipLaunchKernelGGL(gemv_runtime<3>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
+        family = "gemv_runtime";
+        shown_cpg = -1;
+        fn = bits == 4 ? gemv_runtime<4> : bits == 2 ? gemv_runtime<2> : gemv_runtime<3>;
     } else {
-        if (bits == 4) hipLaunchKernelGGL(gemv_generic<4>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
-        else if (bits == 2) hipLaunchKernelGGL(gemv_generic<2>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
-        else hipLaunchKernelGGL(gemv_generic<3>, dim3(blocks), dim3(threads), 0, st, first_blocks(A).a, first_blocks(A).b, first_blocks(A).c, A);
+        family = "gemv_generic";
+        shown_cpg = -1;
+        fn = bits == 4 ? gemv_generic<4> : bits == 2 ? gemv_generic<2> : gemv_generic<3>;
     }
+    if (report) {
+        report->kernel = (const void *)fn;
+        report->threads = threads;
+        report->blocks = (unsigned)blocks;
+        report->lds_dynamic = lds;
+        long waves = 0;
+        size_t in_flight = 0;
+        for (int i = 0; i < count; ++i) {
+            const int64_t per_tile = (pl[i].items + spw_of[i] - 1) / spw_of[i];
+            waves += (long)(L[i].tiles * per_tile);
+            // two register buffers: the step being computed has arrived, the next one is in flight
+            const size_t mine = (size_t)(spw_of[i] > 1 ? 2 : 1) * pl[i].item_bytes;
+            if (mine > in_flight) in_flight = mine;
+        }
+        report->waves = waves;
+        report->bytes_in_flight = in_flight;
+    }
+    if (dry) return QG_OK;
+    if (shown_cpg >= 0) snprintf(g_last_kernel, sizeof g_last_kernel, "%s<%d, %d>", family, bits, shown_cpg);
+    else snprintf(g_last_kernel, sizeof g_last_kernel, "%s<%d>", family, bits);
+    launch_kernel(fn, (unsigned)blocks, threads, lds, st, A);
     return qg_launch_status();
 }
 
@@ -2045,7 +2075,8 @@ extern "C" int qg_workspace_init(void *workspace, size_t bytes, void *stream)
 // pair (0 / unused for a plain product); both NULL for plain launches.
 // check_only: argument checks and planning, nothing enqueued.
 static int gemv_grouped(const qg_gemv_desc *descs, int count, void *workspace, size_t workspace_bytes,
-                        void *stream, const int64_t *gate_rows, float *const *gated, bool check_only = false)
+                        void *stream, const int64_t *gate_rows, float *const *gated, bool check_only = false,
+                        LaunchShape *report = nullptr)       // report: the shape of the call's largest launch
 {
     if (!descs) return QG_ERR_NULL;
     if (count <= 0) return QG_ERR_SHAPE;
@@ -2092,9 +2123,11 @@ static int gemv_grouped(const qg_gemv_desc *descs, int count, void *workspace, s
                 for (int b = a; b > 0 && descs[idx[b]].K > descs[idx[b - 1]].K; --b) {
                     const int t = idx[b]; idx[b] = idx[b - 1]; idx[b - 1] = t;
                 }
+            LaunchShape shape;
             const int rc = launch_class(descs, idx, n, ws_off, (char *)workspace, (hipStream_t)stream,
-                                        gate_rows, gated, 0, pass == 0);
+                                        gate_rows, gated, 0, pass == 0, report ? &shape : nullptr);
             if (rc != QG_OK) return rc;
+            if (report && pass == 0 && (i == 0 || shape.waves > report->waves)) *report = shape;
         }
     }
     return QG_OK;
@@ -2232,11 +2265,58 @@ extern "C" int qg_gemv(const void *packed, int64_t N, int64_t K, int bits, int g
     return qg_gemv_grouped(&d, 1, workspace, workspace_bytes, stream);
 }
 
-// Empirical choice of the launch shape for one grouped launch: the counterpart of the paper's
-// parameter search (Section 3, Algorithm 4 with the model of eqs. (3)-(5)), done by timing
-// instead of by a cache model.  Every candidate (team size, bytes per wavefront, vector-ALU or
-// matrix-core kernel) runs the launch a few times between two events; the fastest is left
-// installed as with qg_set_gemv_tuning.  Unlike every other call this one waits for the GPU.
+// Choice of the launch shape for one grouped launch: the counterpart of the paper's parameter
+// search (Section 3, Algorithm 4 with the model of eqs. (3)-(5)).  The paper bounds its block
+// sizes by what the cache and the register file hold; here a candidate (team size, bytes per
+// wavefront, kernel) is first priced against this machine's budget -- the registers per lane
+// and the LDS per workgroup of the kernel instance give the wavefronts a compute unit can hold,
+// those times the bytes a wavefront keeps requested give the bytes in flight per unit, and a
+// candidate that cannot keep the memory system's round trip covered is dropped -- and only the
+// survivors are timed; the fastest is left installed as with qg_set_gemv_tuning.  Unlike every
+// other call this one waits for the GPU.
+namespace {
+constexpr int AT_TEAMS[] = {0, 2, 4, 8, 12, 16};
+constexpr int AT_SIZES[] = {0, 4096, 8192, 16384, 32768, 49152, 65536};
+constexpr int AT_NT = sizeof(AT_TEAMS) / sizeof(AT_TEAMS[0]), AT_NS = sizeof(AT_SIZES) / sizeof(AT_SIZES[0]);
+constexpr int AT_CANDIDATES = 4 * AT_NT * AT_NS;
+float g_at_us[AT_CANDIDATES];        // microseconds per launch; -1: dropped by the budget
+int g_at_timed = 0, g_at_dropped = 0;
+
+constexpr double AT_HBM_BYTES_PER_S = 8e12;      // MI355X peak
+constexpr double AT_ROUND_TRIP_S = 1.5e-6;       // a request's way to HBM and back under load (measured)
+constexpr size_t AT_LDS_PER_CU = 160 * 1024;
+constexpr int AT_VGPRS_PER_SIMD = 512, AT_MAX_WAVES_PER_SIMD = 8;
+
+// Wavefronts of this kernel instance one compute unit can hold.
+int resident_waves_per_cu(const LaunchShape &sh)
+{
+    hipFuncAttributes attr;
+    if (hipFuncGetAttributes(&attr, sh.kernel) != hipSuccess) {
+        (void)hipGetLastError();
+        return 4 * AT_MAX_WAVES_PER_SIMD;
+    }
+    const int waves_per_wg = (int)(sh.threads / QG_WAVE);
+    const int regs = ((attr.numRegs > 0 ? attr.numRegs : 64) + 7) / 8 * 8;       // allocated in blocks of 8
+    int per_simd = AT_VGPRS_PER_SIMD / regs;
+    if (per_simd > AT_MAX_WAVES_PER_SIMD) per_simd = AT_MAX_WAVES_PER_SIMD;
+    if (per_simd < 1) per_simd = 1;
+    int wgs = per_simd * 4 / waves_per_wg;                    // a workgroup's wavefronts are dealt over the four SIMDs
+    const size_t lds = attr.sharedSizeBytes + sh.lds_dynamic;
+    if (lds > 0 && (int)(AT_LDS_PER_CU / lds) < wgs) wgs = (int)(AT_LDS_PER_CU / lds);
+    if (wgs < 1) wgs = 1;
+    return wgs * waves_per_wg;
+}
+
+// Packed bytes the launch keeps requested per compute unit while it streams.
+double bytes_in_flight_per_cu(const LaunchShape &sh)
+{
+    const int cus = qg_compute_units();
+    const long share = (sh.waves + cus - 1) / cus;            // wavefronts the launch has per unit
+    const int resident = resident_waves_per_cu(sh);
+    return (double)(share < resident ? share : resident) * (double)sh.bytes_in_flight;
+}
+}  // namespace
+
 extern "C" int qg_gemv_autotune(const qg_gemv_desc *descs, int count, int sets, void *workspace,
                                 size_t workspace_bytes, void *stream, int repeats,
                                 int *waves_per_block, int *bytes_per_wave, int *kernel,
@@ -2246,52 +2326,90 @@ extern "C" int qg_gemv_autotune(const qg_gemv_desc *descs, int count, int sets, 
     if (!descs) return QG_ERR_NULL;
     hipStream_t st = (hipStream_t)stream;
     const int saved[3] = {g_tune_wpb, g_tune_bytes_per_wave, g_tune_kernel};
+    auto restore = [&]() { g_tune_wpb = saved[0]; g_tune_bytes_per_wave = saved[1]; g_tune_kernel = saved[2]; };
     int rc = QG_OK;
     for (int s = 0; s < sets && rc == QG_OK; ++s)                                  // argument checks
-        rc = qg_gemv_grouped(descs + (size_t)s * count, count, workspace, workspace_bytes, stream);
+        rc = gemv_grouped(descs + (size_t)s * count, count, workspace, workspace_bytes, stream, nullptr, nullptr, true);
     if (rc != QG_OK) return rc;
+
+    // 1. price every candidate: plan it (nothing is launched) and ask what its kernel instance needs
+    double in_flight[AT_CANDIDATES], most = 0.0;
+    for (int c = 0; c < AT_CANDIDATES && rc == QG_OK; ++c) {
+        g_tune_kernel = 1 + c / (AT_NT * AT_NS);
+        g_tune_wpb = AT_TEAMS[(c / AT_NS) % AT_NT];
+        g_tune_bytes_per_wave = AT_SIZES[c % AT_NS];
+        LaunchShape sh;
+        rc = gemv_grouped(descs, count, workspace, workspace_bytes, stream, nullptr, nullptr, true, &sh);
+        if (rc != QG_OK) break;
+        in_flight[c] = bytes_in_flight_per_cu(sh);
+        if (in_flight[c] > most) most = in_flight[c];
+    }
+    if (rc != QG_OK) { restore(); return rc; }
+    // what a unit has to keep requested to cover the round trip at the peak rate; a launch too
+    // small to get there anyway is held to half of what its best candidate reaches
+    double need = AT_HBM_BYTES_PER_S * AT_ROUND_TRIP_S / qg_compute_units();
+    if (need > 0.5 * most) need = 0.5 * most;
+
+    // 2. time the survivors
     int turn = 0;
     auto run = [&]() {
         const qg_gemv_desc *d = descs + (size_t)(turn++ % sets) * count;
         return qg_gemv_grouped(d, count, workspace, workspace_bytes, stream);
     };
     hipEvent_t e0, e1;
-    if (hipEventCreate(&e0) != hipSuccess) return QG_ERR_DEVICE;
-    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return QG_ERR_DEVICE; }
-    static const int teams[] = {0, 2, 4, 8, 12, 16};
-    static const int sizes[] = {0, 4096, 8192, 16384, 32768, 49152, 65536};
-    constexpr int n_teams = sizeof(teams) / sizeof(teams[0]), n_sizes = sizeof(sizes) / sizeof(sizes[0]);
-    int best[3] = {0, 0, 0};
+    if (hipEventCreate(&e0) != hipSuccess) { restore(); return QG_ERR_DEVICE; }
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); restore(); return QG_ERR_DEVICE; }
+    int best = -1;
     float best_ms = -1.0f;
-    for (int k = 1; k <= 4 && rc == QG_OK; ++k)
-        for (int a = 0; a < n_teams && rc == QG_OK; ++a)
-            for (int b = 0; b < n_sizes && rc == QG_OK; ++b) {
-                g_tune_wpb = teams[a];
-                g_tune_bytes_per_wave = sizes[b];
-                g_tune_kernel = k;
-                for (int i = 0; i < 2 && rc == QG_OK; ++i) rc = run();
-                if (rc != QG_OK) break;
-                if (hipEventRecord(e0, st) != hipSuccess) { rc = QG_ERR_DEVICE; break; }
-                for (int i = 0; i < repeats && rc == QG_OK; ++i) rc = run();
-                if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) rc = QG_ERR_DEVICE;
-                float ms = 0.0f;
-                if (rc == QG_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = QG_ERR_DEVICE;
-                if (rc == QG_OK && (best_ms < 0.0f || ms < best_ms)) {
-                    best_ms = ms;
-                    best[0] = teams[a]; best[1] = sizes[b]; best[2] = k;
-                }
-            }
+    g_at_timed = 0;
+    g_at_dropped = 0;
+    for (int c = 0; c < AT_CANDIDATES && rc == QG_OK; ++c) {
+        if (in_flight[c] < need) {
+            g_at_us[c] = -1.0f;
+            ++g_at_dropped;
+            continue;
+        }
+        g_tune_kernel = 1 + c / (AT_NT * AT_NS);
+        g_tune_wpb = AT_TEAMS[(c / AT_NS) % AT_NT];
+        g_tune_bytes_per_wave = AT_SIZES[c % AT_NS];
+        for (int i = 0; i < 2 && rc == QG_OK; ++i) rc = run();
+        if (rc != QG_OK) break;
+        if (hipEventRecord(e0, st) != hipSuccess) { rc = QG_ERR_DEVICE; break; }
+        for (int i = 0; i < repeats && rc == QG_OK; ++i) rc = run();
+        if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) rc = QG_ERR_DEVICE;
+        float ms = 0.0f;
+        if (rc == QG_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = QG_ERR_DEVICE;
+        if (rc != QG_OK) break;
+        g_at_us[c] = ms * 1e3f / (float)repeats;
+        ++g_at_timed;
+        if (best < 0 || ms < best_ms) {
+            best_ms = ms;
+            best = c;
+        }
+    }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
-    if (rc != QG_OK) {
-        g_tune_wpb = saved[0]; g_tune_bytes_per_wave = saved[1]; g_tune_kernel = saved[2];
-        return rc;
+    if (rc != QG_OK || best < 0) {
+        restore();
+        return rc != QG_OK ? rc : QG_ERR_DEVICE;
     }
-    g_tune_wpb = best[0]; g_tune_bytes_per_wave = best[1]; g_tune_kernel = best[2];
-    if (waves_per_block) *waves_per_block = best[0];
-    if (bytes_per_wave) *bytes_per_wave = best[1];
-    if (kernel) *kernel = best[2];
+    g_tune_kernel = 1 + best / (AT_NT * AT_NS);
+    g_tune_wpb = AT_TEAMS[(best / AT_NS) % AT_NT];
+    g_tune_bytes_per_wave = AT_SIZES[best % AT_NS];
+    if (waves_per_block) *waves_per_block = g_tune_wpb;
+    if (bytes_per_wave) *bytes_per_wave = g_tune_bytes_per_wave;
+    if (kernel) *kernel = g_tune_kernel;
     if (best_us) *best_us = best_ms * 1e3f / (float)repeats;
     return QG_OK;
 }
 
+extern "C" int qg_gemv_autotune_report(float *us, int capacity, int *timed, int *dropped)
+{
+    if (us) {
+        if (capacity < AT_CANDIDATES) return QG_ERR_SHAPE;
+        for (int c = 0; c < AT_CANDIDATES; ++c) us[c] = g_at_us[c];
+    }
+    if (timed) *timed = g_at_timed;
+    if (dropped) *dropped = g_at_dropped;
+    return QG_OK;
+}

@@ -497,6 +497,14 @@ def test_gemv_autotune_leaves_a_working_choice(qg, oracle):
     try:
         wpb, bpw, kernel, us = qg.qg_gemv_autotune([launch, twin], repeats=6)
         assert wpb in (0, 2, 4, 8, 12, 16) and bpw in (0, 4096, 8192, 16384, 32768, 49152, 65536) and kernel in (1, 2, 3, 4) and us > 0
+        # every candidate was either dropped by the resource budget or timed, and the installed
+        # one is the fastest of those that were timed
+        table, timed, dropped = qg.qg_gemv_autotune_report()
+        assert timed + dropped == 168 and timed >= 1
+        assert sum(1 for t in table if t > 0) == timed and sum(1 for t in table if t == -1.0) == dropped
+        chosen = ((kernel - 1) * 6 + qg.AUTOTUNE_TEAMS.index(wpb)) * 7 + qg.AUTOTUNE_SIZES.index(bpw)
+        assert table[chosen] > 0 and table[chosen] == min(t for t in table if t > 0)
+        assert abs(table[chosen] - us) <= 1e-3 * us
         for p in problems:
             p["y"].fill_(7.0)
         launch.launch()
