@@ -421,6 +421,9 @@ def main():
                     help="time the off-line steps (quantize, pack, unpack) instead")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of 256 MiB (reference for HBM byte counters)")
+    ap.add_argument("--gemm-shape", type=int, default=0,
+                    help="--config C5: workgroup shape / kernel of qg_gemm_small (qg_set_gemm_tuning); 13 = raw-code kernel")
+    ap.add_argument("--gemm-splits", type=int, default=0, help="--config C5: K ranges over workgroups (0 = built-in choice)")
     ap.add_argument("--wpb", type=int, default=0)
     ap.add_argument("--bytes-per-wave", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0, help="0 built-in choice, 1 vector-ALU GEMV, 2 matrix-core GEMV (32x32x16), 3 matrix-core GEMV (4x4x4, bf16), 4 matrix-core GEMV (4x4x4, int8)")
@@ -441,6 +444,7 @@ def main():
         print(json.dumps(bench_offline(qg, args)))
         return
     if args.config == "C5":
+        qg.qg_set_gemm_tuning(args.gemm_splits, args.gemm_shape)
         print(json.dumps(bench_gemm(cfg, qg, args)))
         return
     qg.qg_set_gemv_tuning(args.wpb, args.bytes_per_wave, args.kernel)
