@@ -1187,8 +1187,8 @@ int codes_cpg(const QgLayout &L)       // cells per group, 0 for groups of whole
 {
     const int S = L.unit * L.step_units, cells = 4 * L.step_units;
     if (L.K % 16 != 0 || L.K > (1 << 22)) return -1;
-    if (L.group % S == 0) return 0;
-    const int cpg = L.group / L.cell;
+    if (L.group % S == 0 && L.group > S) return 0;
+    const int cpg = L.group / L.cell;        // (a group of exactly one step closes at a compile-time position)
     if (L.group > S || cpg < 2 || cpg % 2 != 0 || cells % cpg != 0) return -1;
     return cpg;
 }
@@ -1289,7 +1289,9 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     // bits, group 128: within 0-20 % of the dequantizing kernels, behind mostly by the launch of
     // prepare_x; at 2 and 3 bits 2-15 times ahead of one GEMV per row.)
     const int cpg = codes_cpg(L);
-    if (cpg >= 0 && M > 1 && (g_tune_shape == NSHAPES + 1 || (g_tune_shape == 0 && !fast_path(L)))) {
+    // (... and, measured, 3-6 % ahead of them beyond 64 rows on the larger 7B shapes)
+    const bool large = M > 64 && L.tiles * L.steps >= 4096;
+    if (cpg >= 0 && M > 1 && (g_tune_shape == NSHAPES + 1 || (g_tune_shape == 0 && (!fast_path(L) || large)))) {
         const int mb = M <= 32 ? 1 : 2;
         const int kw = codes_kw(bits, mb), tn = 8 / kw;
         const int rows_per_block = 32 * mb;
