@@ -134,6 +134,12 @@ def bench_gemm(cfg, qg, args):
             Xd = torch.from_numpy(X).cuda()
             Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
             ws = qg.new_workspace(qg.qg_workspace_bytes(N, K, cfg.bits, cfg.group, M))
+            searched = None
+            if args.autotune:        # the launch-shape search, recorded for this problem; untimed
+                sp, sh, _ = qg.qg_gemm_autotune(blobs, N, K, cfg.bits, cfg.group, Xd, Y, ws, repeats=2 * copies)
+                _, n_timed, n_dropped = qg.qg_gemm_autotune_report()
+                searched = {"K_ranges": sp, "shape": sh, "candidates_timed": n_timed,
+                            "candidates_dropped_by_the_price": n_dropped}
             for i in range(warm):
                 qg.qg_gemm_small(blobs[i % copies], N, K, cfg.bits, cfg.group, Xd, Y, ws)
             torch.cuda.synchronize()
@@ -150,6 +156,8 @@ def bench_gemm(cfg, qg, args):
                          "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
                          "GBps": round(byts / us / 1e3, 1),
                          "frac_of_hbm_peak": round(byts / us / 1e3 / HBM_PEAK_GBS, 4)})
+            if searched:
+                rows[-1]["autotuned"] = searched
             total_us += us
         del blobs, blob
     top = max(rows, key=lambda r: r["TFLOPs"])
@@ -412,7 +420,8 @@ def main():
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="time the headline workload only")
     ap.add_argument("--autotune", action="store_true",
-                    help="let qg_gemv_autotune pick the launch shape (timed over the rotated copies) before the run")
+                    help="let qg_gemv_autotune (C5: qg_gemm_autotune per problem) pick the launch shape, timed over the "
+                         "rotated copies, before the run")
     ap.add_argument("--sweep-groups", type=lambda s: [int(v) for v in s.split(",")], default=[16, 32, 64, 128, 0],
                     help="group sizes of --sweep; 0 = one group per output")
     ap.add_argument("--sweep", action="store_true",

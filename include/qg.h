@@ -183,8 +183,9 @@ int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
                   const float *X, int M, float *Y,
                   void *workspace, size_t workspace_bytes, void *stream);
 
-/* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe).  0 restores the
- * built-in choice.  waves_per_block in 1..16 = most wavefronts that share one tile of 64
+/* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe; while one of them
+ * is non-zero they apply to every launch and the recorded tunings below are not consulted).  0
+ * restores the built-in choice.  waves_per_block in 1..16 = most wavefronts that share one tile of 64
  * outputs inside a workgroup; bytes_per_wave = packed code bytes one wavefront streams;
  * kernel = 1: multiply-adds on the vector ALU; 2: on the matrix cores with the 32 x 32 x 16
  * instruction (where that kernel exists: groups of at least two cells and at most one step,
@@ -192,6 +193,16 @@ int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
  * whole cells up to one step, and, at 2 and 3 bits, groups of whole steps) on bf16; 4: with
  * the 4 x 4 x 4 instruction on int8 (4-bit groups of at least 16 weights). */
 int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int kernel);
+/* Records a launch shape (same three values) for every later qg_gemv / qg_gemv_grouped /
+ * qg_gemv_swiglu / qg_gemv_noalloc launch of this process whose list of (N, K, bits, group) equals
+ * that of `descs` (HOST; only the shapes are read, in order) -- what qg_gemv_autotune does with
+ * its result, for a caller that has kept such a result from an earlier run (the paper keeps the
+ * outcome of its search per matrix size and machine, Section 3).  The table holds 64 lists; a
+ * 65th replaces the oldest.  Other launches keep the built-in choice. */
+int qg_gemv_record_tuning(const qg_gemv_desc *descs /* HOST */, int count, int waves_per_block,
+                          int bytes_per_wave, int kernel);
+/* Forgets every recorded tuning (GEMV and small-M GEMM). */
+void qg_clear_tuning(void);
 /* Name of the kernel instance the last qg_gemv / qg_gemv_grouped / qg_gemv_swiglu launch of this
  * process used (its last launch, if the call made several), e.g. "gemv_mma4i<4, 16>"; "" before
  * the first launch.  HOST string owned by the library.  For benchmark reports. */
@@ -207,8 +218,9 @@ const char *qg_last_gemv_kernel(void);
  * memory system's round trip (8 TB/s x 1.5 us / compute units; for launches too small to get
  * there, half of what the best candidate reaches).  Candidates below that are dropped; the
  * others run the launch `repeats` times, rotating over the sets.  The call WAITS for the GPU
- * (the only one that does), leaves the fastest installed as qg_set_gemv_tuning would, and
- * reports it (HOST pointers, each may be NULL; best_us = microseconds per launch).  The outputs
+ * (as qg_gemm_autotune does; no other call), records the fastest for launches with this list of
+ * shapes as qg_gemv_record_tuning would (the knobs of qg_set_gemv_tuning are left as they were;
+ * they have to be 0 for the recorded shape to be used), and reports it (HOST pointers, each may be NULL; best_us = microseconds per launch).  The outputs
  * y are overwritten as by qg_gemv_grouped; all sets share the workspace. */
 int qg_gemv_autotune(const qg_gemv_desc *descs /* HOST */, int count, int sets,
                      void *workspace, size_t workspace_bytes, void *stream, int repeats,
@@ -227,6 +239,27 @@ int qg_gemv_autotune_report(float *us /* HOST */, int capacity, int *timed, int 
  * raw-code kernel wherever it takes the layout.
  * 0 restores the built-in choice. */
 int qg_set_gemm_tuning(int splits, int shape);
+/* The launch-shape search of qg_gemm_small for one problem (N, K, bits, group, M) -- Section 3,
+ * Algorithm 4 with the resource model of eqs. (3)-(5), on this machine's terms.  The 120
+ * candidates are the 15 values of `shape` above (0, -1, 1..13) x 1..8 K ranges.  Each is planned
+ * without being launched and priced: registers per lane and LDS per workgroup of its kernel
+ * instance give the workgroups the chip holds at once and so the rounds the launch needs; a round
+ * costs a workgroup's fixed time (3.3 us) plus its iterations (2 us each), every further kernel
+ * of the call 3 us.  Candidates the planner maps to a plan already seen are skipped, candidates
+ * priced above 1.5 times the cheapest are dropped, the others run the product `repeats` times,
+ * rotating over the `sets` packed buffers in packed_sets (HOST array of DEVICE pointers, same
+ * matrix shape; different buffers keep a cache from serving the weights).  WAITS for the GPU,
+ * records the fastest for later qg_gemm_small calls on the same (N, K, bits, group, M) (used
+ * while both knobs of qg_set_gemm_tuning are 0; 64 problems are kept; qg_clear_tuning forgets
+ * them) and reports it (HOST pointers, each may be NULL).  Y is overwritten as by qg_gemm_small. */
+int qg_gemm_autotune(const void *const *packed_sets /* HOST */, int sets, int64_t N, int64_t K,
+                     int bits, int group, const float *X, int M, float *Y, void *workspace,
+                     size_t workspace_bytes, void *stream, int repeats,
+                     int *splits, int *shape, float *best_us);
+/* What the last qg_gemm_autotune did: us[c] (HOST, `capacity` >= 120, may be NULL), c = shape
+ * index * 8 + (K ranges - 1) with shape index 0 for shape 0, 1 for shape -1 and i + 1 for shape
+ * i >= 1: microseconds per call, -1 = dropped by the price, -2 = not a plan of its own (or the layout has no such kernel). */
+int qg_gemm_autotune_report(float *us /* HOST */, int capacity, int *timed, int *dropped);
 
 #ifdef __cplusplus
 }

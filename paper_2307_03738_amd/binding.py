@@ -83,6 +83,15 @@ def lib():
         L.qg_gemv_autotune_report.argtypes = [ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.qg_set_gemm_tuning.restype = i32
         L.qg_set_gemm_tuning.argtypes = [i32, i32]
+        L.qg_gemv_record_tuning.restype = i32
+        L.qg_gemv_record_tuning.argtypes = [ctypes.POINTER(_Desc), i32, i32, i32, i32]
+        L.qg_clear_tuning.restype = None
+        L.qg_clear_tuning.argtypes = []
+        L.qg_gemm_autotune.restype = i32
+        L.qg_gemm_autotune.argtypes = [ctypes.POINTER(vp), i32, i64, i64, i32, i32, vp, i32, vp, vp, sz, vp, i32,
+                                       ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_float)]
+        L.qg_gemm_autotune_report.restype = i32
+        L.qg_gemm_autotune_report.argtypes = [ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         _LIB = L
     return _LIB
 
@@ -292,6 +301,57 @@ def qg_gemv_autotune_report():
     us = (ctypes.c_float * 168)()
     timed, dropped = ctypes.c_int(), ctypes.c_int()
     _check(lib().qg_gemv_autotune_report(us, 168, ctypes.byref(timed), ctypes.byref(dropped)), "qg_gemv_autotune_report")
+    return list(us), timed.value, dropped.value
+
+
+def qg_gemv_record_tuning(problems: Sequence[dict], waves_per_block: int, bytes_per_wave: int, kernel: int):
+    """Records a launch shape for every later launch whose list of (N, K, bits, group) equals that of
+    `problems` (dicts with N, K, bits, group)."""
+    descs = (_Desc * len(problems))()
+    for i, p in enumerate(problems):
+        descs[i] = _Desc(0, p["N"], p["K"], p["bits"], p["group"], 0, 0)
+    _check(lib().qg_gemv_record_tuning(descs, len(problems), waves_per_block, bytes_per_wave, kernel),
+           "qg_gemv_record_tuning")
+
+
+def qg_clear_tuning():
+    lib().qg_clear_tuning()
+
+
+def qg_gemm_autotune(packed_sets: Sequence[torch.Tensor], N: int, K: int, bits: int, group: int, X: torch.Tensor,
+                     Y: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, repeats: int = 20):
+    """Searches the launch shape of qg_gemm_small for this problem, records the fastest and returns
+    (K ranges, shape, microseconds per call)."""
+    _dev(X, torch.float32, "X")
+    M = X.shape[0]
+    for b in packed_sets:
+        _dev(b, torch.uint8, "packed")
+        if b.numel() < qg_packed_bytes(N, K, bits, group, QG_LAYOUT_DEVICE):
+            _check(2, "qg_gemm_autotune")
+    if X.dim() != 2 or X.shape[1] != K:
+        _check(2, "qg_gemm_autotune")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=torch.float32, device=X.device)
+    if workspace is None:
+        workspace = new_workspace(qg_workspace_bytes(N, K, bits, group, M), X.device)
+    ptrs = (ctypes.c_void_p * len(packed_sets))(*[b.data_ptr() for b in packed_sets])
+    sp, sh, us = ctypes.c_int(), ctypes.c_int(), ctypes.c_float()
+    _check(lib().qg_gemm_autotune(ptrs, len(packed_sets), N, K, bits, group, X.data_ptr(), M, Y.data_ptr(),
+                                  workspace.data_ptr(), workspace.numel(), _stream(), repeats,
+                                  ctypes.byref(sp), ctypes.byref(sh), ctypes.byref(us)), "qg_gemm_autotune")
+    return sp.value, sh.value, us.value
+
+
+GEMM_AUTOTUNE_SHAPES = (0, -1) + tuple(range(1, 14))
+
+
+def qg_gemm_autotune_report():
+    """(microseconds per candidate: -1 dropped by the price, -2 not a plan of its own; number timed;
+    number dropped) of the last qg_gemm_autotune.  Candidate = GEMM_AUTOTUNE_SHAPES.index(shape) * 8 +
+    K ranges - 1."""
+    us = (ctypes.c_float * 120)()
+    timed, dropped = ctypes.c_int(), ctypes.c_int()
+    _check(lib().qg_gemm_autotune_report(us, 120, ctypes.byref(timed), ctypes.byref(dropped)), "qg_gemm_autotune_report")
     return list(us), timed.value, dropped.value
 
 

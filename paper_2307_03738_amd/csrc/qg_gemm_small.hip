@@ -29,6 +29,7 @@
 //
 // Other bit widths and group sizes take the fp32 GEMV kernel once per activation row, up to
 // 16 rows per launch.
+#include <mutex>
 #include <type_traits>
 
 #include "qg_common.h"
@@ -36,7 +37,7 @@
 
 size_t qg_gemm_workspace_bytes(const QgLayout &L, int M);
 int qg_gemm_rows16(const void *packed, int64_t N, int64_t K, int bits, int group, const float *X,
-                   int M, float *Y, void *workspace, void *stream);   // qg_gemv.hip
+                   int M, float *Y, void *workspace, void *stream, bool dry);   // qg_gemv.hip
 int qg_gemv_grouped_check(const qg_gemv_desc *descs, int count, void *workspace, size_t workspace_bytes);
 
 namespace {
@@ -1082,15 +1083,35 @@ __global__ __launch_bounds__(512) void gemm_codes(const CodesArgs A)
     }
 
     if (!have_tile) return;
-    float *out = A.out + (size_t)blockIdx.y * A.M * A.N;
+    // Register i of an accumulator is row 8 (i / 4) + 4 half + i % 4 of its block: bands of eight
+    // rows, four registers each.  A band that lies inside M in a tile that lies inside N is
+    // stored without a test per lane (both conditions are the same for the whole wavefront).
+    const int nP = tile * QG_WAVE + row, nQ = nP + 32;
+    float *out = A.out + (size_t)blockIdx.y * A.M * A.N + (size_t)(m0 + 4 * half) * A.N + nP;
+    const int rows_left = A.M - m0;
+    const bool whole_tile = (tile + 1) * QG_WAVE <= A.N;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int m = m0 + mb * 32 + 8 * (i / 4) + 4 * half + (i % 4);
-            const int nP = tile * QG_WAVE + row, nQ = nP + 32;
-            if (m < A.M && nP < A.N) out[(size_t)m * A.N + nP] = yP[mb][i];
-            if (m < A.M && nQ < A.N) out[(size_t)m * A.N + nQ] = yQ[mb][i];
+        for (int band = 0; band < 4; ++band) {
+            const int r0 = mb * 32 + 8 * band;
+            if (r0 >= rows_left) break;
+            if (whole_tile && r0 + 8 <= rows_left) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float *o = out + (size_t)(r0 + j) * A.N;
+                    o[0] = yP[mb][4 * band + j];
+                    o[32] = yQ[mb][4 * band + j];
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool in_m = r0 + 4 * half + j < rows_left;
+                    float *o = out + (size_t)(r0 + j) * A.N;
+                    if (in_m && nP < A.N) o[0] = yP[mb][4 * band + j];
+                    if (in_m && nQ < A.N) o[32] = yQ[mb][4 * band + j];
+                }
+            }
         }
 }
 
@@ -1129,13 +1150,65 @@ bool fast_path(const QgLayout &L)
 
 constexpr int MAX_SPLITS = 8;
 int g_tune_splits = 0;      // measurement knobs: 0 = built-in choice
-int g_tune_shape = 0;       // 1 + index into SHAPES
+int g_tune_shape = 0;       // 1 + index into SHAPES, NSHAPES + 1: the raw-code kernel, -1: gemm_rows16
+
+// Choices recorded per problem (qg_gemm_autotune): used where both knobs are 0.
+struct GemmTuneEntry {
+    int64_t N, K;
+    int bits, group, M, splits, shape;
+};
+constexpr int GEMM_TUNE_ENTRIES = 64;
+GemmTuneEntry g_gemm_table[GEMM_TUNE_ENTRIES];
+int g_gemm_count = 0, g_gemm_next = 0;
+std::mutex g_gemm_mutex;
+
+bool gemm_tuning_for(int64_t N, int64_t K, int bits, int group, int M, int *splits, int *shape)
+{
+    std::lock_guard<std::mutex> lock(g_gemm_mutex);
+    for (int i = 0; i < g_gemm_count; ++i) {
+        const GemmTuneEntry &e = g_gemm_table[i];
+        if (e.N == N && e.K == K && e.bits == bits && e.group == group && e.M == M) {
+            *splits = e.splits;
+            *shape = e.shape;
+            return true;
+        }
+    }
+    return false;
+}
+
+void gemm_record_tuning(int64_t N, int64_t K, int bits, int group, int M, int splits, int shape)
+{
+    std::lock_guard<std::mutex> lock(g_gemm_mutex);
+    int at = -1;
+    for (int i = 0; i < g_gemm_count; ++i) {
+        const GemmTuneEntry &e = g_gemm_table[i];
+        if (e.N == N && e.K == K && e.bits == bits && e.group == group && e.M == M) at = i;
+    }
+    if (at < 0) {
+        if (g_gemm_count < GEMM_TUNE_ENTRIES) at = g_gemm_count++;
+        else { at = g_gemm_next; g_gemm_next = (g_gemm_next + 1) % GEMM_TUNE_ENTRIES; }
+    }
+    g_gemm_table[at] = {N, K, bits, group, M, splits, shape};
+}
 
 int gcd(int a, int b) { return b == 0 ? a : gcd(b, a % b); }
 
+// What a launch would run, for the search that prices candidates before it times them
+// (qg_gemm_autotune): filled instead of launching when a launcher is handed one.
+struct KernelInfo {
+    const void *kernel;
+    int threads;
+    size_t lds_dynamic;
+};
+
 template <int MB, int TN, int KW>
-void launch(const GemmArgs &A, dim3 grid, hipStream_t st)
+void launch(const GemmArgs &A, dim3 grid, hipStream_t st, KernelInfo *query)
 {
+    if (query) {
+        *query = {A.group_shift == 7 ? (const void *)gemm_small_b4<MB, TN, KW, true>
+                                     : (const void *)gemm_small_b4<MB, TN, KW, false>, TN * KW * 64, 0};
+        return;
+    }
     if (A.group_shift == 7)
         hipLaunchKernelGGL((gemm_small_b4<MB, TN, KW, true>), grid, dim3(TN * KW * 64), 0, st, A);
     else
@@ -1143,8 +1216,13 @@ void launch(const GemmArgs &A, dim3 grid, hipStream_t st)
 }
 
 template <int MB, int TN>
-void launch_wide(const GemmArgs &A, dim3 grid, hipStream_t st)
+void launch_wide(const GemmArgs &A, dim3 grid, hipStream_t st, KernelInfo *query)
 {
+    if (query) {
+        *query = {A.group_shift == 7 ? (const void *)gemm_wide_b4<MB, TN, true> : (const void *)gemm_wide_b4<MB, TN, false>,
+                  TN * 64, 0};
+        return;
+    }
     if (A.group_shift == 7) hipLaunchKernelGGL((gemm_wide_b4<MB, TN, true>), grid, dim3(TN * 64), 0, st, A);
     else hipLaunchKernelGGL((gemm_wide_b4<MB, TN, false>), grid, dim3(TN * 64), 0, st, A);
 }
@@ -1163,21 +1241,21 @@ constexpr Shape SHAPES[] = {
 };
 constexpr int NSHAPES = sizeof(SHAPES) / sizeof(SHAPES[0]);
 
-void launch_shape(int i, const GemmArgs &A, dim3 grid, hipStream_t st)
+void launch_shape(int i, const GemmArgs &A, dim3 grid, hipStream_t st, KernelInfo *query = nullptr)
 {
     switch (i) {
-    case 0: launch<1, 1, 4>(A, grid, st); break;
-    case 1: launch<1, 2, 4>(A, grid, st); break;
-    case 2: launch<1, 4, 2>(A, grid, st); break;
-    case 3: launch<2, 2, 2>(A, grid, st); break;
-    case 4: launch<2, 4, 1>(A, grid, st); break;
-    case 5: launch<2, 4, 2>(A, grid, st); break;
-    case 6: launch<2, 8, 1>(A, grid, st); break;
-    case 7: launch_wide<2, 4>(A, grid, st); break;
-    case 8: launch_wide<2, 2>(A, grid, st); break;
-    case 9: launch_wide<4, 4>(A, grid, st); break;
-    case 10: launch_wide<4, 2>(A, grid, st); break;
-    default: launch_wide<2, 8>(A, grid, st); break;
+    case 0: launch<1, 1, 4>(A, grid, st, query); break;
+    case 1: launch<1, 2, 4>(A, grid, st, query); break;
+    case 2: launch<1, 4, 2>(A, grid, st, query); break;
+    case 3: launch<2, 2, 2>(A, grid, st, query); break;
+    case 4: launch<2, 4, 1>(A, grid, st, query); break;
+    case 5: launch<2, 4, 2>(A, grid, st, query); break;
+    case 6: launch<2, 8, 1>(A, grid, st, query); break;
+    case 7: launch_wide<2, 4>(A, grid, st, query); break;
+    case 8: launch_wide<2, 2>(A, grid, st, query); break;
+    case 9: launch_wide<4, 4>(A, grid, st, query); break;
+    case 10: launch_wide<4, 2>(A, grid, st, query); break;
+    default: launch_wide<2, 8>(A, grid, st, query); break;
     }
 }
 
@@ -1215,10 +1293,14 @@ CodesSpace codes_space(const QgLayout &L, int M)
 }
 
 template <int BITS, int CPG, int MB>
-int launch_codes(const CodesArgs &A, dim3 grid, hipStream_t st)
+int launch_codes(const CodesArgs &A, dim3 grid, hipStream_t st, KernelInfo *query)
 {
     constexpr int KW = BITS == 4 ? (MB == 1 ? 4 : 2) : (MB == 1 ? 2 : 1);
     constexpr size_t lds = gemm_codes_lds<BITS, CPG, MB, KW>();
+    if (query) {
+        *query = {(const void *)gemm_codes<BITS, CPG, MB, KW>, 512, lds};
+        return QG_OK;
+    }
     static bool prepared = false;              // dynamic LDS above 64 KB has to be asked for once
     if (!prepared) {
         if (hipFuncSetAttribute((const void *)gemm_codes<BITS, CPG, MB, KW>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1233,15 +1315,15 @@ int launch_codes(const CodesArgs &A, dim3 grid, hipStream_t st)
 }
 
 template <int BITS, int MB>
-int launch_codes_cpg(int cpg, const CodesArgs &A, dim3 grid, hipStream_t st)
+int launch_codes_cpg(int cpg, const CodesArgs &A, dim3 grid, hipStream_t st, KernelInfo *query)
 {
     switch (cpg) {
-    case 0: return launch_codes<BITS, 0, MB>(A, grid, st);
-    case 2: return launch_codes<BITS, 2, MB>(A, grid, st);
-    case 4: return launch_codes<BITS, 4, MB>(A, grid, st);
-    case 8: return launch_codes<BITS, 8, MB>(A, grid, st);
+    case 0: return launch_codes<BITS, 0, MB>(A, grid, st, query);
+    case 2: return launch_codes<BITS, 2, MB>(A, grid, st, query);
+    case 4: return launch_codes<BITS, 4, MB>(A, grid, st, query);
+    case 8: return launch_codes<BITS, 8, MB>(A, grid, st, query);
     case 16:
-        if constexpr (BITS != 3) return launch_codes<BITS, 16, MB>(A, grid, st);
+        if constexpr (BITS != 3) return launch_codes<BITS, 16, MB>(A, grid, st, query);
         return QG_ERR_UNSUPPORTED;
     default: return QG_ERR_UNSUPPORTED;
     }
@@ -1270,9 +1352,22 @@ extern "C" int qg_set_gemm_tuning(int splits, int shape)
     return QG_OK;
 }
 
-extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
-                             const float *X, int M, float *Y, void *workspace,
-                             size_t workspace_bytes, void *stream)
+namespace {
+// What one candidate of the launch-shape search costs, by the machine's budget (filled by a
+// planning pass of gemm_small, which then enqueues nothing).
+struct GemmPrice {
+    int family;                // 0 raw codes, 1 gemm_rows16, 2 one GEMV per row, 3 dequantizing kernels
+    int shape, splits;         // what the planner settled on (shape: index into SHAPES for family 3)
+    long workgroups;           // of the main launch
+    long iterations;           // barrier-to-barrier iterations one workgroup runs one after the other
+    int launches;              // kernels the call enqueues
+    KernelInfo kernel;
+};
+
+// Checks, plans and (price == NULL) enqueues one product; knob_*: as qg_set_gemm_tuning.
+int gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group, const float *X, int M,
+               float *Y, void *workspace, size_t workspace_bytes, void *stream, int knob_splits,
+               int knob_shape, GemmPrice *price)
 {
     QgLayout L;
     const int rc = qg_make_layout(N, K, bits, group, &L);
@@ -1291,7 +1386,7 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     const int cpg = codes_cpg(L);
     // (... and, measured, 3-6 % ahead of them beyond 64 rows on the larger 7B shapes)
     const bool large = M > 64 && L.tiles * L.steps >= 4096;
-    if (cpg >= 0 && M > 1 && (g_tune_shape == NSHAPES + 1 || (g_tune_shape == 0 && (!fast_path(L) || large)))) {
+    if (cpg >= 0 && M > 1 && (knob_shape == NSHAPES + 1 || (knob_shape == 0 && (!fast_path(L) || large)))) {
         const int mb = M <= 32 ? 1 : 2;
         const int kw = codes_kw(bits, mb), tn = 8 / kw;
         const int rows_per_block = 32 * mb;
@@ -1300,8 +1395,8 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
         const int quanta = (int)((L.steps + kw - 1) / kw);
         const int cus = qg_compute_units();
         // as many K ranges as keep the launch within one workgroup per compute unit (a workgroup
-        // fills a unit's LDS, so one more would wait for a second round)
-        int splits = g_tune_splits ? g_tune_splits : cus / (blocks_x * zblocks);
+        // takes half of a unit's registers or more, so one more would wait for a second round)
+        int splits = knob_splits ? knob_splits : cus / (blocks_x * zblocks);
         if (splits < 1) splits = 1;
         if (splits > MAX_SPLITS) splits = MAX_SPLITS;
         if (splits > quanta) splits = quanta;
@@ -1318,11 +1413,6 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
         P.rows_padded = W.rows_padded;
         P.kpad = W.steps_padded * L.unit * L.step_units;
         P.groupk = W.groupk;
-        const dim3 pgrid((unsigned)((P.kpad / (bits == 2 ? 16 : 8) + 255) / 256), (unsigned)W.rows_padded);
-        if (bits == 4) hipLaunchKernelGGL(prepare_x<4>, pgrid, dim3(256), 0, st, P);
-        else if (bits == 2) hipLaunchKernelGGL(prepare_x<2>, pgrid, dim3(256), 0, st, P);
-        else hipLaunchKernelGGL(prepare_x<3>, pgrid, dim3(256), 0, st, P);
-        if (qg_launch_status() != QG_OK) return QG_ERR_DEVICE;
         CodesArgs A;
         const char *base = (const char *)packed;
         A.codes = (const uint4 *)(base + L.codes_off);
@@ -1342,10 +1432,26 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
         A.steps_per_group = cpg == 0 ? group / (L.unit * L.step_units) : 1;
         A.steps_per_split = sps;
         const dim3 grid((unsigned)blocks_x, (unsigned)splits, (unsigned)zblocks);
-        int r;
-        if (bits == 4) r = mb == 1 ? launch_codes_cpg<4, 1>(cpg, A, grid, st) : launch_codes_cpg<4, 2>(cpg, A, grid, st);
-        else if (bits == 2) r = mb == 1 ? launch_codes_cpg<2, 1>(cpg, A, grid, st) : launch_codes_cpg<2, 2>(cpg, A, grid, st);
-        else r = mb == 1 ? launch_codes_cpg<3, 1>(cpg, A, grid, st) : launch_codes_cpg<3, 2>(cpg, A, grid, st);
+        KernelInfo info = {nullptr, 0, 0};
+        auto main_kernel = [&](KernelInfo *query) {
+            if (bits == 4) return mb == 1 ? launch_codes_cpg<4, 1>(cpg, A, grid, st, query) : launch_codes_cpg<4, 2>(cpg, A, grid, st, query);
+            if (bits == 2) return mb == 1 ? launch_codes_cpg<2, 1>(cpg, A, grid, st, query) : launch_codes_cpg<2, 2>(cpg, A, grid, st, query);
+            return mb == 1 ? launch_codes_cpg<3, 1>(cpg, A, grid, st, query) : launch_codes_cpg<3, 2>(cpg, A, grid, st, query);
+        };
+        // (the instance is looked up before anything is enqueued: a layout without one is an error
+        // that leaves nothing behind)
+        const int have = main_kernel(&info);
+        if (have != QG_OK) return have;
+        if (price) {
+            *price = {0, NSHAPES, splits, (long)blocks_x * splits * zblocks, sps / kw, splits > 1 ? 3 : 2, info};
+            return QG_OK;
+        }
+        const dim3 pgrid((unsigned)((P.kpad / (bits == 2 ? 16 : 8) + 255) / 256), (unsigned)W.rows_padded);
+        if (bits == 4) hipLaunchKernelGGL(prepare_x<4>, pgrid, dim3(256), 0, st, P);
+        else if (bits == 2) hipLaunchKernelGGL(prepare_x<2>, pgrid, dim3(256), 0, st, P);
+        else hipLaunchKernelGGL(prepare_x<3>, pgrid, dim3(256), 0, st, P);
+        if (qg_launch_status() != QG_OK) return QG_ERR_DEVICE;
+        const int r = main_kernel(nullptr);
         if (r != QG_OK) return r;
         if (qg_launch_status() != QG_OK) return QG_ERR_DEVICE;
         if (splits > 1) {
@@ -1359,8 +1465,9 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     // Up to 16 rows: the barrier-free kernel on the GEMV's launch structure, where it applies.
     // It has one workgroup per tile and no split of K over workgroups, so it needs enough tiles
     // to cover the chip (measured: ahead from about 128 tiles; shape -1 forces it).
-    if (M <= 16 && (g_tune_shape == 0 ? L.tiles >= 128 : g_tune_shape < 0)) {
-        const int r = qg_gemm_rows16(packed, N, K, bits, group, X, M, Y, workspace, stream);
+    if (M <= 16 && (knob_shape == 0 ? L.tiles >= 128 : knob_shape < 0)) {
+        const int r = qg_gemm_rows16(packed, N, K, bits, group, X, M, Y, workspace, stream, price != nullptr);
+        if (r == QG_OK && price) *price = {1, -1, 1, (long)L.tiles, 0, 1, {nullptr, 0, 0}};
         if (r != QG_ERR_UNSUPPORTED) return r;
     }
 
@@ -1370,7 +1477,7 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
         if (K % 16 != 0 && M > 1) return QG_ERR_UNSUPPORTED;
         // two passes over the launches of 16 rows: the first only checks and plans, so that an
         // error leaves nothing enqueued
-        for (int pass = 0; pass < 2; ++pass)
+        for (int pass = 0; pass < (price ? 1 : 2); ++pass)
             for (int m0 = 0; m0 < M; m0 += QG_MAX_GROUPED) {
                 qg_gemv_desc d[QG_MAX_GROUPED];
                 const int rows = M - m0 < QG_MAX_GROUPED ? M - m0 : QG_MAX_GROUPED;
@@ -1387,6 +1494,7 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
                                         : qg_gemv_grouped(d, rows, workspace, workspace_bytes, stream);
                 if (r != QG_OK) return r;
             }
+        if (price) *price = {2, -1, 1, 0, 0, (M + QG_MAX_GROUPED - 1) / QG_MAX_GROUPED, {nullptr, 0, 0}};
         return QG_OK;
     }
 
@@ -1397,9 +1505,9 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     // k-slices (two blocks double the wavefronts of a launch at the price of dequantizing
     // twice, which pays as long as the launch cannot fill the chip).
     int shape = M <= 32 ? 1 : M <= 64 ? 7 : L.tiles >= 128 ? 9 : 5;
-    if (g_tune_shape > 0 && g_tune_shape <= NSHAPES) {
-        const Shape &s = SHAPES[g_tune_shape - 1];
-        if (s.wide ? (M > 32 && M <= s.mb * 32) : ((s.mb == 1) == (M <= 32))) shape = g_tune_shape - 1;
+    if (knob_shape > 0 && knob_shape <= NSHAPES) {
+        const Shape &sh = SHAPES[knob_shape - 1];
+        if (sh.wide ? (M > 32 && M <= sh.mb * 32) : ((sh.mb == 1) == (M <= 32))) shape = knob_shape - 1;
     }
     const int rows_per_block = SHAPES[shape].mb * 32;
     const int zblocks = (M + rows_per_block - 1) / rows_per_block;
@@ -1411,7 +1519,7 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     const int quanta = (int)((L.steps + quantum - 1) / quantum);
     // about one workgroup per compute unit, each with at least one quantum of work
     const int cus = qg_compute_units();
-    int splits = g_tune_splits ? g_tune_splits : (cus + blocks_x * zblocks - 1) / (blocks_x * zblocks);
+    int splits = knob_splits ? knob_splits : (cus + blocks_x * zblocks - 1) / (blocks_x * zblocks);
     if (splits > MAX_SPLITS) splits = MAX_SPLITS;
     if (splits > quanta) splits = quanta;
     const int sps = (quanta + splits - 1) / splits * quantum;
@@ -1436,6 +1544,14 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
     A.steps_per_group = steps_per_group;
     A.steps_per_split = sps;
     const dim3 grid((unsigned)blocks_x, (unsigned)splits, (unsigned)zblocks);
+    if (price) {
+        KernelInfo info = {nullptr, 0, 0};
+        launch_shape(shape, A, grid, st, &info);
+        // (gemm_wide_b4 runs two steps per iteration)
+        *price = {3, shape, splits, (long)blocks_x * splits * zblocks, sps / (SHAPES[shape].wide ? 2 : kw) + 1,
+                  splits > 1 ? 2 : 1, info};
+        return QG_OK;
+    }
     launch_shape(shape, A, grid, st);
     if (qg_launch_status() != QG_OK) return QG_ERR_DEVICE;
     if (splits > 1) {
@@ -1444,4 +1560,147 @@ extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits,
                            (const float *)partial, splits, count, Y);
     }
     return qg_launch_status();
+}
+}  // namespace
+
+void qg_gemm_clear_tuning()
+{
+    std::lock_guard<std::mutex> lock(g_gemm_mutex);
+    g_gemm_count = 0;
+    g_gemm_next = 0;
+}
+
+extern "C" int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
+                             const float *X, int M, float *Y, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    int splits = g_tune_splits, shape = g_tune_shape;
+    if (splits == 0 && shape == 0 && g_gemm_count > 0) (void)gemm_tuning_for(N, K, bits, group, M, &splits, &shape);
+    return gemm_small(packed, N, K, bits, group, X, M, Y, workspace, workspace_bytes, stream, splits, shape, nullptr);
+}
+
+// The launch-shape search of the small-M product: the counterpart of the paper's parameter search
+// (Section 3, Algorithm 4, with the resource model of eqs. (3)-(5)) for this call.  Candidates
+// are (kernel family / workgroup shape) x (number of K ranges).  Each is planned without being
+// launched (a shape that does not fit the problem falls back to the built-in one, and a plan
+// seen before is not tried again) and priced: the registers per lane and the LDS per workgroup of its kernel instance
+// give the workgroups the chip holds at once, hence the rounds the launch needs; a round costs
+// a workgroup's fixed time plus its iterations, and every further kernel of the call a launch.
+// Candidates priced above 1.5 times the cheapest are dropped, the others timed.
+namespace {
+constexpr int GT_SHAPES = NSHAPES + 3;           // 0 (built-in choice), -1 (gemm_rows16), 1 ... NSHAPES, NSHAPES + 1 (raw codes)
+constexpr int GT_CANDIDATES = GT_SHAPES * MAX_SPLITS;
+constexpr int gt_shape(int c) { return c / MAX_SPLITS == 0 ? 0 : c / MAX_SPLITS == 1 ? -1 : c / MAX_SPLITS - 1; }
+float g_gt_us[GT_CANDIDATES];                    // -1: dropped by the price, -2: same plan as an earlier candidate
+int g_gt_timed = 0, g_gt_dropped = 0;
+// measured on this machine: a workgroup's time outside its loop (first loads, reduction across
+// k-slices, output), one barrier-to-barrier iteration (a memory round trip), one more kernel in a call
+constexpr double GT_FIXED_US = 3.3, GT_ITERATION_US = 2.0, GT_LAUNCH_US = 3.0;
+
+double gemm_price_us(const GemmPrice &p)
+{
+    if (p.family == 1 || p.family == 2) return 0.0;          // no model: always timed
+    int resident = 1;
+    hipFuncAttributes attr;
+    if (p.kernel.kernel && hipFuncGetAttributes(&attr, p.kernel.kernel) == hipSuccess) {
+        const int waves = p.kernel.threads / QG_WAVE;
+        const int regs = ((attr.numRegs > 0 ? attr.numRegs : 128) + 7) / 8 * 8;
+        int per_simd = 512 / regs;
+        if (per_simd > 8) per_simd = 8;
+        if (per_simd < 1) per_simd = 1;
+        resident = per_simd * 4 / waves;
+        const size_t lds = attr.sharedSizeBytes + p.kernel.lds_dynamic;
+        if (lds > 0 && (int)((160u << 10) / lds) < resident) resident = (int)((160u << 10) / lds);
+        if (resident < 1) resident = 1;
+    } else {
+        (void)hipGetLastError();
+    }
+    const long capacity = (long)resident * qg_compute_units();
+    const long rounds = (p.workgroups + capacity - 1) / capacity;
+    return (double)rounds * (GT_FIXED_US + (double)p.iterations * GT_ITERATION_US) + (double)(p.launches - 1) * GT_LAUNCH_US;
+}
+}  // namespace
+
+extern "C" int qg_gemm_autotune(const void *const *packed_sets, int sets, int64_t N, int64_t K, int bits,
+                                int group, const float *X, int M, float *Y, void *workspace,
+                                size_t workspace_bytes, void *stream, int repeats, int *splits,
+                                int *shape, float *best_us)
+{
+    if (repeats <= 0 || sets <= 0) return QG_ERR_SHAPE;
+    if (!packed_sets) return QG_ERR_NULL;
+    for (int s = 0; s < sets; ++s)
+        if (!packed_sets[s]) return QG_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    // 1. plan and price every candidate
+    GemmPrice plan[GT_CANDIDATES];
+    double price[GT_CANDIDATES], cheapest = -1.0;
+    bool valid[GT_CANDIDATES];
+    for (int c = 0; c < GT_CANDIDATES; ++c) {
+        const int sh = gt_shape(c), sp = 1 + c % MAX_SPLITS;
+        const int rc = gemm_small(packed_sets[0], N, K, bits, group, X, M, Y, workspace, workspace_bytes, stream, sp, sh, &plan[c]);
+        if (rc == QG_ERR_UNSUPPORTED) { valid[c] = false; continue; }
+        if (rc != QG_OK) return rc;
+        valid[c] = true;
+        for (int e = 0; e < c && valid[c]; ++e)          // a knob the planner did not follow: seen already
+            if (valid[e] && plan[e].family == plan[c].family && plan[e].shape == plan[c].shape && plan[e].splits == plan[c].splits)
+                valid[c] = false;
+        if (!valid[c]) continue;
+        price[c] = gemm_price_us(plan[c]);
+        if (price[c] > 0.0 && (cheapest < 0.0 || price[c] < cheapest)) cheapest = price[c];
+    }
+    // 2. time the survivors
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return QG_ERR_DEVICE;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return QG_ERR_DEVICE; }
+    int best = -1, rc = QG_OK, turn = 0;
+    float best_ms = -1.0f;
+    g_gt_timed = 0;
+    g_gt_dropped = 0;
+    for (int c = 0; c < GT_CANDIDATES && rc == QG_OK; ++c) {
+        g_gt_us[c] = -2.0f;
+        if (!valid[c]) continue;
+        if (price[c] > 1.5 * cheapest && cheapest > 0.0) {
+            g_gt_us[c] = -1.0f;
+            ++g_gt_dropped;
+            continue;
+        }
+        const int sh = gt_shape(c), sp = 1 + c % MAX_SPLITS;
+        auto run = [&]() {
+            return gemm_small(packed_sets[turn++ % sets], N, K, bits, group, X, M, Y, workspace, workspace_bytes, stream, sp, sh, nullptr);
+        };
+        for (int i = 0; i < 2 && rc == QG_OK; ++i) rc = run();
+        if (rc != QG_OK) break;
+        if (hipEventRecord(e0, st) != hipSuccess) { rc = QG_ERR_DEVICE; break; }
+        for (int i = 0; i < repeats && rc == QG_OK; ++i) rc = run();
+        if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) rc = QG_ERR_DEVICE;
+        float ms = 0.0f;
+        if (rc == QG_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = QG_ERR_DEVICE;
+        if (rc != QG_OK) break;
+        g_gt_us[c] = ms * 1e3f / (float)repeats;
+        ++g_gt_timed;
+        if (best < 0 || ms < best_ms) {
+            best_ms = ms;
+            best = c;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != QG_OK || best < 0) return rc != QG_OK ? rc : QG_ERR_DEVICE;
+    const int won_shape = gt_shape(best), won_splits = 1 + best % MAX_SPLITS;
+    gemm_record_tuning(N, K, bits, group, M, won_splits, won_shape);
+    if (splits) *splits = won_splits;
+    if (shape) *shape = won_shape;
+    if (best_us) *best_us = best_ms * 1e3f / (float)repeats;
+    return QG_OK;
+}
+
+extern "C" int qg_gemm_autotune_report(float *us, int capacity, int *timed, int *dropped)
+{
+    if (us) {
+        if (capacity < GT_CANDIDATES) return QG_ERR_SHAPE;
+        for (int c = 0; c < GT_CANDIDATES; ++c) us[c] = g_gt_us[c];
+    }
+    if (timed) *timed = g_gt_timed;
+    if (dropped) *dropped = g_gt_dropped;
+    return QG_OK;
 }

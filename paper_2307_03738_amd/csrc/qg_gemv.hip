@@ -1592,9 +1592,70 @@ __global__ void fill_u32(uint32_t *p, size_t n, uint32_t value)
 
 // ------------------------------------------------------------------ host side
 
+// Launch-shape knobs: 0 = built-in choice.  The process-wide ones (qg_set_gemv_tuning) win; where
+// they are all 0, a launch takes what the tuning table holds for its list of shapes
+// (qg_gemv_autotune, qg_gemv_record_tuning); t_cur is what the launch being planned uses.
+struct Tuning {
+    int wpb, bytes_per_wave, kernel;      // kernel: 1 = vector ALU, 2-4 = the matrix-core kernels
+};
 int g_tune_wpb = 0;
 int g_tune_bytes_per_wave = 0;
-int g_tune_kernel = 0;       // 0 = built-in choice, 1 = vector-ALU kernels, 2 = matrix-core kernel where it exists
+int g_tune_kernel = 0;
+thread_local Tuning t_cur = {0, 0, 0};
+
+struct TuneEntry {
+    uint64_t key;
+    Tuning t;
+};
+constexpr int TUNE_ENTRIES = 64;
+TuneEntry g_tune_table[TUNE_ENTRIES];
+int g_tune_count = 0, g_tune_next = 0;          // entries in use; the one replaced when the table is full
+std::mutex g_tune_mutex;
+
+// FNV-1a over the shapes of a launch, in the caller's order
+uint64_t launch_signature(const qg_gemv_desc *descs, int count)
+{
+    uint64_t h = 0xcbf29ce484222325ull;
+    auto mix = [&](uint64_t v) {
+        for (int b = 0; b < 8; ++b) {
+            h ^= (v >> (8 * b)) & 0xffu;
+            h *= 0x100000001b3ull;
+        }
+    };
+    mix((uint64_t)count);
+    for (int i = 0; i < count; ++i) {
+        mix((uint64_t)descs[i].N);
+        mix((uint64_t)descs[i].K);
+        mix(((uint64_t)(uint32_t)descs[i].bits << 32) | (uint32_t)descs[i].group);
+    }
+    return h;
+}
+
+Tuning tuning_for(const qg_gemv_desc *descs, int count)
+{
+    if (g_tune_wpb || g_tune_bytes_per_wave || g_tune_kernel) return {g_tune_wpb, g_tune_bytes_per_wave, g_tune_kernel};
+    std::lock_guard<std::mutex> lock(g_tune_mutex);
+    if (g_tune_count == 0) return {0, 0, 0};
+    const uint64_t key = launch_signature(descs, count);
+    for (int i = 0; i < g_tune_count; ++i)
+        if (g_tune_table[i].key == key) return g_tune_table[i].t;
+    return {0, 0, 0};
+}
+
+void record_tuning(const qg_gemv_desc *descs, int count, Tuning t)
+{
+    std::lock_guard<std::mutex> lock(g_tune_mutex);
+    const uint64_t key = launch_signature(descs, count);
+    int at = -1;
+    for (int i = 0; i < g_tune_count; ++i)
+        if (g_tune_table[i].key == key) at = i;
+    if (at < 0) {
+        if (g_tune_count < TUNE_ENTRIES) at = g_tune_count++;
+        else { at = g_tune_next; g_tune_next = (g_tune_next + 1) % TUNE_ENTRIES; }
+    }
+    g_tune_table[at].key = key;
+    g_tune_table[at].t = t;
+}
 
 enum Kind { KIND_STATIC, KIND_RUNTIME, KIND_GENERIC };
 
@@ -1784,7 +1845,7 @@ constexpr size_t QG_VALU4_FROM = (size_t)256 << 20;      // code bytes of a laun
 Mul multiplier(int bits, int cpg, Kind kind, size_t code_bytes)
 {
     if (kind != KIND_STATIC && kind != KIND_RUNTIME) return MUL_VALU;
-    const int want = g_tune_kernel ? g_tune_kernel
+    const int want = t_cur.kernel ? t_cur.kernel
                    : bits == 4 && kind == KIND_STATIC && code_bytes >= QG_VALU4_FROM ? 1 : 4;
     if (want == 4 && !(bits == 4 && kind == KIND_STATIC && cpg < 2)) return MUL_MMA4I;
     if (want >= 3 && (kind == KIND_STATIC || bits != 4)) return MUL_MMA4;
@@ -1827,13 +1888,13 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     const bool mma = mul != MUL_VALU;
     // wavefronts per team, at most (measured: 12 is best for the 4-bit vector-ALU kernel with
     // groups inside a step, 8 for the 2- and 3-bit ones, which hold more registers per wavefront)
-    int cap = g_tune_wpb > 0 ? g_tune_wpb : (bits_all == 4 ? 12 : 8);
+    int cap = t_cur.wpb > 0 ? t_cur.wpb : (bits_all == 4 ? 12 : 8);
     if (rows > 0 && cap > 8) cap = 8;          // gemm_rows16 is built for at most 8 wavefronts
     if (mma) {                                 // the matrix-core kernels are built for at most 8 wavefronts;
         if (cap > 8) cap = 8;                  // measured: teams of 4 are best for them ...
-        if (g_tune_wpb == 0) cap = 4;
+        if (t_cur.wpb == 0) cap = 4;
     }
-    size_t target = (size_t)g_tune_bytes_per_wave;               // code bytes per wavefront
+    size_t target = (size_t)t_cur.bytes_per_wave;               // code bytes per wavefront
     // ... except for 2- and 3-bit groups inside a step on gemv_mma4i below 192 MB of codes: there
     // teams of up to 8 with a single step per wavefront are 4-13 % ahead (7B- and 13B-shaped
     // sets; on the 65B-shaped one that shape is 0-6 % behind).  The same on gemv_mma4 for 3-bit
@@ -1842,7 +1903,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
                           ((mul == MUL_MMA4I && bits_all != 4 && code_bytes < ((size_t)192 << 20)) ||
                            (mul == MUL_MMA4 && bits_all == 3 && L[0].group <= 64));
     if (one_step) {
-        if (g_tune_wpb == 0) cap = 8;
+        if (t_cur.wpb == 0) cap = 8;
         if (target == 0) target = pl[0].item_bytes;
     }
     // Few, long wavefronts (teams of up to 4, about 10 wavefronts per CU, up to 48-64 KB of codes
@@ -1854,7 +1915,7 @@ int launch_class(const qg_gemv_desc *descs, const int *idx, int count, const siz
     if (few_long) {
         const size_t share = code_bytes / ((size_t)qg_compute_units() * 10);
         // (the vector-ALU kernel keeps its wider teams while a wavefront has a single step)
-        if (g_tune_wpb == 0 && (mma || share > 4096)) cap = 4;
+        if (t_cur.wpb == 0 && (mma || share > 4096)) cap = 4;
         if (target == 0) {
             size_t most = bits_all == 4 ? 65536 : 49152;
             // (groups of one or two cells: a wavefront holds at most 64 groups, and half of that
@@ -2051,6 +2112,29 @@ extern "C" int qg_set_gemv_tuning(int waves_per_block, int bytes_per_wave, int k
     return QG_OK;
 }
 
+extern "C" int qg_gemv_record_tuning(const qg_gemv_desc *descs, int count, int waves_per_block,
+                                     int bytes_per_wave, int kernel)
+{
+    if (!descs) return QG_ERR_NULL;
+    if (count <= 0 || waves_per_block < 0 || waves_per_block > 16 || bytes_per_wave < 0 || kernel < 0 || kernel > 4)
+        return QG_ERR_SHAPE;
+    if (count > QG_MAX_GROUPED) return QG_ERR_UNSUPPORTED;
+    record_tuning(descs, count, {waves_per_block, bytes_per_wave, kernel});
+    return QG_OK;
+}
+
+void qg_gemm_clear_tuning();     // qg_gemm_small.hip
+
+extern "C" void qg_clear_tuning(void)
+{
+    {
+        std::lock_guard<std::mutex> lock(g_tune_mutex);
+        g_tune_count = 0;
+        g_tune_next = 0;
+    }
+    qg_gemm_clear_tuning();
+}
+
 size_t qg_gemm_workspace_bytes(const QgLayout &L, int M);   // qg_gemm_small.hip
 
 extern "C" size_t qg_workspace_bytes(int64_t N, int64_t K, int bits, int group, int M)
@@ -2097,6 +2181,7 @@ static int gemv_grouped(const qg_gemv_desc *descs, int count, void *workspace, s
     }
     if (!workspace || workspace_bytes < need) return QG_ERR_WORKSPACE;
     if (!qg_aligned16(workspace)) return QG_ERR_ALIGN;
+    t_cur = tuning_for(descs, count);
 
     // one launch per distinct (bits, kernel kind), and per group size where the kernel has it
     // as a compile-time constant.  Two passes: the first plans every class and launches
@@ -2148,9 +2233,9 @@ int qg_gemv_grouped_check(const qg_gemv_desc *descs, int count, void *workspace,
 
 // Y = X What^T for M <= 16 rows on the GEMV's launch structure (used by qg_gemm_small).
 // Returns QG_ERR_UNSUPPORTED if the shape is not one gemm_rows16 takes; the arguments have
-// been checked by the caller.
+// been checked by the caller.  dry: plan only, nothing enqueued.
 int qg_gemm_rows16(const void *packed, int64_t N, int64_t K, int bits, int group, const float *X,
-                   int M, float *Y, void *workspace, void *stream)
+                   int M, float *Y, void *workspace, void *stream, bool dry)
 {
     QgLayout L;
     if (qg_make_layout(N, K, bits, group, &L) != QG_OK) return QG_ERR_UNSUPPORTED;
@@ -2168,7 +2253,8 @@ int qg_gemm_rows16(const void *packed, int64_t N, int64_t K, int bits, int group
     d.y = Y;
     const int idx = 0;
     const size_t ws_off = 0;
-    return launch_class(&d, &idx, 1, &ws_off, (char *)workspace, (hipStream_t)stream, nullptr, nullptr, M);
+    t_cur = {g_tune_wpb, g_tune_bytes_per_wave, g_tune_kernel};
+    return launch_class(&d, &idx, 1, &ws_off, (char *)workspace, (hipStream_t)stream, nullptr, nullptr, M, dry);
 }
 
 extern "C" int qg_gemv_swiglu(const void *packed, int64_t I, int64_t K, int bits, int group,
@@ -2272,8 +2358,9 @@ extern "C" int qg_gemv(const void *packed, int64_t N, int64_t K, int bits, int g
 // and the LDS per workgroup of the kernel instance give the wavefronts a compute unit can hold,
 // those times the bytes a wavefront keeps requested give the bytes in flight per unit, and a
 // candidate that cannot keep the memory system's round trip covered is dropped -- and only the
-// survivors are timed; the fastest is left installed as with qg_set_gemv_tuning.  Unlike every
-// other call this one waits for the GPU.
+// survivors are timed; the fastest is recorded for launches with this list of shapes (as the
+// paper's search result is kept per matrix size).  Unlike every other call this one waits for
+// the GPU.
 namespace {
 constexpr int AT_TEAMS[] = {0, 2, 4, 8, 12, 16};
 constexpr int AT_SIZES[] = {0, 4096, 8192, 16384, 32768, 49152, 65536};
@@ -2393,12 +2480,12 @@ extern "C" int qg_gemv_autotune(const qg_gemv_desc *descs, int count, int sets, 
         restore();
         return rc != QG_OK ? rc : QG_ERR_DEVICE;
     }
-    g_tune_kernel = 1 + best / (AT_NT * AT_NS);
-    g_tune_wpb = AT_TEAMS[(best / AT_NS) % AT_NT];
-    g_tune_bytes_per_wave = AT_SIZES[best % AT_NS];
-    if (waves_per_block) *waves_per_block = g_tune_wpb;
-    if (bytes_per_wave) *bytes_per_wave = g_tune_bytes_per_wave;
-    if (kernel) *kernel = g_tune_kernel;
+    const Tuning won = {AT_TEAMS[(best / AT_NS) % AT_NT], AT_SIZES[best % AT_NS], 1 + best / (AT_NT * AT_NS)};
+    restore();
+    record_tuning(descs, count, won);
+    if (waves_per_block) *waves_per_block = won.wpb;
+    if (bytes_per_wave) *bytes_per_wave = won.bytes_per_wave;
+    if (kernel) *kernel = won.kernel;
     if (best_us) *best_us = best_ms * 1e3f / (float)repeats;
     return QG_OK;
 }

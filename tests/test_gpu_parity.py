@@ -514,6 +514,83 @@ def test_gemv_autotune_leaves_a_working_choice(qg, oracle):
         assert np.all(host(launch.workspace) == 0xFF)
     finally:
         qg.qg_set_gemv_tuning(0, 0, 0)
+        qg.qg_clear_tuning()
+
+
+def test_gemv_recorded_tuning_applies_to_its_shapes_only(qg, oracle):
+    # a tuning recorded for one list of shapes is used by launches with exactly that list, by no
+    # other launch, and not after qg_clear_tuning; the process-wide knobs still win
+    _announce("gemv recorded tuning")
+    N, K, bits, group = 300, 2048, 4, 128
+    W, x = synth.small_case(1300, N, K, 0.02, True)
+    q0, s0, z0 = oracle.quantize(W, bits, group)
+    y_ref, norms = oracle.matvec(q0, s0, z0, group, x), oracle.row_norms(q0, s0, z0, group)
+    q, s, z = qg.qg_quantize(dev(W), bits, group)
+    blob = qg.qg_pack(q, s, z, bits, group)
+    W2, x2 = synth.small_case(1301, 200, 1024, 0.02, True)
+    q2, s2, z2 = qg.qg_quantize(dev(W2), bits, group)
+    blob2 = qg.qg_pack(q2, s2, z2, bits, group)
+
+    def run_a():
+        y = qg.qg_gemv(blob, N, K, bits, group, dev(x))
+        torch.cuda.synchronize()
+        assert scaled_error(host(y), y_ref, norms, x) <= TOL_FP32
+        return qg.qg_last_gemv_kernel()
+
+    def run_b():
+        qg.qg_gemv(blob2, 200, 1024, bits, group, dev(x2))
+        torch.cuda.synchronize()
+        return qg.qg_last_gemv_kernel()
+
+    try:
+        builtin_a, builtin_b = run_a(), run_b()
+        assert builtin_a.startswith("gemv_mma4i") and builtin_b.startswith("gemv_mma4i")
+        qg.qg_gemv_record_tuning([dict(N=N, K=K, bits=bits, group=group)], 8, 8192, 1)
+        assert run_a().startswith("gemv_static")           # the vector-ALU kernel, as recorded
+        assert run_b() == builtin_b                         # another shape: untouched
+        both = [dict(packed=blob, N=N, K=K, bits=bits, group=group, x=dev(x), y=torch.empty(N, device="cuda")),
+                dict(packed=blob2, N=200, K=1024, bits=bits, group=group, x=dev(x2), y=torch.empty(200, device="cuda"))]
+        qg.qg_gemv_grouped(both)                            # another list of shapes: untouched
+        torch.cuda.synchronize()
+        assert qg.qg_last_gemv_kernel().startswith("gemv_mma4i")
+        qg.qg_set_gemv_tuning(0, 0, 3)                      # the knobs win over the record
+        assert run_a().startswith("gemv_mma4<")
+        qg.qg_set_gemv_tuning(0, 0, 0)
+        assert run_a().startswith("gemv_static")
+        qg.qg_clear_tuning()
+        assert run_a() == builtin_a
+    finally:
+        qg.qg_set_gemv_tuning(0, 0, 0)
+        qg.qg_clear_tuning()
+
+
+@pytest.mark.parametrize("N,K,bits,group,M", [(640, 2048, 4, 128, 24), (520, 1536, 3, 64, 70), (300, 1024, 2, 32, 16)])
+def test_gemm_autotune_records_a_working_choice(qg, oracle, N, K, bits, group, M):
+    _announce("gemm autotune", N, K, bits, group, M)
+    W, X = synth.small_case(1400 + bits, N, K, 0.02, True, m=M)
+    q0, s0, z0 = oracle.quantize(W, bits, group)
+    Y_ref, norms = oracle.matmul_small(q0, s0, z0, group, X), oracle.row_norms(q0, s0, z0, group)
+    q, s, z = qg.qg_quantize(dev(W), bits, group)
+    blob = qg.qg_pack(q, s, z, bits, group)
+    try:
+        splits, shape, us = qg.qg_gemm_autotune([blob, blob.clone()], N, K, bits, group, dev(X), repeats=4)
+        table, timed, dropped = qg.qg_gemm_autotune_report()
+        assert 1 <= splits <= 8 and shape in qg.GEMM_AUTOTUNE_SHAPES and us > 0 and timed >= 1
+        assert sum(1 for t in table if t > 0) == timed and sum(1 for t in table if t == -1.0) == dropped
+        chosen = qg.GEMM_AUTOTUNE_SHAPES.index(shape) * 8 + splits - 1
+        assert table[chosen] > 0 and table[chosen] == min(t for t in table if t > 0)
+        # the recorded choice is what the next call runs, and it is a correct one
+        Y = qg.qg_gemm_small(blob, N, K, bits, group, dev(X))
+        torch.cuda.synchronize()
+        err = scaled_error(host(Y), Y_ref, norms, X)
+        assert err <= TOL_BF16 and err <= gemm_model_bound(K), err
+        qg.qg_set_gemm_tuning(splits, shape)                 # the same choice through the knobs: same bits
+        Y2 = qg.qg_gemm_small(blob, N, K, bits, group, dev(X))
+        torch.cuda.synchronize()
+        assert np.array_equal(host(Y), host(Y2))
+    finally:
+        qg.qg_set_gemm_tuning(0, 0)
+        qg.qg_clear_tuning()
 
 
 # ------------------------------------------------------------------ full benchmark sizes
