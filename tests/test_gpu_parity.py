@@ -892,6 +892,34 @@ def test_gemm_small_random_shapes(qg, oracle, seed):
         assert err <= TOL_BF16, (N, K, group, M, splits, shape, err)
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_gemm_small_raw_code_random_shapes(qg, oracle, seed):
+    # seeded sweep of the raw-code kernel over the three widths: groups of 2 ... 16 cells inside a
+    # step and of 1 ... 3 whole steps, K that ends inside a step, ragged N and M, every count of
+    # K ranges
+    rng = np.random.default_rng(8100 + seed)
+    for case in range(7):
+        bits = int(rng.choice([2, 3, 4]))
+        cell, step = {2: (16, 256), 3: (32, 256), 4: (8, 128)}[bits]
+        cells_per_step = step // cell
+        inside = [c * cell for c in (2, 4, 8, 16) if cells_per_step % c == 0]
+        group = int(rng.choice(inside + [step, 2 * step, 3 * step]))
+        K = group * int(rng.integers(1, max(2, 3072 // group)))
+        if K % 16:
+            K *= 16 // np.gcd(K, 16)
+        N = int(rng.integers(1, 600))
+        M = int(rng.integers(2, 129))
+        splits = int(rng.integers(0, 9))
+        _announce("gemm raw codes random", seed, case, N, K, bits, group, M, splits)
+        W, X = synth.small_case(seed * 100 + case + 70, N, K, 0.02, True, m=M)
+        qg.qg_set_gemm_tuning(splits, 13)
+        try:
+            err = _gemm_case(qg, oracle, W, X, bits, group)
+        finally:
+            qg.qg_set_gemm_tuning(0, 0)
+        assert err <= TOL_BF16, (N, K, bits, group, M, splits, err)
+
+
 @pytest.mark.parametrize("shape", [0, 13])
 @pytest.mark.parametrize("index", [0, 1, 2])
 @pytest.mark.parametrize("mi", [0, 1, 2])
