@@ -388,6 +388,44 @@ def test_gemv_team_size_fallback(qg, oracle, N, K, bits, group, tuning):
     assert err <= TOL_FP32, err
 
 
+def test_calls_run_on_the_stream_they_are_given(qg, oracle):
+    # every kernel of a call goes to the caller's stream: on a side stream (default priority) that is
+    # held back by a long fill, the results are there after that stream alone has been waited for
+    _announce("side stream")
+    N, K, bits, group, M = 300, 4096, 4, 128, 24
+    W, X = synth.small_case(1600, N, K, 0.02, True, m=M)
+    q0, s0, z0 = oracle.quantize(W, bits, group)
+    norms = oracle.row_norms(q0, s0, z0, group)
+    y_ref = oracle.matvec(q0, s0, z0, group, X[0])
+    Y_ref = oracle.matmul_small(q0, s0, z0, group, X)
+    q, s, z = qg.qg_quantize(dev(W), bits, group)
+    blob = qg.qg_pack(q, s, z, bits, group)
+    Xd = dev(X)
+    x0 = Xd[0].contiguous()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    ballast = torch.empty(64 << 20, dtype=torch.float32, device="cuda")
+    with torch.cuda.stream(side):
+        ws = qg.new_workspace(qg.qg_workspace_bytes(N, K, bits, group, 1))
+        wsm = qg.new_workspace(qg.qg_workspace_bytes(N, K, bits, group, M))
+        for _ in range(4):
+            ballast.fill_(1.0)
+        y = qg.qg_gemv(blob, N, K, bits, group, x0, None, ws)
+        y2 = qg.qg_gemv_noalloc(blob, N, K, bits, group, x0, torch.empty(N, dtype=torch.float32, device="cuda"))
+        Y = qg.qg_gemm_small(blob, N, K, bits, group, Xd, None, wsm)
+        qg.qg_set_gemm_tuning(0, 13)
+        try:
+            Yc = qg.qg_gemm_small(blob, N, K, bits, group, Xd, None, wsm)
+        finally:
+            qg.qg_set_gemm_tuning(0, 0)
+    side.synchronize()
+    assert scaled_error(host(y), y_ref, norms, X[0]) <= TOL_FP32
+    assert np.array_equal(host(y), host(y2))
+    assert scaled_error(host(Y), Y_ref, norms, X) <= gemm_model_bound(K)
+    assert scaled_error(host(Yc), Y_ref, norms, X) <= gemm_model_bound(K)
+    torch.cuda.synchronize()
+
+
 def test_gemv_zero_input_and_unit_scale(qg, oracle):
     _announce("gemv x = 0, s = 1 z = 0")
     rng = np.random.default_rng(5)
