@@ -348,13 +348,13 @@ def other_workloads(qg, args):
     return out
 
 
-def bench_gemm_other_widths(qg, args):
-    """The small-M product at 3 and 2 bits: M = 16 on the three shapes of the 13B- and 65B-shaped
-    layer sets (timing only, weights drawn on the GPU), packed copies rotated."""
+def bench_gemm_other_widths(qg, args, Ms=(16,)):
+    """The small-M product at 3 and 2 bits: M = 16 (or `Ms`) on the three shapes of the 13B- and
+    65B-shaped layer sets (timing only, weights drawn on the GPU), packed copies rotated."""
     from paper_2307_03738_amd import synth
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     steps, warm = max(20, args.steps // 10), max(5, args.warmup // 10)
-    rows, M = [], 16
+    rows = []
     for name in ("C3", "C4"):
         cfg = synth.CONFIGS[name]
         gen = torch.Generator(device="cuda").manual_seed(200 + cfg.seed)
@@ -365,21 +365,24 @@ def bench_gemm_other_widths(qg, args):
             del W, q, s, z
             copies = max(2, int(np.ceil(ROTATE_BYTES / blob.numel())))
             blobs = [blob] + [blob.clone() for _ in range(copies - 1)]
-            X = torch.randn((M, K), device="cuda", generator=gen)
-            Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
-            ws = qg.new_workspace(qg.qg_workspace_bytes(N, K, cfg.bits, cfg.group, M))
-            for i in range(warm):
-                qg.qg_gemm_small(blobs[i % copies], N, K, cfg.bits, cfg.group, X, Y, ws)
-            torch.cuda.synchronize()
-            start.record()
-            for i in range(steps):
-                qg.qg_gemm_small(blobs[i % copies], N, K, cfg.bits, cfg.group, X, Y, ws)
-            stop.record()
-            torch.cuda.synchronize()
-            us = start.elapsed_time(stop) / steps * 1e3
-            byts = (cfg.bits * N * K + (32 + cfg.bits) * N * (K // cfg.group)) // 8 + 4 * M * K + 4 * M * N
-            rows.append({"N": N, "K": K, "bits": cfg.bits, "group": cfg.group, "M": M, "us": round(us, 2),
-                         "GBps": round(byts / us / 1e3, 1), "frac_of_hbm_peak": round(byts / us / 1e3 / HBM_PEAK_GBS, 4)})
+            for M in Ms:
+                X = torch.randn((M, K), device="cuda", generator=gen)
+                Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+                ws = qg.new_workspace(qg.qg_workspace_bytes(N, K, cfg.bits, cfg.group, M))
+                for i in range(warm):
+                    qg.qg_gemm_small(blobs[i % copies], N, K, cfg.bits, cfg.group, X, Y, ws)
+                torch.cuda.synchronize()
+                start.record()
+                for i in range(steps):
+                    qg.qg_gemm_small(blobs[i % copies], N, K, cfg.bits, cfg.group, X, Y, ws)
+                stop.record()
+                torch.cuda.synchronize()
+                us = start.elapsed_time(stop) / steps * 1e3
+                byts = (cfg.bits * N * K + (32 + cfg.bits) * N * (K // cfg.group)) // 8 + 4 * M * K + 4 * M * N
+                rows.append({"N": N, "K": K, "bits": cfg.bits, "group": cfg.group, "M": M, "us": round(us, 2),
+                             "GBps": round(byts / us / 1e3, 1), "frac_of_hbm_peak": round(byts / us / 1e3 / HBM_PEAK_GBS, 4),
+                             "TFLOPs": round(2.0 * M * N * K / us / 1e6, 1),
+                             "frac_of_bf16_mfma_peak": round(2.0 * M * N * K / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)})
             del blobs, blob
     return rows
 
@@ -417,6 +420,8 @@ def main():
     ap.add_argument("--config", default="C2", choices=["C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle leg (and with it the check of the timed result)")
+    ap.add_argument("--gemm-widths", action="store_true",
+                    help="the small-M product at 3 and 2 bits on the 13B- and 65B-shaped matrices, M = 16, 64, 128")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="time the headline workload only")
     ap.add_argument("--autotune", action="store_true",
@@ -445,6 +450,11 @@ def main():
     from paper_2307_03738_amd import binding as qg, synth
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
+    if args.gemm_widths:
+        rows = bench_gemm_other_widths(qg, args, (16, 64, 128))
+        print(json.dumps({"metric": "us per small-M product, 3-bit g64 and 2-bit g32", "unit": "us", "n_gpus": 1,
+                          "data": "synthetic", "dtype": "bf16", "problems": rows}))
+        return
     if args.sweep:
         qg.qg_set_gemv_tuning(args.wpb, args.bytes_per_wave, args.kernel)
         print(json.dumps(bench_sweep(qg, args)))
