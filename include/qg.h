@@ -172,6 +172,9 @@ int qg_gemv_swiglu(const void *packed, int64_t I, int64_t K, int bits, int group
  *     matrix instruction as exact bf16 integers, X is rounded to bf16, and scale and zero-point
  *     are applied in fp32 once per group and element of Y (eq. (2)); X is converted by a
  *     kernel of its own first, so a call enqueues two or three kernels.
+ * Where both apply (4 bits) the first is used, except beyond 64 rows on matrices of 4096 tile-steps
+ * or more (64 outputs x 128 k each), where the second measured faster; qg_set_gemm_tuning and
+ * qg_gemm_autotune choose otherwise.
  * Every other layout (odd numbers of cells per group, K % 16 != 0 only with M == 1) runs
  * qg_gemv once per row in fp32, 16 rows per launch; with K % 16 != 0 and M > 1 the call returns
  * QG_ERR_UNSUPPORTED.  M == 1 is qg_gemv.
