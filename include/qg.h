@@ -52,7 +52,11 @@ typedef enum {
     QG_LAYOUT_CANONICAL = 0,
     /* The layout qg_gemv and qg_gemm_small read.  Opaque; a pure permutation of the same
      * codes, scales and zero-points (plus zero padding), fixed by (N, K, bits, group). */
-    QG_LAYOUT_DEVICE = 1
+    QG_LAYOUT_DEVICE = 1,
+    /* The layout qg_gemv_narrow reads (made from a QG_LAYOUT_DEVICE blob by qg_to_narrow): the same
+     * bytes in rows of 16 outputs x 4 steps of K.  Only qg_packed_bytes, qg_to_narrow,
+     * qg_from_narrow and the qg_gemv*_narrow calls know it. */
+    QG_LAYOUT_DEVICE_NARROW = 2
 } qg_layout;
 
 /* Smallest granule of codes the kernels decode at once: 8 codes (one word) at 4 bits, 16
@@ -185,6 +189,27 @@ int qg_gemv_swiglu(const void *packed, int64_t I, int64_t K, int bits, int group
 int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
                   const float *X, int M, float *Y,
                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* The GEMV on the narrow layout: y = What x as qg_gemv computes it (eq. (1), (2), Algorithm 1;
+ * same arithmetic, same <= 1e-4 bound, bitwise deterministic), for launches made of short matrices,
+ * where it is faster.  A workgroup covers the whole K of its 16 outputs, so nothing is added
+ * across workgroups: these calls need no workspace and allocate nothing.
+ * Formats: K a whole number of steps (128 k at 4 bits, 256 at 2 and 3), G from 16 (32 at 3 bits)
+ * up to one step and dividing a step, K <= 32768 at 4 bits and 65536 otherwise; anything else
+ * returns QG_ERR_UNSUPPORTED (from qg_packed_bytes: 0).
+ *   qg_to_narrow:   packed = QG_LAYOUT_DEVICE blob (DEVICE) -> narrow, qg_packed_bytes(...,
+ *                   QG_LAYOUT_DEVICE_NARROW) bytes (DEVICE, 16-byte aligned, caller's); a permutation
+ *                   of 16-byte pieces, scales and zero words plus zero padding; qg_from_narrow is its
+ *                   inverse and gives back the QG_LAYOUT_DEVICE blob byte for byte.
+ *   qg_gemv_narrow / qg_gemv_grouped_narrow: as qg_gemv / qg_gemv_grouped with `packed` in the
+ *                   narrow layout (descs HOST; x 64-byte aligned; y overwritten).
+ * qg_last_narrow_kernel: name of the kernel instance of the last such launch ("" before). */
+int qg_to_narrow(const void *packed, int64_t N, int64_t K, int bits, int group, void *narrow, void *stream);
+int qg_from_narrow(const void *narrow, int64_t N, int64_t K, int bits, int group, void *packed, void *stream);
+int qg_gemv_narrow(const void *narrow, int64_t N, int64_t K, int bits, int group,
+                   const float *x, float *y, void *stream);
+int qg_gemv_grouped_narrow(const qg_gemv_desc *descs /* HOST */, int count, void *stream);
+const char *qg_last_narrow_kernel(void);
 
 /* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe; while one of them
  * is non-zero they apply to every launch and the recorded tunings below are not consulted).  0

@@ -14,6 +14,7 @@ from . import build as _build
 
 QG_LAYOUT_CANONICAL = 0
 QG_LAYOUT_DEVICE = 1
+QG_LAYOUT_DEVICE_NARROW = 2
 QG_MAX_GROUPED = 16
 
 _LIB = None
@@ -83,6 +84,16 @@ def lib():
         L.qg_gemv_autotune_report.argtypes = [ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.qg_set_gemm_tuning.restype = i32
         L.qg_set_gemm_tuning.argtypes = [i32, i32]
+        L.qg_to_narrow.restype = i32
+        L.qg_to_narrow.argtypes = [vp, i64, i64, i32, i32, vp, vp]
+        L.qg_from_narrow.restype = i32
+        L.qg_from_narrow.argtypes = [vp, i64, i64, i32, i32, vp, vp]
+        L.qg_gemv_narrow.restype = i32
+        L.qg_gemv_narrow.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
+        L.qg_gemv_grouped_narrow.restype = i32
+        L.qg_gemv_grouped_narrow.argtypes = [ctypes.POINTER(_Desc), i32, vp]
+        L.qg_last_narrow_kernel.restype = ctypes.c_char_p
+        L.qg_last_narrow_kernel.argtypes = []
         L.qg_gemv_record_tuning.restype = i32
         L.qg_gemv_record_tuning.argtypes = [ctypes.POINTER(_Desc), i32, i32, i32, i32]
         L.qg_clear_tuning.restype = None
@@ -198,6 +209,75 @@ def qg_gemv_noalloc(packed: torch.Tensor, N: int, K: int, bits: int, group: int,
     _check(lib().qg_gemv_noalloc(packed.data_ptr(), N, K, bits, group, x.data_ptr(), y.data_ptr(), _stream()),
            "qg_gemv_noalloc")
     return y
+
+
+def qg_to_narrow(packed: torch.Tensor, N: int, K: int, bits: int, group: int) -> torch.Tensor:
+    """The narrow-layout copy of a QG_LAYOUT_DEVICE blob."""
+    _dev(packed, torch.uint8, "packed")
+    nbytes = qg_packed_bytes(N, K, bits, group, QG_LAYOUT_DEVICE_NARROW)
+    if nbytes == 0:
+        _check(3, "qg_to_narrow")
+    if packed.numel() < qg_packed_bytes(N, K, bits, group, QG_LAYOUT_DEVICE):
+        _check(2, "qg_to_narrow")
+    out = torch.empty(nbytes, dtype=torch.uint8, device=packed.device)
+    _check(lib().qg_to_narrow(packed.data_ptr(), N, K, bits, group, out.data_ptr(), _stream()), "qg_to_narrow")
+    return out
+
+
+def qg_from_narrow(narrow: torch.Tensor, N: int, K: int, bits: int, group: int) -> torch.Tensor:
+    _dev(narrow, torch.uint8, "narrow")
+    if narrow.numel() < qg_packed_bytes(N, K, bits, group, QG_LAYOUT_DEVICE_NARROW) or \
+            qg_packed_bytes(N, K, bits, group, QG_LAYOUT_DEVICE_NARROW) == 0:
+        _check(2, "qg_from_narrow")
+    out = torch.empty(qg_packed_bytes(N, K, bits, group, QG_LAYOUT_DEVICE), dtype=torch.uint8, device=narrow.device)
+    _check(lib().qg_from_narrow(narrow.data_ptr(), N, K, bits, group, out.data_ptr(), _stream()), "qg_from_narrow")
+    return out
+
+
+def qg_gemv_narrow(narrow: torch.Tensor, N: int, K: int, bits: int, group: int, x: torch.Tensor,
+                   y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(narrow, torch.uint8, "narrow"); _dev(x, torch.float32, "x")
+    nbytes = qg_packed_bytes(N, K, bits, group, QG_LAYOUT_DEVICE_NARROW)
+    if nbytes == 0:
+        _check(3, "qg_gemv_narrow")
+    if x.numel() != K or narrow.numel() < nbytes:
+        _check(2, "qg_gemv_narrow")
+    if y is None:
+        y = torch.empty(N, dtype=torch.float32, device=x.device)
+    _dev(y, torch.float32, "y")
+    if y.numel() != N:
+        _check(2, "qg_gemv_narrow")
+    _check(lib().qg_gemv_narrow(narrow.data_ptr(), N, K, bits, group, x.data_ptr(), y.data_ptr(), _stream()),
+           "qg_gemv_narrow")
+    return y
+
+
+class GroupedGemvNarrow:
+    """A prepared grouped launch on narrow-layout blobs (dicts with packed, N, K, bits, group, x, y)."""
+
+    def __init__(self, problems: Sequence[dict]):
+        self.count = len(problems)
+        self.descs = (_Desc * self.count)()
+        self._keep = list(problems)
+        for i, p in enumerate(problems):
+            _dev(p["packed"], torch.uint8, "packed"); _dev(p["x"], torch.float32, "x"); _dev(p["y"], torch.float32, "y")
+            nbytes = qg_packed_bytes(p["N"], p["K"], p["bits"], p["group"], QG_LAYOUT_DEVICE_NARROW)
+            if nbytes == 0:
+                _check(3, "qg_gemv_grouped_narrow")
+            if p["x"].numel() != p["K"] or p["y"].numel() != p["N"] or p["packed"].numel() < nbytes:
+                _check(2, "qg_gemv_grouped_narrow")
+            self.descs[i] = _Desc(p["packed"].data_ptr(), p["N"], p["K"], p["bits"], p["group"],
+                                  p["x"].data_ptr(), p["y"].data_ptr())
+        self._fn = lib().qg_gemv_grouped_narrow
+
+    def launch(self, stream: Optional[int] = None):
+        rc = self._fn(self.descs, self.count, _stream() if stream is None else stream)
+        if rc != 0:
+            _check(rc, "qg_gemv_grouped_narrow")
+
+
+def qg_last_narrow_kernel() -> str:
+    return lib().qg_last_narrow_kernel().decode()
 
 
 def qg_last_gemv_kernel() -> str:

@@ -1,0 +1,534 @@
+// libqg: the GEMV on the "narrow" device layout.
+//
+// y[n] = sum_g s[n][g] ( sum_{k in g} q[n][k] x[k]  -  z[n][g] sum_{k in g} x[k] )       (eq. (2))
+//
+// Same arithmetic as gemv_mma4i (qg_gemv.hip): codes enter v_mfma_i32_4x4x4_16B_i8 as int8 after
+// masks, x as 32-bit fixed point cut into four signed base-256 digits, groups closed in fp32.
+// What differs is which outputs and which k a wavefront's 1 KB load holds.
+//
+// The wide device layout gives a wavefront 64 outputs x one step of K per loop iteration, so a
+// matrix with K = 4096 is 32 steps deep and a launch of short jobs (a few KB per wavefront, handed
+// out by the hardware as others end -- what streams fastest on this machine) has to add partial
+// results of several workgroups per output.  The narrow layout holds the same bytes in rows of
+// 16 outputs x 4 steps: lane = 16 * slice + output, slice j of wave-step w being step 4 w + j.
+// Eight wavefronts with one wave-step each then cover K = 4096 (4 bits) of their 16 outputs, a
+// workgroup owns its outputs, and nothing is added across workgroups: no workspace, no atomics.
+//
+//   codes : uint4  [tile16][wave-step][load][lane]     lane = 16 * slice + output
+//   scales: float  [tile16][wave-step][group of the step][lane]
+//   zeros : uint32 [tile16][zword][output]             the wide layout's zero words
+//
+// Steps past the end of K and outputs past N hold zero codes and zero scales.
+#include <hip/hip_runtime.h>
+#include <cstdio>
+#include <stdint.h>
+
+#include "qg_common.h"
+#include "qg_mma.h"
+
+namespace {
+
+constexpr int NW_OUT = 16;             // outputs per wavefront
+constexpr int NW_SLICES = 4;           // steps per wave-step
+constexpr int NW_MAX_TEAM = 8;         // wavefronts per workgroup
+constexpr int NW_MAX_SPW = 8;          // wave-steps one wavefront takes at most
+
+struct NarrowLayout {
+    int bits, group, gps, loads;       // gps: groups per step; loads: 128-bit vectors per lane and step
+    int64_t N, K, tiles16, steps, wsteps, zwords;
+    size_t codes_off, scales_off, zeros_off, total;
+    QgLayout wide;
+};
+
+// The formats the narrow layout takes: K a whole number of steps, groups of 16 weights (32 at 3
+// bits) up to one step that divide a step, K within what one workgroup covers.
+int make_narrow_layout(int64_t N, int64_t K, int bits, int group, NarrowLayout *L)
+{
+    const int rc = qg_make_layout(N, K, bits, group, &L->wide);
+    if (rc != QG_OK) return rc;
+    const int S = L->wide.unit * L->wide.step_units;
+    if (K % S != 0 || group > S || S % group != 0 || group < (bits == 3 ? 32 : 16)) return QG_ERR_UNSUPPORTED;
+    L->bits = bits;
+    L->group = group;
+    L->gps = S / group;
+    L->loads = L->wide.step_units * L->wide.planes;
+    L->N = N;
+    L->K = K;
+    L->tiles16 = (N + NW_OUT - 1) / NW_OUT;
+    L->steps = L->wide.steps;
+    L->wsteps = (L->steps + NW_SLICES - 1) / NW_SLICES;
+    if (L->wsteps > NW_MAX_TEAM * NW_MAX_SPW) return QG_ERR_UNSUPPORTED;
+    L->zwords = L->wide.zwords;
+    L->codes_off = 0;
+    const size_t codes_bytes = (size_t)L->tiles16 * L->wsteps * L->loads * QG_WAVE * 16;
+    L->scales_off = qg_round_up(codes_bytes, QG_SECTION_ALIGN);
+    const size_t scales_bytes = (size_t)L->tiles16 * L->wsteps * L->gps * QG_WAVE * 4;
+    L->zeros_off = qg_round_up(L->scales_off + scales_bytes, QG_SECTION_ALIGN);
+    const size_t zeros_bytes = (size_t)L->tiles16 * L->zwords * NW_OUT * 4;
+    L->total = qg_round_up(L->zeros_off + zeros_bytes, QG_SECTION_ALIGN);
+    return QG_OK;
+}
+
+// ---- wide <-> narrow: a permutation of 16-byte pieces, scales and zero words ------------------
+struct RepackArgs {
+    const char *src;
+    char *dst;
+    size_t w_codes, w_scales, w_zeros;      // section offsets of the wide blob
+    size_t n_codes, n_scales, n_zeros;      // ... of the narrow blob
+    long tiles64, tiles16, steps, wsteps, ngroups, zwords;
+    int loads, gps;
+};
+
+// One thread per element of the narrow blob's three sections (codes, then scales, then zeros).
+// to_narrow: narrow[e] = wide[its source] or 0; otherwise wide[source of e] = narrow[e].
+template <bool TO_NARROW>
+__global__ void repack_narrow(const RepackArgs A)
+{
+    const size_t n_code = (size_t)A.tiles16 * A.wsteps * A.loads * QG_WAVE;
+    const size_t n_scale = (size_t)A.tiles16 * A.wsteps * A.gps * QG_WAVE;
+    const size_t n_zero = (size_t)A.tiles16 * A.zwords * NW_OUT;
+    size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < n_code) {
+        const int lane = (int)(e % QG_WAVE);
+        size_t r = e / QG_WAVE;
+        const int i = (int)(r % A.loads);
+        r /= A.loads;
+        const long w = (long)(r % A.wsteps), T = (long)(r / A.wsteps);
+        const long t = NW_SLICES * w + (lane >> 4), tile = T / 4;
+        const int lane64 = (int)(T % 4) * NW_OUT + (lane & 15);
+        const bool real = t < A.steps;
+        const size_t wide = ((size_t)(tile * A.steps + (real ? t : 0)) * A.loads + i) * QG_WAVE + lane64;
+        uint4 *n = (uint4 *)(A.dst + A.n_codes) + e;
+        if (TO_NARROW) *n = real ? ((const uint4 *)(A.src + A.w_codes))[wide] : make_uint4(0u, 0u, 0u, 0u);
+        else if (real) ((uint4 *)(A.dst + A.w_codes))[wide] = ((const uint4 *)(A.src + A.n_codes))[e];
+        return;
+    }
+    e -= n_code;
+    if (e < n_scale) {
+        const int lane = (int)(e % QG_WAVE);
+        size_t r = e / QG_WAVE;
+        const int gs = (int)(r % A.gps);
+        r /= A.gps;
+        const long w = (long)(r % A.wsteps), T = (long)(r / A.wsteps);
+        const long t = NW_SLICES * w + (lane >> 4), tile = T / 4;
+        const int lane64 = (int)(T % 4) * NW_OUT + (lane & 15);
+        const bool real = t < A.steps;
+        const size_t wide = (size_t)(tile * A.ngroups + (real ? t * A.gps + gs : 0)) * QG_WAVE + lane64;
+        if (TO_NARROW) ((float *)(A.dst + A.n_scales))[e] = real ? ((const float *)(A.src + A.w_scales))[wide] : 0.0f;
+        else if (real) ((float *)(A.dst + A.w_scales))[wide] = ((const float *)(A.src + A.n_scales))[e];
+        return;
+    }
+    e -= n_scale;
+    if (e < n_zero) {
+        const int o = (int)(e % NW_OUT);
+        const size_t r = e / NW_OUT;
+        const long zw = (long)(r % A.zwords), T = (long)(r / A.zwords);
+        const size_t wide = (size_t)((T / 4) * A.zwords + zw) * QG_WAVE + (T % 4) * NW_OUT + o;
+        if (TO_NARROW) ((uint32_t *)(A.dst + A.n_zeros))[e] = ((const uint32_t *)(A.src + A.w_zeros))[wide];
+        else ((uint32_t *)(A.dst + A.w_zeros))[wide] = ((const uint32_t *)(A.src + A.n_zeros))[e];
+    }
+}
+
+__global__ void zero_bytes16(uint4 *p, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+// ---- the kernel --------------------------------------------------------------------------------
+struct NarrowProblem {
+    const uint4 *codes;
+    const float *scales;
+    const uint32_t *zeros;
+    const float *x;
+    float *y;
+    int N, steps, wsteps, zwords;
+    int spw;                // wave-steps per wavefront
+    int team;               // wavefronts with work
+    int pad;
+};
+struct NarrowArgs {
+    int block_begin[QG_MAX_GROUPED];    // first workgroup of each problem; 0x7fffffff past the last
+    NarrowProblem p[QG_MAX_GROUPED];
+};
+
+typedef int nw_acc __attribute__((ext_vector_type(4)));
+typedef uint8_t __attribute__((may_alias)) nw_lds_u8;
+typedef uint32_t __attribute__((may_alias)) nw_lds_u32;
+
+// v op (v moved across lanes by the DPP control CTRL), inside rows of 16 lanes
+template <int CTRL>
+__device__ inline float nw_dpp_max(float v)
+{
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+    return fmaxf(v, __int_as_float(moved));
+}
+template <int CTRL>
+__device__ inline float nw_dpp_add(float v)
+{
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+    return v + __int_as_float(moved);
+}
+constexpr int NW_QUAD_XOR1 = 0xB1, NW_QUAD_XOR2 = 0x4E, NW_HALF_MIRROR = 0x141, NW_ROW_MIRROR = 0x140;
+constexpr int NW_ROW_BCAST0 = 0x150;          // lane n of every row to all lanes of the row: 0x150 + n
+
+// Where value e of a lane's XPL consecutive x values goes among the lane's XPL operand bytes (the
+// order the masked code fields have inside the B operands), and what its field counts.
+template <int BITS>
+__device__ constexpr int nw_byte_of(int e)
+{
+    return BITS == 4 ? (e % 2) * 4 + e / 2 : BITS == 2 ? (e % 4) * 4 + e / 4 : e;
+}
+template <int BITS>
+__device__ constexpr int nw_value_at(int byte)      // inverse of nw_byte_of
+{
+    return BITS == 4 ? 2 * (byte % 4) + byte / 4 : BITS == 2 ? 4 * (byte % 4) + byte / 4 : byte;
+}
+template <int BITS>
+__device__ constexpr float nw_xdiv(int e)           // 1 / (what the field of the code that meets value e counts)
+{
+    return BITS == 3 ? ((e & 7) >= 4 ? 0.125f : 1.0f)
+         : BITS == 2 ? ((e & 3) == 1 ? 0.25f : (e & 3) == 2 ? 0.0625f : 1.0f)
+                     : 1.0f;
+}
+
+// lane G * LPG of every row of 16 lanes to all lanes of the row, for G = 0 .. GPS - 1
+template <int GPS, int LPG, int G = 0>
+__device__ inline void nw_spread(float part, float *xhat)
+{
+    if constexpr (G < GPS) {
+        xhat[G] = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(part), NW_ROW_BCAST0 + G * LPG, 0xf, 0xf, false));
+        nw_spread<GPS, LPG, G + 1>(part, xhat);
+    }
+}
+
+template <int BITS, int GPS>
+__global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(const NarrowArgs A)
+{
+    using F = Fmt<BITS>;
+    constexpr int L = loads_per_step<BITS>();
+    constexpr int S = codes_per_step<BITS>();
+    constexpr int XPL = S / NW_OUT;                 // x values per lane and wave-step: 8 or 16
+    constexpr int READS = S / 16;                   // 128-bit reads of A per step, four matrix instructions each
+    constexpr int RPG = READS / GPS;
+    constexpr int LPG = NW_OUT / GPS;               // lanes whose x values make up one group
+    constexpr int ZPER = 32 / F::ZBITS;
+    constexpr int PITCH = S + 16;                   // bytes per digit row: the four rows on different banks
+    static_assert(GPS >= 1 && GPS <= NW_OUT && READS % GPS == 0 && ZPER % GPS == 0, "groups of a step");
+    __shared__ float red[NW_MAX_TEAM][NW_OUT];
+    // per wavefront and slice: the four digit rows of the slice's x in operand order
+    __shared__ __attribute__((aligned(16))) nw_lds_u8 xs[NW_MAX_TEAM][NW_SLICES][4][PITCH];
+
+    // which problem: the table of first workgroups comes in with one scalar load, the entry with another
+    int pi = 0;
+#pragma unroll
+    for (int i = 1; i < QG_MAX_GROUPED; ++i) pi += (int)blockIdx.x >= A.block_begin[i] ? 1 : 0;
+    const NarrowProblem P = A.p[pi];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int T = blockIdx.x - A.block_begin[pi];
+    const int j = lane >> 4, o = lane & 15;
+    const int w0 = wave * P.spw;
+    if (w0 >= P.wsteps) return;                     // no work: leave before the barrier
+    const int w1 = w0 + P.spw < P.wsteps ? w0 + P.spw : P.wsteps;
+
+    // uniform bases; what a lane adds to them fits 32 bits
+    const uint4 *codes = P.codes + (size_t)T * P.wsteps * L * QG_WAVE;
+    const float *scales = P.scales + (size_t)T * P.wsteps * GPS * QG_WAVE;
+    const uint32_t *zeros = P.zeros + (size_t)T * P.zwords * NW_OUT;
+    nw_lds_u8 *mine = &xs[wave][j][0][0] + o * XPL;              // this lane's bytes of digit row 0
+    const nw_lds_u8 *abase = &xs[wave][j][lane & 3][0];         // the digit row this lane supplies to its block
+
+    float yacc = 0.0f;
+    for (int w = w0; w < w1; ++w) {
+        // A slice past the end of K has zero codes and zero scales and adds nothing whatever x it
+        // meets; it takes the last step's x (its output meets that x in a real slice as well).
+        const int t = NW_SLICES * w + j;
+        const uint32_t tc = (uint32_t)(t < P.steps ? t : P.steps - 1);
+        // x goes first: loads return in order, and its digits are made while the codes are on their way
+        float xv[XPL];
+        {
+            const float4 *src = (const float4 *)P.x;
+#pragma unroll
+            for (int q = 0; q < XPL / 4; ++q) {
+                const float4 f = src[tc * (S / 4) + (uint32_t)o * (XPL / 4) + q];
+                xv[4 * q + 0] = f.x;
+                xv[4 * q + 1] = f.y;
+                xv[4 * q + 2] = f.z;
+                xv[4 * q + 3] = f.w;
+            }
+        }
+        uint4 v[L];
+#pragma unroll
+        for (int i = 0; i < L; ++i) v[i] = codes[(uint32_t)(w * L + i) * QG_WAVE + lane];
+        float s[GPS];
+#pragma unroll
+        for (int g = 0; g < GPS; ++g) s[g] = scales[(uint32_t)(w * GPS + g) * QG_WAVE + lane];
+        const uint32_t g0 = tc * GPS;                             // a step's groups share one zero word
+        const uint32_t zword = zeros[(g0 / ZPER) * NW_OUT + o] >> (F::ZBITS * (g0 % ZPER));
+
+        // fixed point of the slice: |x| scale < 2^30 for its largest |x|
+        float m = 0.0f;
+#pragma unroll
+        for (int e = 0; e < XPL; ++e) m = fmaxf(m, fabsf(xv[e]));
+        m = nw_dpp_max<NW_QUAD_XOR1>(m);
+        m = nw_dpp_max<NW_QUAD_XOR2>(m);
+        m = nw_dpp_max<NW_HALF_MIRROR>(m);
+        m = nw_dpp_max<NW_ROW_MIRROR>(m);                         // every lane of the row holds the row's maximum
+        uint32_t eb = __float_as_uint(m) >> 23;                   // biased exponent (m >= 0)
+        eb = eb < 30u ? 30u : eb > 254u ? 254u : eb;
+        const float scale = __uint_as_float((283u - eb) << 23);   // 2^(156 - eb)
+        const float inv = __uint_as_float((eb - 29u) << 23);      // 2^(eb - 156)
+        uint32_t pat[XPL];
+#pragma unroll
+        for (int e = 0; e < XPL; ++e) {
+            const int fixed = (int)(xv[e] * (scale * nw_xdiv<BITS>(e)));
+            // the four bytes of (fixed + 0x808080) ^ 0x808080, read as signed, are digits base 256 of `fixed`
+            pat[e] = ((uint32_t)fixed + 0x00808080u) ^ 0x00808080u;
+        }
+        // digit row r of this lane: byte b holds digit r of the value that belongs at byte b
+        // (a 4 x 4 byte transpose per four values)
+#pragma unroll
+        for (int d = 0; d < XPL / 4; ++d) {
+            const uint32_t p0 = pat[nw_value_at<BITS>(4 * d + 0)], p1 = pat[nw_value_at<BITS>(4 * d + 1)];
+            const uint32_t p2 = pat[nw_value_at<BITS>(4 * d + 2)], p3 = pat[nw_value_at<BITS>(4 * d + 3)];
+            const uint32_t lo01 = __builtin_amdgcn_perm(p1, p0, 0x05010400u), hi01 = __builtin_amdgcn_perm(p1, p0, 0x07030602u);
+            const uint32_t lo23 = __builtin_amdgcn_perm(p3, p2, 0x05010400u), hi23 = __builtin_amdgcn_perm(p3, p2, 0x07030602u);
+            *(nw_lds_u32 *)(mine + 0 * PITCH + 4 * d) = __builtin_amdgcn_perm(lo23, lo01, 0x05040100u);
+            *(nw_lds_u32 *)(mine + 1 * PITCH + 4 * d) = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
+            *(nw_lds_u32 *)(mine + 2 * PITCH + 4 * d) = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
+            *(nw_lds_u32 *)(mine + 3 * PITCH + 4 * d) = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
+        }
+
+        // x-hat of the slice's groups: the lanes of a group add up, every lane of the row gets every sum
+        float part = 0.0f;
+#pragma unroll
+        for (int e = 0; e < XPL; ++e) part += xv[e];
+        if constexpr (LPG >= 2) part = nw_dpp_add<NW_QUAD_XOR1>(part);
+        if constexpr (LPG >= 4) part = nw_dpp_add<NW_QUAD_XOR2>(part);
+        if constexpr (LPG >= 8) part = nw_dpp_add<NW_HALF_MIRROR>(part);
+        if constexpr (LPG >= 16) part = nw_dpp_add<NW_ROW_MIRROR>(part);
+        float xhat[GPS];
+        if constexpr (GPS == 1) {
+            xhat[0] = part;
+        } else {
+            nw_spread<GPS, LPG>(part, xhat);
+        }
+
+        // the matrix instructions: per 128-bit read of A (16 k) two 4-bit cells, one 2-bit cell or
+        // half a 3-bit cell; lane l receives the sums of its own output
+        nw_acc acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+        uint32_t spare = 0;
+#pragma unroll
+        for (int rd = 0; rd < READS; ++rd) {
+            MmaOperand a;
+            a.q = *(const lds_u128 *)(abase + rd * 16);
+            uint32_t b[4];
+            if constexpr (BITS == 4) {
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const int cell = 2 * rd + c;
+                    const uint32_t wd = word_of(v[cell >> 2], cell & 3);
+                    b[2 * c] = wd & 0x0f0f0f0fu;
+                    b[2 * c + 1] = (wd >> 4) & 0x0f0f0f0fu;
+                }
+            } else if constexpr (BITS == 2) {
+                const uint32_t wd = word_of(v[rd >> 2], rd & 3);
+                b[0] = wd & 0x03030303u;
+                b[1] = wd & 0x0c0c0c0cu;
+                b[2] = wd & 0x30303030u;
+                b[3] = (wd >> 6) & 0x03030303u;
+            } else {
+                const int cell = rd >> 1, u = cell >> 2, c = cell & 3;
+                if ((rd & 1) == 0) {
+                    const uint32_t wa = word_of(v[u * 3], c), wb = word_of(v[u * 3 + 1], c), wc = word_of(v[u * 3 + 2], c);
+                    spare = ((wa >> 6) & 0x03030303u) | ((wb >> 4) & 0x0c0c0c0cu) | ((wc >> 2) & 0x30303030u);
+                    b[0] = wa & 0x07070707u;
+                    b[1] = wa & 0x38383838u;
+                    b[2] = wb & 0x07070707u;
+                    b[3] = wb & 0x38383838u;
+                } else {
+                    const uint32_t wc = word_of(v[u * 3 + 2], c);
+                    b[0] = wc & 0x07070707u;
+                    b[1] = wc & 0x38383838u;
+                    b[2] = spare & 0x07070707u;
+                    b[3] = spare & 0x38383838u;
+                }
+            }
+            acc0 = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[0], (int)b[0], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[1], (int)b[1], acc1, 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[2], (int)b[2], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[3], (int)b[3], acc1, 0, 0, 0);
+            if ((rd + 1) % RPG == 0) {
+                const int gs = (rd + 1) / RPG - 1;
+                // sum_i 256^i D_i of the group, in units of 1 / scale (|D_i| stays below 2^21)
+                const int lo = (acc0[1] + acc1[1]) * 256 + (acc0[0] + acc1[0]);
+                const int hi = (acc0[3] + acc1[3]) * 256 + (acc0[2] + acc1[2]);
+                acc0 = nw_acc{0, 0, 0, 0};
+                acc1 = nw_acc{0, 0, 0, 0};
+                const float tsum = fmaf((float)hi, 65536.0f, (float)lo) * inv;
+                const uint32_t zq = (zword >> (F::ZBITS * gs)) & ((1u << F::ZBITS) - 1u);
+                yacc = fmaf(s[gs], fmaf(-(float)zq, xhat[gs], tsum), yacc);
+            }
+        }
+    }
+
+    // the four slices of an output, then the wavefronts of the workgroup in order
+    yacc += __shfl_xor(yacc, 16, QG_WAVE);
+    yacc += __shfl_xor(yacc, 32, QG_WAVE);
+    if (lane < NW_OUT) red[wave][lane] = yacc;
+    __syncthreads();
+    if (wave != 0 || lane >= NW_OUT) return;
+    float sum = red[0][lane];
+    for (int k = 1; k < P.team; ++k) sum += red[k][lane];
+    const int n = T * NW_OUT + lane;
+    if (n < P.N) P.y[n] = sum;
+}
+
+typedef void (*NarrowKernel)(const NarrowArgs);
+
+template <int BITS>
+NarrowKernel pick_narrow(int gps)
+{
+    switch (gps) {
+    case 1: return gemv_narrow<BITS, 1>;
+    case 2: return gemv_narrow<BITS, 2>;
+    case 4: return gemv_narrow<BITS, 4>;
+    case 8: return gemv_narrow<BITS, 8>;
+    case 16:
+        if constexpr (BITS == 2) return gemv_narrow<2, 16>;
+        return nullptr;
+    default: return nullptr;
+    }
+}
+
+char g_narrow_kernel[48] = "";
+
+int repack(const void *src, void *dst, int64_t N, int64_t K, int bits, int group, bool to_narrow, hipStream_t st)
+{
+    NarrowLayout L;
+    const int rc = make_narrow_layout(N, K, bits, group, &L);
+    if (rc != QG_OK) return rc;
+    if (!src || !dst) return QG_ERR_NULL;
+    if (!qg_aligned16(src) || !qg_aligned16(dst)) return QG_ERR_ALIGN;
+    RepackArgs A;
+    A.src = (const char *)src;
+    A.dst = (char *)dst;
+    A.w_codes = L.wide.codes_off; A.w_scales = L.wide.scales_off; A.w_zeros = L.wide.zeros_off;
+    A.n_codes = L.codes_off; A.n_scales = L.scales_off; A.n_zeros = L.zeros_off;
+    A.tiles64 = (long)L.wide.tiles; A.tiles16 = (long)L.tiles16; A.steps = (long)L.steps; A.wsteps = (long)L.wsteps;
+    A.ngroups = (long)L.wide.ngroups; A.zwords = (long)L.zwords;
+    A.loads = L.loads; A.gps = L.gps;
+    const size_t elements = (size_t)L.tiles16 * L.wsteps * L.loads * QG_WAVE + (size_t)L.tiles16 * L.wsteps * L.gps * QG_WAVE +
+                            (size_t)L.tiles16 * L.zwords * NW_OUT;
+    const unsigned blocks = (unsigned)((elements + 255) / 256);
+    // the destination is cleared first: the gaps between its sections, and (wide) the outputs past
+    // the last tile of 16, are written by nothing else
+    const size_t n16 = (to_narrow ? L.total : L.wide.total) / 16;
+    hipLaunchKernelGGL(zero_bytes16, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, (uint4 *)dst, n16);
+    if (qg_launch_status() != QG_OK) return QG_ERR_DEVICE;
+    if (to_narrow) hipLaunchKernelGGL(repack_narrow<true>, dim3(blocks), dim3(256), 0, st, A);
+    else hipLaunchKernelGGL(repack_narrow<false>, dim3(blocks), dim3(256), 0, st, A);
+    return qg_launch_status();
+}
+}  // namespace
+
+size_t qg_narrow_bytes(int64_t N, int64_t K, int bits, int group)
+{
+    NarrowLayout L;
+    return make_narrow_layout(N, K, bits, group, &L) == QG_OK ? L.total : 0;
+}
+
+extern "C" int qg_to_narrow(const void *packed, int64_t N, int64_t K, int bits, int group, void *narrow, void *stream)
+{
+    return repack(packed, narrow, N, K, bits, group, true, (hipStream_t)stream);
+}
+
+extern "C" int qg_from_narrow(const void *narrow, int64_t N, int64_t K, int bits, int group, void *packed, void *stream)
+{
+    return repack(narrow, packed, N, K, bits, group, false, (hipStream_t)stream);
+}
+
+extern "C" const char *qg_last_narrow_kernel(void) { return g_narrow_kernel; }
+
+extern "C" int qg_gemv_grouped_narrow(const qg_gemv_desc *descs, int count, void *stream)
+{
+    if (!descs) return QG_ERR_NULL;
+    if (count <= 0) return QG_ERR_SHAPE;
+    if (count > QG_MAX_GROUPED) return QG_ERR_UNSUPPORTED;
+    NarrowLayout L[QG_MAX_GROUPED];
+    for (int i = 0; i < count; ++i) {
+        const int rc = make_narrow_layout(descs[i].N, descs[i].K, descs[i].bits, descs[i].group, &L[i]);
+        if (rc != QG_OK) return rc;
+        if (!descs[i].packed || !descs[i].x || !descs[i].y) return QG_ERR_NULL;
+        if (!qg_aligned16(descs[i].packed) || ((uintptr_t)descs[i].x & 63u)) return QG_ERR_ALIGN;
+        if (L[i].tiles16 > (1 << 24)) return QG_ERR_SHAPE;
+    }
+    // one launch per (bits, groups per step); inside a launch the longest K first, so that the
+    // wavefronts that run longest start first.  Two passes: every launch is planned before the
+    // first one is enqueued.
+    for (int pass = 0; pass < 2; ++pass) {
+        bool done[QG_MAX_GROUPED] = {false};
+        for (int i = 0; i < count; ++i) {
+            if (done[i]) continue;
+            int idx[QG_MAX_GROUPED], n = 0;
+            for (int k = i; k < count; ++k)
+                if (!done[k] && L[k].bits == L[i].bits && L[k].gps == L[i].gps) {
+                    idx[n++] = k;
+                    done[k] = true;
+                }
+            for (int a = 1; a < n; ++a)
+                for (int b = a; b > 0 && L[idx[b]].K > L[idx[b - 1]].K; --b) {
+                    const int t = idx[b]; idx[b] = idx[b - 1]; idx[b - 1] = t;
+                }
+            const NarrowKernel fn = L[i].bits == 4 ? pick_narrow<4>(L[i].gps) : L[i].bits == 2 ? pick_narrow<2>(L[i].gps) : pick_narrow<3>(L[i].gps);
+            if (!fn) return QG_ERR_UNSUPPORTED;
+            NarrowArgs A;
+            for (int k = 0; k < QG_MAX_GROUPED; ++k) A.block_begin[k] = 0x7fffffff;
+            long blocks = 0;
+            int team_max = 1;
+            for (int k = 0; k < n; ++k) {
+                const NarrowLayout &Lk = L[idx[k]];
+                const qg_gemv_desc &d = descs[idx[k]];
+                NarrowProblem &P = A.p[k];
+                const char *base = (const char *)d.packed;
+                P.codes = (const uint4 *)(base + Lk.codes_off);
+                P.scales = (const float *)(base + Lk.scales_off);
+                P.zeros = (const uint32_t *)(base + Lk.zeros_off);
+                P.x = d.x;
+                P.y = d.y;
+                P.N = (int)Lk.N;
+                P.steps = (int)Lk.steps;
+                P.wsteps = (int)Lk.wsteps;
+                P.zwords = (int)Lk.zwords;
+                P.spw = (int)((Lk.wsteps + NW_MAX_TEAM - 1) / NW_MAX_TEAM);
+                P.team = (int)((Lk.wsteps + P.spw - 1) / P.spw);
+                P.pad = 0;
+                A.block_begin[k] = (int)blocks;
+                blocks += (long)Lk.tiles16;
+                if (P.team > team_max) team_max = P.team;
+            }
+            for (int k = n; k < QG_MAX_GROUPED; ++k) A.p[k] = A.p[0];
+            if (blocks > 0x7fffffffL) return QG_ERR_SHAPE;
+            if (pass == 0) continue;
+            hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)team_max * QG_WAVE), 0, (hipStream_t)stream, A);
+            if (qg_launch_status() != QG_OK) return QG_ERR_DEVICE;
+            snprintf(g_narrow_kernel, sizeof g_narrow_kernel, "gemv_narrow<%d, %d>", L[i].bits, L[i].gps);
+        }
+    }
+    return QG_OK;
+}
+
+extern "C" int qg_gemv_narrow(const void *narrow, int64_t N, int64_t K, int bits, int group,
+                              const float *x, float *y, void *stream)
+{
+    qg_gemv_desc d;
+    d.packed = narrow;
+    d.N = N;
+    d.K = K;
+    d.bits = bits;
+    d.group = group;
+    d.x = x;
+    d.y = y;
+    return qg_gemv_grouped_narrow(&d, 1, stream);
+}

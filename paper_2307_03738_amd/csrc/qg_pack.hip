@@ -538,8 +538,11 @@ extern "C" const char *qg_status_string(int status)
     }
 }
 
+size_t qg_narrow_bytes(int64_t N, int64_t K, int bits, int group);   // qg_gemv_narrow.hip
+
 extern "C" size_t qg_packed_bytes(int64_t N, int64_t K, int bits, int group, int layout)
 {
+    if (layout == QG_LAYOUT_DEVICE_NARROW) return qg_narrow_bytes(N, K, bits, group);
     if (layout == QG_LAYOUT_CANONICAL) {
         QgCanonical C;
         if (qg_make_canonical(N, K, bits, group, &C) != QG_OK) return 0;

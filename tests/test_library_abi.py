@@ -30,7 +30,9 @@ def test_every_declared_symbol_is_exported(qg):
             "qg_packed_bytes", "qg_workspace_bytes", "qg_workspace_init", "qg_status_string",
             "qg_cell", "qg_set_gemv_tuning", "qg_set_gemm_tuning", "qg_gemv_autotune", "qg_gemv_swiglu",
             "qg_gemv_noalloc", "qg_last_gemv_kernel", "qg_gemv_record_tuning", "qg_clear_tuning",
-            "qg_gemm_autotune", "qg_gemm_autotune_report", "qg_gemv_autotune_report", "qg_build_id"} <= set(names)
+            "qg_gemm_autotune", "qg_gemm_autotune_report", "qg_gemv_autotune_report", "qg_build_id",
+            "qg_to_narrow", "qg_from_narrow", "qg_gemv_narrow", "qg_gemv_grouped_narrow",
+            "qg_last_narrow_kernel"} <= set(names)
     L = qg.lib()
     for n in names:
         assert hasattr(L, n), n
