@@ -145,23 +145,31 @@ struct NarrowProblem {
     int N, steps, wsteps, zwords;
     int spw;                // wave-steps per wavefront
     int team;               // wavefronts with work
-    int pad;
+    int block_begin;        // first workgroup of this problem
 };
 struct NarrowArgs {
-    int block_begin[QG_MAX_GROUPED];    // first workgroup of each problem; 0x7fffffff past the last
     NarrowProblem p[QG_MAX_GROUPED];
+    int more_first[4];      // first workgroups of problems 13, 14, 15 (0x7fffffff past the last)
 };
+// The first workgroups of problems 1 ... 12 (0x7fffffff past the last) travel as twelve leading
+// scalar kernel arguments: those reach a wavefront in registers when it starts (kernel-argument
+// preload), so the search for its problem begins without a load, and the load of the problem's
+// entry is the only one in front of the first loads of weights (launches of more than 13
+// problems read the rest of the table from the argument buffer first).
+typedef int nw_v4i __attribute__((ext_vector_type(4)));
+#define NW_FIRST_BLOCKS const nw_v4i fb_a, const nw_v4i fb_b, const nw_v4i fb_c
 
 typedef int nw_acc __attribute__((ext_vector_type(4)));
 typedef uint8_t __attribute__((may_alias)) nw_lds_u8;
 typedef uint32_t __attribute__((may_alias)) nw_lds_u32;
 
 // v op (v moved across lanes by the DPP control CTRL), inside rows of 16 lanes
+// (for bit patterns of non-negative floats: they order like unsigned integers, and a NaN is the largest)
 template <int CTRL>
-__device__ inline float nw_dpp_max(float v)
+__device__ inline uint32_t nw_dpp_max(uint32_t v)
 {
-    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
-    return fmaxf(v, __int_as_float(moved));
+    const uint32_t moved = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
+    return v > moved ? v : moved;
 }
 template <int CTRL>
 __device__ inline float nw_dpp_add(float v)
@@ -203,7 +211,7 @@ __device__ inline void nw_spread(float part, float *xhat)
 }
 
 template <int BITS, int GPS>
-__global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(const NarrowArgs A)
+__global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BLOCKS, const NarrowArgs A)
 {
     using F = Fmt<BITS>;
     constexpr int L = loads_per_step<BITS>();
@@ -219,14 +227,25 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(const Narro
     // per wavefront and slice: the four digit rows of the slice's x in operand order
     __shared__ __attribute__((aligned(16))) nw_lds_u8 xs[NW_MAX_TEAM][NW_SLICES][4][PITCH];
 
-    // which problem: the table of first workgroups comes in with one scalar load, the entry with another
+    // which problem: the last one whose first workgroup is <= this one
+    const int first[12] = {fb_a.x, fb_a.y, fb_a.z, fb_a.w, fb_b.x, fb_b.y, fb_b.z, fb_b.w, fb_c.x, fb_c.y, fb_c.z, fb_c.w};
+    const int bid = (int)blockIdx.x;
     int pi = 0;
 #pragma unroll
-    for (int i = 1; i < QG_MAX_GROUPED; ++i) pi += (int)blockIdx.x >= A.block_begin[i] ? 1 : 0;
+    for (int i = 0; i < 12; ++i)
+        if (bid >= first[i]) pi = i + 1;
+    if (first[11] != 0x7fffffff) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            if (bid >= A.more_first[i]) pi = 13 + i;
+    }
     const NarrowProblem P = A.p[pi];
+    // every field now, so that the loads of the entry are issued together
+    asm volatile("" ::"s"(P.codes), "s"(P.scales), "s"(P.zeros), "s"(P.x), "s"(P.y));
+    asm volatile("" ::"s"(P.N), "s"(P.steps), "s"(P.wsteps), "s"(P.zwords), "s"(P.spw), "s"(P.team), "s"(P.block_begin));
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int T = blockIdx.x - A.block_begin[pi];
+    const int T = bid - P.block_begin;
     const int j = lane >> 4, o = lane & 15;
     const int w0 = wave * P.spw;
     if (w0 >= P.wsteps) return;                     // no work: leave before the barrier
@@ -265,17 +284,20 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(const Narro
 #pragma unroll
         for (int g = 0; g < GPS; ++g) s[g] = scales[(uint32_t)(w * GPS + g) * QG_WAVE + lane];
         const uint32_t g0 = tc * GPS;                             // a step's groups share one zero word
-        const uint32_t zword = zeros[(g0 / ZPER) * NW_OUT + o] >> (F::ZBITS * (g0 % ZPER));
+        const uint32_t zraw = zeros[(g0 / ZPER) * NW_OUT + o];
+        __builtin_amdgcn_sched_barrier(0);                        // every load is requested before the arithmetic starts
+        const uint32_t zword = zraw >> (F::ZBITS * (g0 % ZPER));
 
         // fixed point of the slice: |x| scale < 2^30 for its largest |x|
-        float m = 0.0f;
+        float mf = 0.0f;
 #pragma unroll
-        for (int e = 0; e < XPL; ++e) m = fmaxf(m, fabsf(xv[e]));
+        for (int e = 0; e < XPL; ++e) mf = fmaxf(mf, fabsf(xv[e]));
+        uint32_t m = __float_as_uint(mf);
         m = nw_dpp_max<NW_QUAD_XOR1>(m);
         m = nw_dpp_max<NW_QUAD_XOR2>(m);
         m = nw_dpp_max<NW_HALF_MIRROR>(m);
         m = nw_dpp_max<NW_ROW_MIRROR>(m);                         // every lane of the row holds the row's maximum
-        uint32_t eb = __float_as_uint(m) >> 23;                   // biased exponent (m >= 0)
+        uint32_t eb = m >> 23;                                    // biased exponent (m >= 0)
         eb = eb < 30u ? 30u : eb > 254u ? 254u : eb;
         const float scale = __uint_as_float((283u - eb) << 23);   // 2^(156 - eb)
         const float inv = __uint_as_float((eb - 29u) << 23);      // 2^(eb - 156)
@@ -385,7 +407,7 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(const Narro
     if (n < P.N) P.y[n] = sum;
 }
 
-typedef void (*NarrowKernel)(const NarrowArgs);
+typedef void (*NarrowKernel)(nw_v4i, nw_v4i, nw_v4i, const NarrowArgs);
 
 template <int BITS>
 NarrowKernel pick_narrow(int gps)
@@ -484,7 +506,8 @@ extern "C" int qg_gemv_grouped_narrow(const qg_gemv_desc *descs, int count, void
             const NarrowKernel fn = L[i].bits == 4 ? pick_narrow<4>(L[i].gps) : L[i].bits == 2 ? pick_narrow<2>(L[i].gps) : pick_narrow<3>(L[i].gps);
             if (!fn) return QG_ERR_UNSUPPORTED;
             NarrowArgs A;
-            for (int k = 0; k < QG_MAX_GROUPED; ++k) A.block_begin[k] = 0x7fffffff;
+            int first[QG_MAX_GROUPED];
+            for (int k = 0; k < QG_MAX_GROUPED; ++k) first[k] = 0x7fffffff;
             long blocks = 0;
             int team_max = 1;
             for (int k = 0; k < n; ++k) {
@@ -503,15 +526,18 @@ extern "C" int qg_gemv_grouped_narrow(const qg_gemv_desc *descs, int count, void
                 P.zwords = (int)Lk.zwords;
                 P.spw = (int)((Lk.wsteps + NW_MAX_TEAM - 1) / NW_MAX_TEAM);
                 P.team = (int)((Lk.wsteps + P.spw - 1) / P.spw);
-                P.pad = 0;
-                A.block_begin[k] = (int)blocks;
+                P.block_begin = (int)blocks;
+                first[k] = (int)blocks;
                 blocks += (long)Lk.tiles16;
                 if (P.team > team_max) team_max = P.team;
             }
             for (int k = n; k < QG_MAX_GROUPED; ++k) A.p[k] = A.p[0];
             if (blocks > 0x7fffffffL) return QG_ERR_SHAPE;
             if (pass == 0) continue;
-            hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)team_max * QG_WAVE), 0, (hipStream_t)stream, A);
+            const nw_v4i fa = {first[1], first[2], first[3], first[4]}, fb = {first[5], first[6], first[7], first[8]};
+            const nw_v4i fc = {first[9], first[10], first[11], first[12]};
+            A.more_first[0] = first[13]; A.more_first[1] = first[14]; A.more_first[2] = first[15]; A.more_first[3] = 0x7fffffff;
+            hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)team_max * QG_WAVE), 0, (hipStream_t)stream, fa, fb, fc, A);
             if (qg_launch_status() != QG_OK) return QG_ERR_DEVICE;
             snprintf(g_narrow_kernel, sizeof g_narrow_kernel, "gemv_narrow<%d, %d>", L[i].bits, L[i].gps);
         }

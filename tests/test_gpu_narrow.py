@@ -133,6 +133,26 @@ def test_gemv_narrow_grouped_mixed_problems(qg, oracle):
         assert scaled_error(y1, y_ref, norms, x) <= TOL_FP32
 
 
+@pytest.mark.parametrize("count", [12, 13, 14, 16])
+def test_gemv_narrow_grouped_many_problems_of_one_format(qg, oracle, count):
+    # one kernel launch with up to the maximum number of problems: the table of first workgroups is
+    # searched in two parts, twelve entries in registers and the rest from the argument buffer
+    _announce("gemv narrow grouped, one format", count)
+    problems, refs = [], []
+    for i in range(count):
+        N, K, bits, group = 20 + 37 * i, 512 + 128 * (i % 5), 4, 128
+        W, x = synth.small_case(4100 + i, N, K, 0.02, False)
+        q0, s0, z0 = oracle.quantize(W, bits, group)
+        refs.append((oracle.matvec(q0, s0, z0, group, x), oracle.row_norms(q0, s0, z0, group), x))
+        q, s, z = qg.qg_quantize(dev(W), bits, group)
+        problems.append(dict(packed=qg.qg_to_narrow(qg.qg_pack(q, s, z, bits, group), N, K, bits, group), N=N, K=K,
+                             bits=bits, group=group, x=dev(x), y=torch.empty(N, dtype=torch.float32, device="cuda")))
+    qg.GroupedGemvNarrow(problems).launch()
+    torch.cuda.synchronize()
+    for p, (y_ref, norms, x) in zip(problems, refs):
+        assert scaled_error(host(p["y"]), y_ref, norms, x) <= TOL_FP32
+
+
 @pytest.mark.parametrize("name", ["C2", "C3", "C4"])
 def test_narrow_layer_set_full_size(qg, oracle, name):
     # the whole layer set in one grouped launch on the narrow layout, every output of every matrix
