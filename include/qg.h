@@ -210,6 +210,9 @@ int qg_gemv_narrow(const void *narrow, int64_t N, int64_t K, int bits, int group
                    const float *x, float *y, void *stream);
 int qg_gemv_grouped_narrow(const qg_gemv_desc *descs /* HOST */, int count, void *stream);
 const char *qg_last_narrow_kernel(void);
+/* Measurement knob of the narrow GEMV (process-wide): tiles of 16 outputs a wavefront takes against
+ * the same staged x, 1 or 2; 0 restores the built-in choice. */
+int qg_set_narrow_tuning(int tiles_per_wave);
 
 /* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe; while one of them
  * is non-zero they apply to every launch and the recorded tunings below are not consulted).  0

@@ -92,6 +92,8 @@ def lib():
         L.qg_gemv_narrow.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         L.qg_gemv_grouped_narrow.restype = i32
         L.qg_gemv_grouped_narrow.argtypes = [ctypes.POINTER(_Desc), i32, vp]
+        L.qg_set_narrow_tuning.restype = i32
+        L.qg_set_narrow_tuning.argtypes = [i32]
         L.qg_last_narrow_kernel.restype = ctypes.c_char_p
         L.qg_last_narrow_kernel.argtypes = []
         L.qg_gemv_record_tuning.restype = i32
@@ -274,6 +276,10 @@ class GroupedGemvNarrow:
         rc = self._fn(self.descs, self.count, _stream() if stream is None else stream)
         if rc != 0:
             _check(rc, "qg_gemv_grouped_narrow")
+
+
+def qg_set_narrow_tuning(tiles_per_wave: int = 0):
+    _check(lib().qg_set_narrow_tuning(tiles_per_wave), "qg_set_narrow_tuning")
 
 
 def qg_last_narrow_kernel() -> str:

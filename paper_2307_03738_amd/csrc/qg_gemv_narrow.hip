@@ -143,6 +143,7 @@ struct NarrowProblem {
     const float *x;
     float *y;
     int N, steps, wsteps, zwords;
+    int tiles16;
     int spw;                // wave-steps per wavefront
     int team;               // wavefronts with work
     int block_begin;        // first workgroup of this problem
@@ -210,7 +211,9 @@ __device__ inline void nw_spread(float part, float *xhat)
     }
 }
 
-template <int BITS, int GPS>
+// TPW: tiles of 16 outputs a wavefront takes through its wave-steps, one after the other against
+// the same digits of x (the staging of x is the larger part of a wave-step's vector work).
+template <int BITS, int GPS, int TPW>
 __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BLOCKS, const NarrowArgs A)
 {
     using F = Fmt<BITS>;
@@ -223,7 +226,7 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BL
     constexpr int ZPER = 32 / F::ZBITS;
     constexpr int PITCH = S + 16;                   // bytes per digit row: the four rows on different banks
     static_assert(GPS >= 1 && GPS <= NW_OUT && READS % GPS == 0 && ZPER % GPS == 0, "groups of a step");
-    __shared__ float red[NW_MAX_TEAM][NW_OUT];
+    __shared__ float red[NW_MAX_TEAM][TPW * NW_OUT];
     // per wavefront and slice: the four digit rows of the slice's x in operand order
     __shared__ __attribute__((aligned(16))) nw_lds_u8 xs[NW_MAX_TEAM][NW_SLICES][4][PITCH];
 
@@ -242,23 +245,34 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BL
     const NarrowProblem P = A.p[pi];
     // every field now, so that the loads of the entry are issued together
     asm volatile("" ::"s"(P.codes), "s"(P.scales), "s"(P.zeros), "s"(P.x), "s"(P.y));
-    asm volatile("" ::"s"(P.N), "s"(P.steps), "s"(P.wsteps), "s"(P.zwords), "s"(P.spw), "s"(P.team), "s"(P.block_begin));
+    asm volatile("" ::"s"(P.N), "s"(P.steps), "s"(P.wsteps), "s"(P.zwords), "s"(P.tiles16), "s"(P.spw), "s"(P.team),
+                 "s"(P.block_begin));
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int T = bid - P.block_begin;
+    const int T0 = (bid - P.block_begin) * TPW;
     const int j = lane >> 4, o = lane & 15;
     const int w0 = wave * P.spw;
     if (w0 >= P.wsteps) return;                     // no work: leave before the barrier
     const int w1 = w0 + P.spw < P.wsteps ? w0 + P.spw : P.wsteps;
 
-    // uniform bases; what a lane adds to them fits 32 bits
-    const uint4 *codes = P.codes + (size_t)T * P.wsteps * L * QG_WAVE;
-    const float *scales = P.scales + (size_t)T * P.wsteps * GPS * QG_WAVE;
-    const uint32_t *zeros = P.zeros + (size_t)T * P.zwords * NW_OUT;
+    // uniform bases; what a lane adds to them fits 32 bits.  A tile past the last one reads the
+    // last one again and stores nothing.
+    const uint4 *codes[TPW];
+    const float *scales[TPW];
+    const uint32_t *zeros[TPW];
+#pragma unroll
+    for (int u = 0; u < TPW; ++u) {
+        const int T = T0 + u < P.tiles16 ? T0 + u : P.tiles16 - 1;
+        codes[u] = P.codes + (size_t)T * P.wsteps * L * QG_WAVE;
+        scales[u] = P.scales + (size_t)T * P.wsteps * GPS * QG_WAVE;
+        zeros[u] = P.zeros + (size_t)T * P.zwords * NW_OUT;
+    }
     nw_lds_u8 *mine = &xs[wave][j][0][0] + o * XPL;              // this lane's bytes of digit row 0
     const nw_lds_u8 *abase = &xs[wave][j][lane & 3][0];         // the digit row this lane supplies to its block
 
-    float yacc = 0.0f;
+    float yacc[TPW];
+#pragma unroll
+    for (int u = 0; u < TPW; ++u) yacc[u] = 0.0f;
     for (int w = w0; w < w1; ++w) {
         // A slice past the end of K has zero codes and zero scales and adds nothing whatever x it
         // meets; it takes the last step's x (its output meets that x in a real slice as well).
@@ -277,16 +291,21 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BL
                 xv[4 * q + 3] = f.w;
             }
         }
-        uint4 v[L];
-#pragma unroll
-        for (int i = 0; i < L; ++i) v[i] = codes[(uint32_t)(w * L + i) * QG_WAVE + lane];
-        float s[GPS];
-#pragma unroll
-        for (int g = 0; g < GPS; ++g) s[g] = scales[(uint32_t)(w * GPS + g) * QG_WAVE + lane];
+        uint4 v[TPW][L];
+        float s[TPW][GPS];
+        uint32_t zword[TPW];
         const uint32_t g0 = tc * GPS;                             // a step's groups share one zero word
-        const uint32_t zraw = zeros[(g0 / ZPER) * NW_OUT + o];
+#pragma unroll
+        for (int u = 0; u < TPW; ++u) {
+#pragma unroll
+            for (int i = 0; i < L; ++i) v[u][i] = codes[u][(uint32_t)(w * L + i) * QG_WAVE + lane];
+#pragma unroll
+            for (int g = 0; g < GPS; ++g) s[u][g] = scales[u][(uint32_t)(w * GPS + g) * QG_WAVE + lane];
+            zword[u] = zeros[u][(g0 / ZPER) * NW_OUT + o];
+        }
         __builtin_amdgcn_sched_barrier(0);                        // every load is requested before the arithmetic starts
-        const uint32_t zword = zraw >> (F::ZBITS * (g0 % ZPER));
+#pragma unroll
+        for (int u = 0; u < TPW; ++u) zword[u] >>= F::ZBITS * (g0 % ZPER);
 
         // fixed point of the slice: |x| scale < 2^30 for its largest |x|
         float mf = 0.0f;
@@ -339,90 +358,108 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BL
 
         // the matrix instructions: per 128-bit read of A (16 k) two 4-bit cells, one 2-bit cell or
         // half a 3-bit cell; lane l receives the sums of its own output
-        nw_acc acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
-        uint32_t spare = 0;
+        nw_acc acc0[TPW], acc1[TPW];
+        uint32_t spare[TPW];
+#pragma unroll
+        for (int u = 0; u < TPW; ++u) {
+            acc0[u] = nw_acc{0, 0, 0, 0};
+            acc1[u] = nw_acc{0, 0, 0, 0};
+            spare[u] = 0;
+        }
 #pragma unroll
         for (int rd = 0; rd < READS; ++rd) {
             MmaOperand a;
             a.q = *(const lds_u128 *)(abase + rd * 16);
-            uint32_t b[4];
-            if constexpr (BITS == 4) {
 #pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    const int cell = 2 * rd + c;
-                    const uint32_t wd = word_of(v[cell >> 2], cell & 3);
-                    b[2 * c] = wd & 0x0f0f0f0fu;
-                    b[2 * c + 1] = (wd >> 4) & 0x0f0f0f0fu;
-                }
-            } else if constexpr (BITS == 2) {
-                const uint32_t wd = word_of(v[rd >> 2], rd & 3);
-                b[0] = wd & 0x03030303u;
-                b[1] = wd & 0x0c0c0c0cu;
-                b[2] = wd & 0x30303030u;
-                b[3] = (wd >> 6) & 0x03030303u;
-            } else {
-                const int cell = rd >> 1, u = cell >> 2, c = cell & 3;
-                if ((rd & 1) == 0) {
-                    const uint32_t wa = word_of(v[u * 3], c), wb = word_of(v[u * 3 + 1], c), wc = word_of(v[u * 3 + 2], c);
-                    spare = ((wa >> 6) & 0x03030303u) | ((wb >> 4) & 0x0c0c0c0cu) | ((wc >> 2) & 0x30303030u);
-                    b[0] = wa & 0x07070707u;
-                    b[1] = wa & 0x38383838u;
-                    b[2] = wb & 0x07070707u;
-                    b[3] = wb & 0x38383838u;
+            for (int u = 0; u < TPW; ++u) {
+                uint32_t b[4];
+                if constexpr (BITS == 4) {
+#pragma unroll
+                    for (int c = 0; c < 2; ++c) {
+                        const int cell = 2 * rd + c;
+                        const uint32_t wd = word_of(v[u][cell >> 2], cell & 3);
+                        b[2 * c] = wd & 0x0f0f0f0fu;
+                        b[2 * c + 1] = (wd >> 4) & 0x0f0f0f0fu;
+                    }
+                } else if constexpr (BITS == 2) {
+                    const uint32_t wd = word_of(v[u][rd >> 2], rd & 3);
+                    b[0] = wd & 0x03030303u;
+                    b[1] = wd & 0x0c0c0c0cu;
+                    b[2] = wd & 0x30303030u;
+                    b[3] = (wd >> 6) & 0x03030303u;
                 } else {
-                    const uint32_t wc = word_of(v[u * 3 + 2], c);
-                    b[0] = wc & 0x07070707u;
-                    b[1] = wc & 0x38383838u;
-                    b[2] = spare & 0x07070707u;
-                    b[3] = spare & 0x38383838u;
+                    const int cell = rd >> 1, un = cell >> 2, c = cell & 3;
+                    if ((rd & 1) == 0) {
+                        const uint32_t wa = word_of(v[u][un * 3], c), wb = word_of(v[u][un * 3 + 1], c),
+                                       wc = word_of(v[u][un * 3 + 2], c);
+                        spare[u] = ((wa >> 6) & 0x03030303u) | ((wb >> 4) & 0x0c0c0c0cu) | ((wc >> 2) & 0x30303030u);
+                        b[0] = wa & 0x07070707u;
+                        b[1] = wa & 0x38383838u;
+                        b[2] = wb & 0x07070707u;
+                        b[3] = wb & 0x38383838u;
+                    } else {
+                        const uint32_t wc = word_of(v[u][un * 3 + 2], c);
+                        b[0] = wc & 0x07070707u;
+                        b[1] = wc & 0x38383838u;
+                        b[2] = spare[u] & 0x07070707u;
+                        b[3] = spare[u] & 0x38383838u;
+                    }
                 }
-            }
-            acc0 = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[0], (int)b[0], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[1], (int)b[1], acc1, 0, 0, 0);
-            acc0 = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[2], (int)b[2], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[3], (int)b[3], acc1, 0, 0, 0);
-            if ((rd + 1) % RPG == 0) {
-                const int gs = (rd + 1) / RPG - 1;
-                // sum_i 256^i D_i of the group, in units of 1 / scale (|D_i| stays below 2^21)
-                const int lo = (acc0[1] + acc1[1]) * 256 + (acc0[0] + acc1[0]);
-                const int hi = (acc0[3] + acc1[3]) * 256 + (acc0[2] + acc1[2]);
-                acc0 = nw_acc{0, 0, 0, 0};
-                acc1 = nw_acc{0, 0, 0, 0};
-                const float tsum = fmaf((float)hi, 65536.0f, (float)lo) * inv;
-                const uint32_t zq = (zword >> (F::ZBITS * gs)) & ((1u << F::ZBITS) - 1u);
-                yacc = fmaf(s[gs], fmaf(-(float)zq, xhat[gs], tsum), yacc);
+                acc0[u] = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[0], (int)b[0], acc0[u], 0, 0, 0);
+                acc1[u] = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[1], (int)b[1], acc1[u], 0, 0, 0);
+                acc0[u] = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[2], (int)b[2], acc0[u], 0, 0, 0);
+                acc1[u] = __builtin_amdgcn_mfma_i32_4x4x4i8((int)a.r[3], (int)b[3], acc1[u], 0, 0, 0);
+                if ((rd + 1) % RPG == 0) {
+                    const int gs = (rd + 1) / RPG - 1;
+                    // sum_i 256^i D_i of the group, in units of 1 / scale (|D_i| stays below 2^21)
+                    const int lo = (acc0[u][1] + acc1[u][1]) * 256 + (acc0[u][0] + acc1[u][0]);
+                    const int hi = (acc0[u][3] + acc1[u][3]) * 256 + (acc0[u][2] + acc1[u][2]);
+                    acc0[u] = nw_acc{0, 0, 0, 0};
+                    acc1[u] = nw_acc{0, 0, 0, 0};
+                    const float tsum = fmaf((float)hi, 65536.0f, (float)lo) * inv;
+                    const uint32_t zq = (zword[u] >> (F::ZBITS * gs)) & ((1u << F::ZBITS) - 1u);
+                    yacc[u] = fmaf(s[u][gs], fmaf(-(float)zq, xhat[gs], tsum), yacc[u]);
+                }
             }
         }
     }
 
     // the four slices of an output, then the wavefronts of the workgroup in order
-    yacc += __shfl_xor(yacc, 16, QG_WAVE);
-    yacc += __shfl_xor(yacc, 32, QG_WAVE);
-    if (lane < NW_OUT) red[wave][lane] = yacc;
+    // (lanes 16 u + o of wavefront 0 finish tile u)
+    float mine_y = 0.0f;
+#pragma unroll
+    for (int u = 0; u < TPW; ++u) {
+        yacc[u] += __shfl_xor(yacc[u], 16, QG_WAVE);
+        yacc[u] += __shfl_xor(yacc[u], 32, QG_WAVE);
+        if (j == u) mine_y = yacc[u];
+    }
+    if (lane < TPW * NW_OUT) red[wave][lane] = mine_y;
     __syncthreads();
-    if (wave != 0 || lane >= NW_OUT) return;
+    if (wave != 0 || lane >= TPW * NW_OUT) return;
     float sum = red[0][lane];
     for (int k = 1; k < P.team; ++k) sum += red[k][lane];
-    const int n = T * NW_OUT + lane;
-    if (n < P.N) P.y[n] = sum;
+    const int n = (T0 + j) * NW_OUT + o;
+    if (T0 + j < P.tiles16 && n < P.N) P.y[n] = sum;
 }
 
 typedef void (*NarrowKernel)(nw_v4i, nw_v4i, nw_v4i, const NarrowArgs);
 
-template <int BITS>
+template <int BITS, int TPW>
 NarrowKernel pick_narrow(int gps)
 {
     switch (gps) {
-    case 1: return gemv_narrow<BITS, 1>;
-    case 2: return gemv_narrow<BITS, 2>;
-    case 4: return gemv_narrow<BITS, 4>;
-    case 8: return gemv_narrow<BITS, 8>;
+    case 1: return gemv_narrow<BITS, 1, TPW>;
+    case 2: return gemv_narrow<BITS, 2, TPW>;
+    case 4: return gemv_narrow<BITS, 4, TPW>;
+    case 8: return gemv_narrow<BITS, 8, TPW>;
     case 16:
-        if constexpr (BITS == 2) return gemv_narrow<2, 16>;
+        if constexpr (BITS == 2) return gemv_narrow<2, 16, TPW>;
         return nullptr;
     default: return nullptr;
     }
 }
+
+int g_narrow_tpw = 0;       // measurement knob: tiles per wavefront, 0 = built-in choice
 
 char g_narrow_kernel[48] = "";
 
@@ -473,6 +510,13 @@ extern "C" int qg_from_narrow(const void *narrow, int64_t N, int64_t K, int bits
 
 extern "C" const char *qg_last_narrow_kernel(void) { return g_narrow_kernel; }
 
+extern "C" int qg_set_narrow_tuning(int tiles_per_wave)
+{
+    if (tiles_per_wave < 0 || tiles_per_wave > 2) return QG_ERR_SHAPE;
+    g_narrow_tpw = tiles_per_wave;
+    return QG_OK;
+}
+
 extern "C" int qg_gemv_grouped_narrow(const qg_gemv_desc *descs, int count, void *stream)
 {
     if (!descs) return QG_ERR_NULL;
@@ -503,7 +547,11 @@ extern "C" int qg_gemv_grouped_narrow(const qg_gemv_desc *descs, int count, void
                 for (int b = a; b > 0 && L[idx[b]].K > L[idx[b - 1]].K; --b) {
                     const int t = idx[b]; idx[b] = idx[b - 1]; idx[b - 1] = t;
                 }
-            const NarrowKernel fn = L[i].bits == 4 ? pick_narrow<4>(L[i].gps) : L[i].bits == 2 ? pick_narrow<2>(L[i].gps) : pick_narrow<3>(L[i].gps);
+            // (measured on the three layer sets: two tiles per wavefront pay at 2 bits, where a wave-step's
+            // codes are half as many bytes per x value staged; one tile is ahead at 3 and 4 bits)
+            const int tpw = g_narrow_tpw ? g_narrow_tpw : L[i].bits == 2 ? 2 : 1;
+            const NarrowKernel fn = tpw == 2 ? (L[i].bits == 4 ? pick_narrow<4, 2>(L[i].gps) : L[i].bits == 2 ? pick_narrow<2, 2>(L[i].gps) : pick_narrow<3, 2>(L[i].gps))
+                                             : (L[i].bits == 4 ? pick_narrow<4, 1>(L[i].gps) : L[i].bits == 2 ? pick_narrow<2, 1>(L[i].gps) : pick_narrow<3, 1>(L[i].gps));
             if (!fn) return QG_ERR_UNSUPPORTED;
             NarrowArgs A;
             int first[QG_MAX_GROUPED];
@@ -524,11 +572,12 @@ extern "C" int qg_gemv_grouped_narrow(const qg_gemv_desc *descs, int count, void
                 P.steps = (int)Lk.steps;
                 P.wsteps = (int)Lk.wsteps;
                 P.zwords = (int)Lk.zwords;
+                P.tiles16 = (int)Lk.tiles16;
                 P.spw = (int)((Lk.wsteps + NW_MAX_TEAM - 1) / NW_MAX_TEAM);
                 P.team = (int)((Lk.wsteps + P.spw - 1) / P.spw);
                 P.block_begin = (int)blocks;
                 first[k] = (int)blocks;
-                blocks += (long)Lk.tiles16;
+                blocks += (long)((Lk.tiles16 + tpw - 1) / tpw);
                 if (P.team > team_max) team_max = P.team;
             }
             for (int k = n; k < QG_MAX_GROUPED; ++k) A.p[k] = A.p[0];
@@ -539,7 +588,7 @@ extern "C" int qg_gemv_grouped_narrow(const qg_gemv_desc *descs, int count, void
             A.more_first[0] = first[13]; A.more_first[1] = first[14]; A.more_first[2] = first[15]; A.more_first[3] = 0x7fffffff;
             hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)team_max * QG_WAVE), 0, (hipStream_t)stream, fa, fb, fc, A);
             if (qg_launch_status() != QG_OK) return QG_ERR_DEVICE;
-            snprintf(g_narrow_kernel, sizeof g_narrow_kernel, "gemv_narrow<%d, %d>", L[i].bits, L[i].gps);
+            snprintf(g_narrow_kernel, sizeof g_narrow_kernel, "gemv_narrow<%d, %d, %d>", L[i].bits, L[i].gps, tpw);
         }
     }
     return QG_OK;

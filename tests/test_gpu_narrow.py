@@ -64,9 +64,10 @@ def test_narrow_repack_comes_back_byte_for_byte(qg, N, K, bits, group):
     assert np.array_equal(np.bincount(a, minlength=256)[1:], np.bincount(b, minlength=256)[1:])
 
 
+@pytest.mark.parametrize("tpw", [0, 1, 2])        # the built-in choice; one and two tiles per wavefront
 @pytest.mark.parametrize("N,K,bits,group", NARROW_CASES)
-def test_gemv_narrow_matches_oracle(qg, oracle, N, K, bits, group):
-    _announce("gemv narrow", N, K, bits, group)
+def test_gemv_narrow_matches_oracle(qg, oracle, N, K, bits, group, tpw):
+    _announce("gemv narrow", N, K, bits, group, tpw)
     W, x = synth.small_case(N * 3 + K + group, N, K, 0.02, True)
     q0, s0, z0 = oracle.quantize(W, bits, group)
     y_ref, norms = oracle.matvec(q0, s0, z0, group, x), oracle.row_norms(q0, s0, z0, group)
@@ -74,9 +75,13 @@ def test_gemv_narrow_matches_oracle(qg, oracle, N, K, bits, group):
     blob = qg.qg_pack(q, s, z, bits, group)
     narrow = qg.qg_to_narrow(blob, N, K, bits, group)
     y = torch.full((N + 64,), 7.0, dtype=torch.float32, device="cuda")          # canary behind y
-    qg.qg_gemv_narrow(narrow, N, K, bits, group, dev(x), y[:N])
-    y2 = qg.qg_gemv_narrow(narrow, N, K, bits, group, dev(x))
-    torch.cuda.synchronize()
+    qg.qg_set_narrow_tuning(tpw)
+    try:
+        qg.qg_gemv_narrow(narrow, N, K, bits, group, dev(x), y[:N])
+        y2 = qg.qg_gemv_narrow(narrow, N, K, bits, group, dev(x))
+        torch.cuda.synchronize()
+    finally:
+        qg.qg_set_narrow_tuning(0)
     yh = host(y)
     assert np.all(yh[N:] == 7.0), "write past the end of y"
     assert np.array_equal(yh[:N], host(y2)), "not deterministic"
@@ -124,13 +129,19 @@ def test_gemv_narrow_grouped_mixed_problems(qg, oracle):
         problems.append(dict(packed=narrow, N=N, K=K, bits=bits, group=group, x=dev(x),
                              y=torch.full((N,), 7.0, dtype=torch.float32, device="cuda")))
     launch = qg.GroupedGemvNarrow(problems)
-    launch.launch()
-    first = [host(p["y"]).copy() for p in problems]
-    launch.launch()
-    torch.cuda.synchronize()
-    for p, y1, (y_ref, norms, x) in zip(problems, first, refs):
-        assert np.array_equal(host(p["y"]), y1), "not deterministic"
-        assert scaled_error(y1, y_ref, norms, x) <= TOL_FP32
+    for tpw in (1, 2):
+        qg.qg_set_narrow_tuning(tpw)
+        try:
+            launch.launch()
+            first = [host(p["y"]).copy() for p in problems]
+            launch.launch()
+            torch.cuda.synchronize()
+        finally:
+            qg.qg_set_narrow_tuning(0)
+        for p, y1, (y_ref, norms, x) in zip(problems, first, refs):
+            assert np.array_equal(host(p["y"]), y1), "not deterministic"
+            assert scaled_error(y1, y_ref, norms, x) <= TOL_FP32
+            p["y"].fill_(7.0)
 
 
 @pytest.mark.parametrize("count", [12, 13, 14, 16])
@@ -153,8 +164,9 @@ def test_gemv_narrow_grouped_many_problems_of_one_format(qg, oracle, count):
         assert scaled_error(host(p["y"]), y_ref, norms, x) <= TOL_FP32
 
 
+@pytest.mark.parametrize("tpw", [1, 2])
 @pytest.mark.parametrize("name", ["C2", "C3", "C4"])
-def test_narrow_layer_set_full_size(qg, oracle, name):
+def test_narrow_layer_set_full_size(qg, oracle, name, tpw):
     # the whole layer set in one grouped launch on the narrow layout, every output of every matrix
     # against the oracle; and against the wide layout's GEMV, which computes the same sums in another order
     cfg = synth.CONFIGS[name]
@@ -174,9 +186,13 @@ def test_narrow_layer_set_full_size(qg, oracle, name):
         wide.append(dict(packed=blob, N=N, K=K, bits=cfg.bits, group=cfg.group, x=xd,
                          y=torch.empty(N, dtype=torch.float32, device="cuda")))
     launch = qg.GroupedGemvNarrow(problems)
-    launch.launch()
-    first = [host(p["y"]).copy() for p in problems]
-    launch.launch()
+    qg.qg_set_narrow_tuning(tpw)
+    try:
+        launch.launch()
+        first = [host(p["y"]).copy() for p in problems]
+        launch.launch()
+    finally:
+        qg.qg_set_narrow_tuning(0)
     qg.qg_gemv_grouped(wide)
     torch.cuda.synchronize()
     worst = 0.0
