@@ -3,7 +3,9 @@
 A step is one pass of the whole path over the LLaMA-7B-shaped decoder layer set at batch 1,
 4-bit codes, group 128 (seven matrices: four 4096x4096, two 11008x4096, one 4096x11008, each
 with its own fp32 x): ONE grouped kernel launch reading the packed weights from HBM.
-Weights are quantized and packed by the library before the timed region and stay resident
+Weights are quantized and packed by the library before the timed region (by default into the
+narrow device layout, qg_pack + qg_to_narrow, read by qg_gemv_grouped_narrow; --layout wide
+times qg_gemv_grouped on the wide layout, and the default run reports it beside) and stay resident
 in HBM; to keep the 256 MB last-level cache from serving them, the timed loop rotates over
 enough distinct packed copies of the set that consecutive uses of a copy are more than 1.2 GB
 of traffic apart.
@@ -47,8 +49,11 @@ def measured_traffic(name, kernel):
         return None, "no profiles/hbm_traffic.json"
     if not rec:
         return None, f"no counter run recorded for {name}"
-    if rec["kernel"] != kernel:
-        return None, f"counters were taken on {rec['kernel']}, this run used {kernel}"
+    recs = rec if isinstance(rec, list) else [rec]
+    match = [r for r in recs if r["kernel"] == kernel]
+    if not match:
+        return None, f"counters were taken on {', '.join(r['kernel'] for r in recs)}, this run used {kernel}"
+    rec = match[0]
     return rec["bytes"], f"{rec['source']} ({rec['date']}; rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, carried over)"
 
 
@@ -285,7 +290,13 @@ def bench_offline(qg, args):
             "rows": rows}
 
 
-def gpu_drawn_launches(qg, name):
+def narrow_launch(qg, problems):
+    """The same grouped launch on the narrow layout (same x and y tensors, repacked weights)."""
+    return qg.GroupedGemvNarrow([dict(p, packed=qg.qg_to_narrow(p["packed"], p["N"], p["K"], p["bits"], p["group"]))
+                                 for p in problems])
+
+
+def gpu_drawn_launches(qg, name, layout="wide"):
     """Rotated grouped launches of configuration `name` with Gaussian weights drawn on the GPU
     (timing only: the kernels have no data-dependent control flow)."""
     from paper_2307_03738_amd import synth
@@ -305,7 +316,7 @@ def gpu_drawn_launches(qg, name):
         probs = [dict(packed=(packed[(n, k)] if c == 0 else packed[(n, k)].clone()), N=n, K=k, bits=cfg.bits,
                       group=cfg.group, x=xs[k], y=torch.empty(n, dtype=torch.float32, device="cuda"))
                  for n, k in cfg.shapes]
-        launches.append(qg.GroupedGemv(probs))
+        launches.append(narrow_launch(qg, probs) if layout == "narrow" else qg.GroupedGemv(probs))
     torch.cuda.synchronize()
     return cfg, launches
 
@@ -331,15 +342,21 @@ def other_workloads(qg, args):
     from paper_2307_03738_amd import synth
     out = {}
     for name in ("C3", "C4"):
-        cfg, launches = gpu_drawn_launches(qg, name)
-        us = time_launches(launches, max(20, args.steps // 4), max(5, args.warmup // 4))
-        alg = algorithmic_bytes(cfg)
+        row = {}
+        for layout in ("narrow", "wide"):
+            cfg, launches = gpu_drawn_launches(qg, name, layout)
+            us = time_launches(launches, max(20, args.steps // 4), max(5, args.warmup // 4))
+            alg = algorithmic_bytes(cfg)
+            row[layout] = {"kernel": qg.qg_last_narrow_kernel() if layout == "narrow" else qg.qg_last_gemv_kernel(),
+                           "us": round(us, 3), "GBps": round(alg / us / 1e3, 1),
+                           "frac_of_hbm_peak": round(alg / us / 1e3 / HBM_PEAK_GBS, 4),
+                           "packed_copies_rotated": len(launches)}
+            del launches
+        best = min(row, key=lambda k: row[k]["us"])
         out[name] = {"workload": f"{name}: decoder layer set {list(cfg.shapes)}, {cfg.bits}-bit, group {cfg.group}, "
                                  "batch 1, one grouped launch per set (timing only, weights drawn on the GPU)",
-                     "kernel": qg.qg_last_gemv_kernel(), "us": round(us, 3), "algorithmic_bytes_per_set": alg,
-                     "GBps": round(alg / us / 1e3, 1), "frac_of_hbm_peak": round(alg / us / 1e3 / HBM_PEAK_GBS, 4),
-                     "packed_copies_rotated": len(launches)}
-        del launches
+                     "algorithmic_bytes_per_set": alg, "layout": best, **row[best],
+                     "other_layout": {"layout": [k for k in row if k != best][0], **row[[k for k in row if k != best][0]]}}
     gemm = bench_gemm(synth.CONFIGS["C5"], qg, args)
     out["C5"] = {"workload": gemm["config"]["workload"], "us_all_problems": gemm["value"],
                  "problems": gemm["problems"]}
@@ -438,6 +455,10 @@ def main():
     ap.add_argument("--gemm-shape", type=int, default=0,
                     help="--config C5: workgroup shape / kernel of qg_gemm_small (qg_set_gemm_tuning); 13 = raw-code kernel")
     ap.add_argument("--gemm-splits", type=int, default=0, help="--config C5: K ranges over workgroups (0 = built-in choice)")
+    ap.add_argument("--layout", default="narrow", choices=["narrow", "wide"],
+                    help="device layout of the packed weights for the GEMV: narrow (rows of 16 outputs x 4 steps of K, "
+                         "qg_to_narrow + qg_gemv_grouped_narrow) or wide (rows of 64 outputs, qg_gemv_grouped)")
+    ap.add_argument("--narrow-tiles-per-wave", type=int, default=0, help="qg_set_narrow_tuning (0 = built-in choice)")
     ap.add_argument("--wpb", type=int, default=0)
     ap.add_argument("--bytes-per-wave", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0, help="0 built-in choice, 1 vector-ALU GEMV, 2 matrix-core GEMV (32x32x16), 3 matrix-core GEMV (4x4x4, bf16), 4 matrix-core GEMV (4x4x4, int8)")
@@ -471,10 +492,16 @@ def main():
     base = prepare_set(cfg, qg)
     set_bytes = sum(p["packed"].numel() for p in base)
     copies = max(2, int(np.ceil(ROTATE_BYTES / set_bytes)))
-    launches = []
+    narrow = args.layout == "narrow"
+    if narrow and (args.autotune or args.wpb or args.bytes_per_wave or args.kernel):
+        print("--autotune, --wpb, --bytes-per-wave and --kernel belong to the wide layout (--layout wide)", file=sys.stderr)
+        sys.exit(2)
+    qg.qg_set_narrow_tuning(args.narrow_tiles_per_wave)
+    launches, wide_launches = [], []
     for c in range(copies):
         probs = [dict(p, packed=(p["packed"] if c == 0 else p["packed"].clone())) for p in base]
-        launches.append(qg.GroupedGemv(probs))
+        wide_launches.append(qg.GroupedGemv(probs))
+        launches.append(narrow_launch(qg, probs) if narrow else wide_launches[-1])
     torch.cuda.synchronize()
 
     if args.copy_calibration:
@@ -493,7 +520,7 @@ def main():
     for i in range(args.warmup):
         launches[i % copies].launch(stream)
     torch.cuda.synchronize()
-    kernel_name = qg.qg_last_gemv_kernel()
+    kernel_name = qg.qg_last_narrow_kernel() if narrow else qg.qg_last_gemv_kernel()
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     start.record()
@@ -512,6 +539,9 @@ def main():
 
     # the same launches on a single copy: weights served largely by the last-level cache
     warm_ms = time_launches(launches[:1], args.steps, 20) / 1e3
+    # the other layout, for comparison
+    wide_us = time_launches(wide_launches, args.steps, max(20, args.warmup // 10)) if narrow else None
+    wide_kernel = qg.qg_last_gemv_kernel() if narrow else None
 
     alg = algorithmic_bytes(cfg)
     achieved = alg / (ms_per_step * 1e-3) / 1e9
@@ -525,11 +555,14 @@ def main():
         "vs_baseline": None,
         # what the multiply-adds run in: 4-bit codes as int8 against the int8 digits of x in 32-bit
         # fixed point (per step) on the 4x4x4 matrix instruction, int32 sums, fp32 per group and beyond
-        "dtype": "i8 mfma (x as 32-bit fixed point), f32 accumulate" if "mma4i" in kernel_name else "f32",
+        "dtype": "i8 mfma (x as 32-bit fixed point), f32 accumulate"
+                 if ("mma4i" in kernel_name or "narrow" in kernel_name) else "f32",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: decoder layer set {list(cfg.shapes)}, {cfg.bits}-bit, "
                                f"group {cfg.group}, batch 1, one grouped launch per set",
                    "kernel": kernel_name,
+                   "layout": "narrow: rows of 16 outputs x 4 steps of K (qg_pack, qg_to_narrow, qg_gemv_grouped_narrow)"
+                             if narrow else "wide: rows of 64 outputs (qg_pack, qg_gemv_grouped)",
                    "packed_copies_rotated": copies, "packed_bytes_per_set": set_bytes,
                    "algorithmic_bytes_per_set": alg},
         "effective_weight_GBps": round(achieved, 1),
@@ -542,6 +575,9 @@ def main():
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "traffic_source": traffic_source},
     }
+    if narrow:
+        out["wide_layout"] = {"kernel": wide_kernel, "us": round(wide_us, 3),
+                              "frac_of_hbm_peak": round(alg / wide_us / 1e3 / HBM_PEAK_GBS, 4)}
     if tuned is not None:
         _, timed, dropped = qg.qg_gemv_autotune_report()
         out["autotuned"] = {"waves_per_block": tuned[0], "bytes_per_wave": tuned[1], "kernel": tuned[2],
@@ -553,7 +589,7 @@ def main():
         out["parity_max_scaled_err"] = float(f"{err:.3e}")
         out["parity_bound"] = TOL_FP32
         failed = not (err <= TOL_FP32)
-    del launches, base
+    del launches, wide_launches, base
     if not args.no_other_workloads:
         qg.qg_set_gemv_tuning(0, 0, 0)
         out["other_workloads"] = other_workloads(qg, args)
