@@ -540,7 +540,7 @@ def main():
     # the same launches on a single copy: weights served largely by the last-level cache
     warm_ms = time_launches(launches[:1], args.steps, 20) / 1e3
     # the other layout, for comparison
-    wide_us = time_launches(wide_launches, args.steps, max(20, args.warmup // 10)) if narrow else None
+    wide_us = time_launches(wide_launches, max(args.steps, 400), max(50, args.warmup // 10)) if narrow else None
     wide_kernel = qg.qg_last_gemv_kernel() if narrow else None
 
     alg = algorithmic_bytes(cfg)
