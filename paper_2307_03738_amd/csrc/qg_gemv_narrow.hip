@@ -19,6 +19,13 @@
 //   zeros : uint32 [tile16][zword][output]             the wide layout's zero words
 //
 // Steps past the end of K and outputs past N hold zero codes and zero scales.
+//
+// 4 bits: bit 7 of every code byte is stored inverted, which makes the byte's high code q read
+// h = q - 8 as a two's-complement nibble, and the whole byte, read as int8, lo + 16 h.  The
+// kernel multiplies x_lo with the whole byte and (x_hi / 16 - x_lo) with the byte under the mask
+// 0xf0 (16 h):  x_lo (lo + 16 h) + (x_hi / 16 - x_lo) 16 h = x_lo lo + x_hi h, exactly, the
+// subtraction being made on the fixed-point integers.  That is one mask per eight codes instead
+// of two masks and a shift; 8 times the sum of the x that meet high codes puts the 8 back.
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <stdint.h>
@@ -77,6 +84,7 @@ struct RepackArgs {
     size_t n_codes, n_scales, n_zeros;      // ... of the narrow blob
     long tiles64, tiles16, steps, wsteps, ngroups, zwords;
     int loads, gps;
+    uint32_t flip;                          // what every code word is XORed with on its way (either way)
 };
 
 // One thread per element of the narrow blob's three sections (codes, then scales, then zeros).
@@ -99,8 +107,18 @@ __global__ void repack_narrow(const RepackArgs A)
         const bool real = t < A.steps;
         const size_t wide = ((size_t)(tile * A.steps + (real ? t : 0)) * A.loads + i) * QG_WAVE + lane64;
         uint4 *n = (uint4 *)(A.dst + A.n_codes) + e;
-        if (TO_NARROW) *n = real ? ((const uint4 *)(A.src + A.w_codes))[wide] : make_uint4(0u, 0u, 0u, 0u);
-        else if (real) ((uint4 *)(A.dst + A.w_codes))[wide] = ((const uint4 *)(A.src + A.n_codes))[e];
+        if (TO_NARROW) {
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);       // (a padded step meets zero scales: what its codes read as is immaterial)
+            if (real) {
+                v = ((const uint4 *)(A.src + A.w_codes))[wide];
+                v.x ^= A.flip; v.y ^= A.flip; v.z ^= A.flip; v.w ^= A.flip;
+            }
+            *n = v;
+        } else if (real) {
+            uint4 v = ((const uint4 *)(A.src + A.n_codes))[e];
+            v.x ^= A.flip; v.y ^= A.flip; v.z ^= A.flip; v.w ^= A.flip;
+            ((uint4 *)(A.dst + A.w_codes))[wide] = v;
+        }
         return;
     }
     e -= n_code;
@@ -198,7 +216,7 @@ __device__ constexpr float nw_xdiv(int e)           // 1 / (what the field of th
 {
     return BITS == 3 ? ((e & 7) >= 4 ? 0.125f : 1.0f)
          : BITS == 2 ? ((e & 3) == 1 ? 0.25f : (e & 3) == 2 ? 0.0625f : 1.0f)
-                     : 1.0f;
+                     : ((e & 1) ? 0.0625f : 1.0f);
 }
 
 // lane G * LPG of every row of 16 lanes to all lanes of the row, for G = 0 .. GPS - 1
@@ -323,9 +341,14 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BL
         uint32_t pat[XPL];
 #pragma unroll
         for (int e = 0; e < XPL; ++e) {
-            const int fixed = (int)(xv[e] * (scale * nw_xdiv<BITS>(e)));
-            // the four bytes of (fixed + 0x808080) ^ 0x808080, read as signed, are digits base 256 of `fixed`
-            pat[e] = ((uint32_t)fixed + 0x00808080u) ^ 0x00808080u;
+            // the four bytes of (fixed + 0x808080) ^ 0x808080, read as signed, are digits base 256 of
+            // `fixed`; the 0x808080 is added in fp32 (where that rounds, it rounds below the last bit of x)
+            int lifted = (int)fmaf(xv[e], scale * nw_xdiv<BITS>(e), (BITS == 4 && (e & 1)) ? 2.0f * 8421504.0f : 8421504.0f);
+            // 4 bits: the value that meets a byte's high code is x_hi / 16 - x_lo in fixed point (the
+            // low code's operand is the whole byte, lo + 16 hi': what x_lo gathers from hi' comes off here)
+            if constexpr (BITS == 4)
+                if (e & 1) lifted -= (int)(pat[e - 1] ^ 0x00808080u);
+            pat[e] = (uint32_t)lifted ^ 0x00808080u;
         }
         // digit row r of this lane: byte b holds digit r of the value that belongs at byte b
         // (a 4 x 4 byte transpose per four values)
@@ -342,22 +365,44 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BL
         }
 
         // x-hat of the slice's groups: the lanes of a group add up, every lane of the row gets every sum
-        float part = 0.0f;
+        // (4 bits: the high codes read 8 too low, which 8 times the sum of the x they meet makes up for)
+        float part = 0.0f, part_high = 0.0f;
 #pragma unroll
-        for (int e = 0; e < XPL; ++e) part += xv[e];
+        for (int e = 0; e < XPL; ++e) {
+            if (BITS == 4 && (e & 1)) part_high += xv[e];
+            else part += xv[e];
+        }
+        if constexpr (BITS == 4) part += part_high;
         if constexpr (LPG >= 2) part = nw_dpp_add<NW_QUAD_XOR1>(part);
         if constexpr (LPG >= 4) part = nw_dpp_add<NW_QUAD_XOR2>(part);
         if constexpr (LPG >= 8) part = nw_dpp_add<NW_HALF_MIRROR>(part);
         if constexpr (LPG >= 16) part = nw_dpp_add<NW_ROW_MIRROR>(part);
-        float xhat[GPS];
+        float xhat[GPS], lift[GPS];
         if constexpr (GPS == 1) {
             xhat[0] = part;
         } else {
             nw_spread<GPS, LPG>(part, xhat);
         }
+        if constexpr (BITS == 4) {
+            part_high *= 8.0f;
+            if constexpr (LPG >= 2) part_high = nw_dpp_add<NW_QUAD_XOR1>(part_high);
+            if constexpr (LPG >= 4) part_high = nw_dpp_add<NW_QUAD_XOR2>(part_high);
+            if constexpr (LPG >= 8) part_high = nw_dpp_add<NW_HALF_MIRROR>(part_high);
+            if constexpr (LPG >= 16) part_high = nw_dpp_add<NW_ROW_MIRROR>(part_high);
+            if constexpr (GPS == 1) {
+                lift[0] = part_high;
+            } else {
+                nw_spread<GPS, LPG>(part_high, lift);
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < GPS; ++g) lift[g] = 0.0f;
+        }
 
         // the matrix instructions: per 128-bit read of A (16 k) two 4-bit cells, one 2-bit cell or
-        // half a 3-bit cell; lane l receives the sums of its own output
+        // half a 3-bit cell; lane l receives the sums of its own output.  The B operands are the
+        // code fields where they sit in their bytes (the x that meets a field counts it by its
+        // place: nw_xdiv), 4 bits: the whole byte and its high nibble.
         nw_acc acc0[TPW], acc1[TPW];
         uint32_t spare[TPW];
 #pragma unroll
@@ -378,8 +423,8 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BL
                     for (int c = 0; c < 2; ++c) {
                         const int cell = 2 * rd + c;
                         const uint32_t wd = word_of(v[u][cell >> 2], cell & 3);
-                        b[2 * c] = wd & 0x0f0f0f0fu;
-                        b[2 * c + 1] = (wd >> 4) & 0x0f0f0f0fu;
+                        b[2 * c] = wd;                      // int8: lo + 16 (hi - 8)
+                        b[2 * c + 1] = wd & 0xf0f0f0f0u;    // int8: 16 (hi - 8), against x_hi / 16 - x_lo
                     }
                 } else if constexpr (BITS == 2) {
                     const uint32_t wd = word_of(v[u][rd >> 2], rd & 3);
@@ -418,7 +463,7 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BL
                     acc1[u] = nw_acc{0, 0, 0, 0};
                     const float tsum = fmaf((float)hi, 65536.0f, (float)lo) * inv;
                     const uint32_t zq = (zword[u] >> (F::ZBITS * gs)) & ((1u << F::ZBITS) - 1u);
-                    yacc[u] = fmaf(s[u][gs], fmaf(-(float)zq, xhat[gs], tsum), yacc[u]);
+                    yacc[u] = fmaf(s[u][gs], fmaf(-(float)zq, xhat[gs], BITS == 4 ? tsum + lift[gs] : tsum), yacc[u]);
                 }
             }
         }
@@ -478,6 +523,7 @@ int repack(const void *src, void *dst, int64_t N, int64_t K, int bits, int group
     A.tiles64 = (long)L.wide.tiles; A.tiles16 = (long)L.tiles16; A.steps = (long)L.steps; A.wsteps = (long)L.wsteps;
     A.ngroups = (long)L.wide.ngroups; A.zwords = (long)L.zwords;
     A.loads = L.loads; A.gps = L.gps;
+    A.flip = bits == 4 ? 0x80808080u : 0u;
     const size_t elements = (size_t)L.tiles16 * L.wsteps * L.loads * QG_WAVE + (size_t)L.tiles16 * L.wsteps * L.gps * QG_WAVE +
                             (size_t)L.tiles16 * L.zwords * NW_OUT;
     const unsigned blocks = (unsigned)((elements + 255) / 256);
