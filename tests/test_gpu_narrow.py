@@ -117,6 +117,56 @@ def test_gemv_narrow_non_finite_activations_reach_the_output(qg):
         assert not np.any(np.isfinite(host(y))), bad
 
 
+def _hard_activations(K, kind, rng):
+    """x vectors aimed at the fixed-point conversion of the kernel: values at the top of a step's
+    range with both signs next to each other, one outlier among small values, tiny and zero steps."""
+    top = np.float32(np.nextafter(np.float32(2.0), np.float32(0.0)))       # the largest mantissa
+    if kind == "alternating top":
+        x = np.where(np.arange(K) % 2 == 0, top, -top).astype(np.float32) * np.float32(1e4)
+    elif kind == "negative top":
+        x = np.full(K, -top, dtype=np.float32)
+    elif kind == "pairs of opposite sign":
+        x = (rng.standard_normal(K) * 3.0).astype(np.float32)
+        x[1::2] = -16.0 * x[0::2]                                           # x_hi / 16 - x_lo = -2 x_lo
+    elif kind == "outlier":
+        x = (rng.standard_normal(K) * 1e-3).astype(np.float32)
+        x[rng.integers(0, K, size=max(1, K // 512))] = np.float32(1e6)
+    elif kind == "tiny and zero":
+        x = (rng.standard_normal(K) * 1e-30).astype(np.float32)
+        x[: K // 2] = 0.0
+        x[K // 2 + 3] = np.float32(1e-42)                                   # a denormal
+    else:
+        raise ValueError(kind)
+    return x
+
+
+@pytest.mark.parametrize("kind", ["alternating top", "negative top", "pairs of opposite sign", "outlier", "tiny and zero"])
+@pytest.mark.parametrize("N,K,bits,group", [(70, 4096, 4, 128), (33, 1024, 4, 32), (20, 512, 4, 16), (40, 2304, 3, 64),
+                                            (50, 1536, 2, 32)])
+def test_gemv_narrow_hard_activations(qg, oracle, N, K, bits, group, kind):
+    _announce("gemv narrow hard x", N, K, bits, group, kind)
+    rng = np.random.default_rng(N + K + len(kind))
+    W, _ = synth.small_case(N + 5 * K + bits, N, K, 0.02, True)
+    x = _hard_activations(K, kind, rng)
+    q0, s0, z0 = oracle.quantize(W, bits, group)
+    y_ref, norms = oracle.matvec(q0, s0, z0, group, x), oracle.row_norms(q0, s0, z0, group)
+    q, s, z = qg.qg_quantize(dev(W), bits, group)
+    narrow = qg.qg_to_narrow(qg.qg_pack(q, s, z, bits, group), N, K, bits, group)
+    for tpw in (1, 2):
+        qg.qg_set_narrow_tuning(tpw)
+        try:
+            y = qg.qg_gemv_narrow(narrow, N, K, bits, group, dev(x))
+            torch.cuda.synchronize()
+        finally:
+            qg.qg_set_narrow_tuning(0)
+        assert np.all(np.isfinite(host(y)))
+        # the bound of the boundary, and the level the fixed point is built for (32-bit per step:
+        # an error of a few 2^-24 of the step's largest |x| per weight)
+        err = scaled_error(host(y), y_ref, norms, x)
+        assert err <= TOL_FP32
+        assert err <= 2e-6, (err, kind)
+
+
 def test_gemv_narrow_grouped_mixed_problems(qg, oracle):
     # one call, three kernel classes, K of different lengths inside a class, ragged N
     _announce("gemv narrow grouped")
