@@ -54,8 +54,9 @@ typedef enum {
      * codes, scales and zero-points (plus zero padding), fixed by (N, K, bits, group). */
     QG_LAYOUT_DEVICE = 1,
     /* The layout qg_gemv_narrow reads (made from a QG_LAYOUT_DEVICE blob by qg_to_narrow): the same
-     * bytes in rows of 16 outputs x 4 steps of K.  Only qg_packed_bytes, qg_to_narrow,
-     * qg_from_narrow and the qg_gemv*_narrow calls know it. */
+     * codes, scales and zero-points in records of 16 outputs x 4 steps of K (codes, then their
+     * scales, then their zero-points).  Only qg_packed_bytes, qg_to_narrow, qg_from_narrow and the
+     * qg_gemv*_narrow calls know it. */
     QG_LAYOUT_DEVICE_NARROW = 2
 } qg_layout;
 
@@ -198,8 +199,9 @@ int qg_gemm_small(const void *packed, int64_t N, int64_t K, int bits, int group,
  * up to one step and dividing a step, K <= 32768 at 4 bits and 65536 otherwise; anything else
  * returns QG_ERR_UNSUPPORTED (from qg_packed_bytes: 0).
  *   qg_to_narrow:   packed = QG_LAYOUT_DEVICE blob (DEVICE) -> narrow, qg_packed_bytes(...,
- *                   QG_LAYOUT_DEVICE_NARROW) bytes (DEVICE, 16-byte aligned, caller's); a permutation
- *                   of 16-byte pieces, scales and zero words plus zero padding; qg_from_narrow is its
+ *                   QG_LAYOUT_DEVICE_NARROW) bytes (DEVICE, 16-byte aligned, caller's); the 16-byte
+ *                   pieces of codes and the scales move as they are (4 bits: bit 7 of every code byte
+ *                   inverted), the zero-points are packed anew, padding is zero; qg_from_narrow is its
  *                   inverse and gives back the QG_LAYOUT_DEVICE blob byte for byte.
  *   qg_gemv_narrow / qg_gemv_grouped_narrow: as qg_gemv / qg_gemv_grouped with `packed` in the
  *                   narrow layout (descs HOST; x 64-byte aligned; y overwritten).

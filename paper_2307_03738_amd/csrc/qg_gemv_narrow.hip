@@ -14,11 +14,18 @@
 // Eight wavefronts with one wave-step each then cover K = 4096 (4 bits) of their 16 outputs, a
 // workgroup owns its outputs, and nothing is added across workgroups: no workspace, no atomics.
 //
-//   codes : uint4  [tile16][wave-step][load][lane]     lane = 16 * slice + output
-//   scales: float  [tile16][wave-step][group of the step][lane]
-//   zeros : uint32 [tile16][zword][output]             the wide layout's zero words
+// What a wavefront needs for one wave-step is one contiguous record (scales and zero-points in
+// sections of their own, 2 KB and 256 B per workgroup apart from its 32 KB of codes, cost C2 1.6 us:
+// measured with the loads of the two taken out):
 //
-// Steps past the end of K and outputs past N hold zero codes and zero scales.
+//   record [tile16][wave-step]:
+//     codes : uint4  [load][lane]                       lane = 16 * slice + output
+//     scales: float  [group of the step][lane]
+//     zeros : uint32 [64 * zb / 32]                     zb = groups of a step x bits of a zero-point: lane l's
+//                                                       zero-points are bits (l % (32 / zb)) * zb ... of word
+//                                                       l / (32 / zb), its first group lowest; padded to 16 bytes
+//
+// Steps past the end of K and outputs past N hold zero codes, zero scales and zero zero-points.
 //
 // 4 bits: bit 7 of every code byte is stored inverted, which makes the byte's high code q read
 // h = q - 8 as a two's-complement nibble, and the whole byte, read as int8, lo + 16 h.  The
@@ -42,9 +49,22 @@ constexpr int NW_MAX_SPW = 8;          // wave-steps one wavefront takes at most
 
 struct NarrowLayout {
     int bits, group, gps, loads;       // gps: groups per step; loads: 128-bit vectors per lane and step
-    int64_t N, K, tiles16, steps, wsteps, zwords;
-    size_t codes_off, scales_off, zeros_off, total;
+    int zb;                            // bits of zero-points per lane and wave-step
+    int code_bytes, meta_zeros, meta_bytes;    // a record: codes, then scales, then (at meta_zeros behind the codes) zero-points
+    int rec_bytes;
+    int64_t N, K, tiles16, steps, wsteps;
+    size_t total;
     QgLayout wide;
+};
+
+// (the same numbers at compile time, for the kernel)
+template <int BITS, int GPS>
+struct NarrowRecord {
+    static constexpr int ZB = GPS * Fmt<BITS>::ZBITS;
+    static constexpr int ZEROS = GPS * QG_WAVE * 4;
+    static constexpr int META = ZEROS + (QG_WAVE * ZB / 8 + 15) / 16 * 16;
+    static constexpr int CODES = loads_per_step<BITS>() * QG_WAVE * 16;
+    static constexpr int BYTES = CODES + META;
 };
 
 // The formats the narrow layout takes: K a whole number of steps, groups of 16 weights (32 at 3
@@ -65,85 +85,106 @@ int make_narrow_layout(int64_t N, int64_t K, int bits, int group, NarrowLayout *
     L->steps = L->wide.steps;
     L->wsteps = (L->steps + NW_SLICES - 1) / NW_SLICES;
     if (L->wsteps > NW_MAX_TEAM * NW_MAX_SPW) return QG_ERR_UNSUPPORTED;
-    L->zwords = L->wide.zwords;
-    L->codes_off = 0;
-    const size_t codes_bytes = (size_t)L->tiles16 * L->wsteps * L->loads * QG_WAVE * 16;
-    L->scales_off = qg_round_up(codes_bytes, QG_SECTION_ALIGN);
-    const size_t scales_bytes = (size_t)L->tiles16 * L->wsteps * L->gps * QG_WAVE * 4;
-    L->zeros_off = qg_round_up(L->scales_off + scales_bytes, QG_SECTION_ALIGN);
-    const size_t zeros_bytes = (size_t)L->tiles16 * L->zwords * NW_OUT * 4;
-    L->total = qg_round_up(L->zeros_off + zeros_bytes, QG_SECTION_ALIGN);
+    L->zb = L->gps * L->wide.zbits;
+    if (L->zb > 32) return QG_ERR_UNSUPPORTED;
+    L->meta_zeros = L->gps * QG_WAVE * 4;
+    L->meta_bytes = L->meta_zeros + (QG_WAVE * L->zb / 8 + 15) / 16 * 16;
+    L->code_bytes = L->loads * QG_WAVE * 16;
+    L->rec_bytes = L->code_bytes + L->meta_bytes;
+    L->total = qg_round_up((size_t)L->tiles16 * L->wsteps * L->rec_bytes, QG_SECTION_ALIGN);
     return QG_OK;
 }
 
-// ---- wide <-> narrow: a permutation of 16-byte pieces, scales and zero words ------------------
+// ---- wide <-> narrow: 16-byte pieces and scales move, zero-points are re-packed ---------------
 struct RepackArgs {
     const char *src;
     char *dst;
     size_t w_codes, w_scales, w_zeros;      // section offsets of the wide blob
-    size_t n_codes, n_scales, n_zeros;      // ... of the narrow blob
     long tiles64, tiles16, steps, wsteps, ngroups, zwords;
-    int loads, gps;
+    int loads, gps, zbits, zb;
+    int meta_zeros, code_bytes, rec_bytes;
     uint32_t flip;                          // what every code word is XORed with on its way (either way)
 };
 
-// One thread per element of the narrow blob's three sections (codes, then scales, then zeros).
-// to_narrow: narrow[e] = wide[its source] or 0; otherwise wide[source of e] = narrow[e].
+// One thread per 16-byte piece of codes, per scale and per zero word of the blob that is written
+// (the narrow records' zero words, or the wide blob's).
 template <bool TO_NARROW>
 __global__ void repack_narrow(const RepackArgs A)
 {
-    const size_t n_code = (size_t)A.tiles16 * A.wsteps * A.loads * QG_WAVE;
-    const size_t n_scale = (size_t)A.tiles16 * A.wsteps * A.gps * QG_WAVE;
-    const size_t n_zero = (size_t)A.tiles16 * A.zwords * NW_OUT;
+    const size_t recs = (size_t)A.tiles16 * A.wsteps;
+    const size_t per_rec = (size_t)(A.loads + A.gps) * QG_WAVE;
+    const int zper = 32 / A.zbits, lpd = 32 / A.zb;         // zero-points per wide word; lanes per narrow word
+    const uint32_t zmask = (1u << A.zbits) - 1u;
     size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e < n_code) {
-        const int lane = (int)(e % QG_WAVE);
-        size_t r = e / QG_WAVE;
-        const int i = (int)(r % A.loads);
-        r /= A.loads;
+    if (e < recs * per_rec) {
+        const size_t r = e / per_rec;
+        const int i = (int)(e % per_rec);
         const long w = (long)(r % A.wsteps), T = (long)(r / A.wsteps);
+        const int lane = i % QG_WAVE;
         const long t = NW_SLICES * w + (lane >> 4), tile = T / 4;
         const int lane64 = (int)(T % 4) * NW_OUT + (lane & 15);
         const bool real = t < A.steps;
-        const size_t wide = ((size_t)(tile * A.steps + (real ? t : 0)) * A.loads + i) * QG_WAVE + lane64;
-        uint4 *n = (uint4 *)(A.dst + A.n_codes) + e;
-        if (TO_NARROW) {
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);       // (a padded step meets zero scales: what its codes read as is immaterial)
-            if (real) {
-                v = ((const uint4 *)(A.src + A.w_codes))[wide];
+        const size_t codes_at = r * A.rec_bytes, meta_at = codes_at + A.code_bytes;
+        if (i < A.loads * QG_WAVE) {
+            const int ld = i / QG_WAVE;
+            const size_t wide = ((size_t)(tile * A.steps + (real ? t : 0)) * A.loads + ld) * QG_WAVE + lane64;
+            if (TO_NARROW) {
+                uint4 v = make_uint4(0u, 0u, 0u, 0u);       // (a padded step meets zero scales: what its codes read as is immaterial)
+                if (real) {
+                    v = ((const uint4 *)(A.src + A.w_codes))[wide];
+                    v.x ^= A.flip; v.y ^= A.flip; v.z ^= A.flip; v.w ^= A.flip;
+                }
+                ((uint4 *)(A.dst + codes_at))[ld * QG_WAVE + lane] = v;
+            } else if (real) {
+                uint4 v = ((const uint4 *)(A.src + codes_at))[ld * QG_WAVE + lane];
                 v.x ^= A.flip; v.y ^= A.flip; v.z ^= A.flip; v.w ^= A.flip;
+                ((uint4 *)(A.dst + A.w_codes))[wide] = v;
             }
-            *n = v;
-        } else if (real) {
-            uint4 v = ((const uint4 *)(A.src + A.n_codes))[e];
-            v.x ^= A.flip; v.y ^= A.flip; v.z ^= A.flip; v.w ^= A.flip;
-            ((uint4 *)(A.dst + A.w_codes))[wide] = v;
+        } else {
+            const int gs = i / QG_WAVE - A.loads;
+            const size_t wide = (size_t)(tile * A.ngroups + (real ? t * A.gps + gs : 0)) * QG_WAVE + lane64;
+            if (TO_NARROW) ((float *)(A.dst + meta_at))[gs * QG_WAVE + lane] = real ? ((const float *)(A.src + A.w_scales))[wide] : 0.0f;
+            else if (real) ((float *)(A.dst + A.w_scales))[wide] = ((const float *)(A.src + meta_at))[gs * QG_WAVE + lane];
         }
         return;
     }
-    e -= n_code;
-    if (e < n_scale) {
-        const int lane = (int)(e % QG_WAVE);
-        size_t r = e / QG_WAVE;
-        const int gs = (int)(r % A.gps);
-        r /= A.gps;
+    e -= recs * per_rec;
+    if (TO_NARROW) {
+        const int words = 2 * A.zb;                                 // zero words of a record
+        if (e >= recs * words) return;
+        const size_t r = e / words;
+        const int d = (int)(e % words);
         const long w = (long)(r % A.wsteps), T = (long)(r / A.wsteps);
-        const long t = NW_SLICES * w + (lane >> 4), tile = T / 4;
-        const int lane64 = (int)(T % 4) * NW_OUT + (lane & 15);
-        const bool real = t < A.steps;
-        const size_t wide = (size_t)(tile * A.ngroups + (real ? t * A.gps + gs : 0)) * QG_WAVE + lane64;
-        if (TO_NARROW) ((float *)(A.dst + A.n_scales))[e] = real ? ((const float *)(A.src + A.w_scales))[wide] : 0.0f;
-        else if (real) ((float *)(A.dst + A.w_scales))[wide] = ((const float *)(A.src + A.n_scales))[e];
-        return;
-    }
-    e -= n_scale;
-    if (e < n_zero) {
-        const int o = (int)(e % NW_OUT);
-        const size_t r = e / NW_OUT;
-        const long zw = (long)(r % A.zwords), T = (long)(r / A.zwords);
-        const size_t wide = (size_t)((T / 4) * A.zwords + zw) * QG_WAVE + (T % 4) * NW_OUT + o;
-        if (TO_NARROW) ((uint32_t *)(A.dst + A.n_zeros))[e] = ((const uint32_t *)(A.src + A.w_zeros))[wide];
-        else ((uint32_t *)(A.dst + A.w_zeros))[wide] = ((const uint32_t *)(A.src + A.n_zeros))[e];
+        uint32_t val = 0;
+        for (int li = 0; li < lpd; ++li) {
+            const int lane = d * lpd + li;
+            const long t = NW_SLICES * w + (lane >> 4);
+            if (t >= A.steps) continue;
+            const int lane64 = (int)(T % 4) * NW_OUT + (lane & 15);
+            for (int gs = 0; gs < A.gps; ++gs) {
+                const long g = t * A.gps + gs;
+                const uint32_t zw = ((const uint32_t *)(A.src + A.w_zeros))[(size_t)((T / 4) * A.zwords + g / zper) * QG_WAVE + lane64];
+                val |= ((zw >> (A.zbits * (int)(g % zper))) & zmask) << (li * A.zb + gs * A.zbits);
+            }
+        }
+        ((uint32_t *)(A.dst + r * A.rec_bytes + A.code_bytes + A.meta_zeros))[d] = val;
+    } else {
+        if (e >= (size_t)A.tiles64 * A.zwords * QG_WAVE) return;
+        const int lane64 = (int)(e % QG_WAVE);
+        const long zw = (long)((e / QG_WAVE) % A.zwords), tile = (long)(e / QG_WAVE / A.zwords);
+        const long T = tile * 4 + lane64 / NW_OUT;
+        uint32_t val = 0;
+        if (T < A.tiles16)
+            for (int f = 0; f < zper; ++f) {
+                const long g = zw * zper + f;
+                if (g >= A.ngroups) break;
+                const long t = g / A.gps;
+                const int gs = (int)(g % A.gps), lane = (int)(t % NW_SLICES) * NW_OUT + lane64 % NW_OUT;
+                const size_t meta_at = ((size_t)T * A.wsteps + t / NW_SLICES) * A.rec_bytes + A.code_bytes;
+                const uint32_t word = ((const uint32_t *)(A.src + meta_at + A.meta_zeros))[lane / lpd];
+                val |= ((word >> ((lane % lpd) * A.zb + gs * A.zbits)) & zmask) << (A.zbits * f);
+            }
+        ((uint32_t *)(A.dst + A.w_zeros))[e] = val;
     }
 }
 
@@ -155,12 +196,10 @@ __global__ void zero_bytes16(uint4 *p, size_t n)
 
 // ---- the kernel --------------------------------------------------------------------------------
 struct NarrowProblem {
-    const uint4 *codes;
-    const float *scales;
-    const uint32_t *zeros;
+    const char *blob;       // records [tile16][wave-step]
     const float *x;
     float *y;
-    int N, steps, wsteps, zwords;
+    int N, steps, wsteps;
     int tiles16;
     int spw;                // wave-steps per wavefront
     int team;               // wavefronts with work
@@ -241,9 +280,10 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BL
     constexpr int READS = S / 16;                   // 128-bit reads of A per step, four matrix instructions each
     constexpr int RPG = READS / GPS;
     constexpr int LPG = NW_OUT / GPS;               // lanes whose x values make up one group
-    constexpr int ZPER = 32 / F::ZBITS;
+    using R = NarrowRecord<BITS, GPS>;
+    constexpr int LPW = 32 / R::ZB;                 // lanes whose zero-points share a word
     constexpr int PITCH = S + 16;                   // bytes per digit row: the four rows on different banks
-    static_assert(GPS >= 1 && GPS <= NW_OUT && READS % GPS == 0 && ZPER % GPS == 0, "groups of a step");
+    static_assert(GPS >= 1 && GPS <= NW_OUT && READS % GPS == 0 && R::ZB <= 32 && 32 % R::ZB == 0, "groups of a step");
     __shared__ float red[NW_MAX_TEAM][TPW * NW_OUT];
     // per wavefront and slice: the four digit rows of the slice's x in operand order
     __shared__ __attribute__((aligned(16))) nw_lds_u8 xs[NW_MAX_TEAM][NW_SLICES][4][PITCH];
@@ -262,8 +302,8 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BL
     }
     const NarrowProblem P = A.p[pi];
     // every field now, so that the loads of the entry are issued together
-    asm volatile("" ::"s"(P.codes), "s"(P.scales), "s"(P.zeros), "s"(P.x), "s"(P.y));
-    asm volatile("" ::"s"(P.N), "s"(P.steps), "s"(P.wsteps), "s"(P.zwords), "s"(P.tiles16), "s"(P.spw), "s"(P.team),
+    asm volatile("" ::"s"(P.blob), "s"(P.x), "s"(P.y));
+    asm volatile("" ::"s"(P.N), "s"(P.steps), "s"(P.wsteps), "s"(P.tiles16), "s"(P.spw), "s"(P.team),
                  "s"(P.block_begin));
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -275,15 +315,11 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BL
 
     // uniform bases; what a lane adds to them fits 32 bits.  A tile past the last one reads the
     // last one again and stores nothing.
-    const uint4 *codes[TPW];
-    const float *scales[TPW];
-    const uint32_t *zeros[TPW];
+    const char *records[TPW];                       // the tile's record of wave-step 0
 #pragma unroll
     for (int u = 0; u < TPW; ++u) {
         const int T = T0 + u < P.tiles16 ? T0 + u : P.tiles16 - 1;
-        codes[u] = P.codes + (size_t)T * P.wsteps * L * QG_WAVE;
-        scales[u] = P.scales + (size_t)T * P.wsteps * GPS * QG_WAVE;
-        zeros[u] = P.zeros + (size_t)T * P.zwords * NW_OUT;
+        records[u] = P.blob + (size_t)T * P.wsteps * R::BYTES;
     }
     nw_lds_u8 *mine = &xs[wave][j][0][0] + o * XPL;              // this lane's bytes of digit row 0
     const nw_lds_u8 *abase = &xs[wave][j][lane & 3][0];         // the digit row this lane supplies to its block
@@ -312,18 +348,19 @@ __global__ __launch_bounds__(NW_MAX_TEAM * QG_WAVE) void gemv_narrow(NW_FIRST_BL
         uint4 v[TPW][L];
         float s[TPW][GPS];
         uint32_t zword[TPW];
-        const uint32_t g0 = tc * GPS;                             // a step's groups share one zero word
 #pragma unroll
         for (int u = 0; u < TPW; ++u) {
 #pragma unroll
-            for (int i = 0; i < L; ++i) v[u][i] = codes[u][(uint32_t)(w * L + i) * QG_WAVE + lane];
+            for (int i = 0; i < L; ++i)
+                v[u][i] = *(const uint4 *)(records[u] + ((uint32_t)w * R::BYTES + (uint32_t)(i * QG_WAVE + lane) * 16u));
 #pragma unroll
-            for (int g = 0; g < GPS; ++g) s[u][g] = scales[u][(uint32_t)(w * GPS + g) * QG_WAVE + lane];
-            zword[u] = zeros[u][(g0 / ZPER) * NW_OUT + o];
+            for (int g = 0; g < GPS; ++g)
+                s[u][g] = *(const float *)(records[u] + ((uint32_t)w * R::BYTES + R::CODES + (uint32_t)(g * QG_WAVE + lane) * 4u));
+            zword[u] = *(const uint32_t *)(records[u] + ((uint32_t)w * R::BYTES + R::CODES + R::ZEROS + (uint32_t)(lane / LPW) * 4u));
         }
         __builtin_amdgcn_sched_barrier(0);                        // every load is requested before the arithmetic starts
 #pragma unroll
-        for (int u = 0; u < TPW; ++u) zword[u] >>= F::ZBITS * (g0 % ZPER);
+        for (int u = 0; u < TPW; ++u) zword[u] >>= (lane % LPW) * R::ZB;     // this lane's zero-points, first group lowest
 
         // fixed point of the slice: |x| scale < 2^30 for its largest |x|
         float mf = 0.0f;
@@ -519,16 +556,18 @@ int repack(const void *src, void *dst, int64_t N, int64_t K, int bits, int group
     A.src = (const char *)src;
     A.dst = (char *)dst;
     A.w_codes = L.wide.codes_off; A.w_scales = L.wide.scales_off; A.w_zeros = L.wide.zeros_off;
-    A.n_codes = L.codes_off; A.n_scales = L.scales_off; A.n_zeros = L.zeros_off;
     A.tiles64 = (long)L.wide.tiles; A.tiles16 = (long)L.tiles16; A.steps = (long)L.steps; A.wsteps = (long)L.wsteps;
-    A.ngroups = (long)L.wide.ngroups; A.zwords = (long)L.zwords;
+    A.ngroups = (long)L.wide.ngroups; A.zwords = (long)L.wide.zwords;
+    A.zbits = L.wide.zbits; A.zb = L.zb;
+    A.meta_zeros = L.meta_zeros; A.code_bytes = L.code_bytes; A.rec_bytes = L.rec_bytes;
     A.loads = L.loads; A.gps = L.gps;
     A.flip = bits == 4 ? 0x80808080u : 0u;
-    const size_t elements = (size_t)L.tiles16 * L.wsteps * L.loads * QG_WAVE + (size_t)L.tiles16 * L.wsteps * L.gps * QG_WAVE +
-                            (size_t)L.tiles16 * L.zwords * NW_OUT;
+    const size_t elements = (size_t)L.tiles16 * L.wsteps * (L.loads + L.gps) * QG_WAVE +
+                            (to_narrow ? (size_t)L.tiles16 * L.wsteps * 2 * L.zb : (size_t)L.wide.tiles * L.wide.zwords * QG_WAVE);
+    if ((elements + 255) / 256 > 0x7fffffffu) return QG_ERR_SHAPE;
     const unsigned blocks = (unsigned)((elements + 255) / 256);
-    // the destination is cleared first: the gaps between its sections, and (wide) the outputs past
-    // the last tile of 16, are written by nothing else
+    // the destination is cleared first: the padding of its records or sections, and (wide) the
+    // outputs past the last tile of 16, are written by nothing else
     const size_t n16 = (to_narrow ? L.total : L.wide.total) / 16;
     hipLaunchKernelGGL(zero_bytes16, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, (uint4 *)dst, n16);
     if (qg_launch_status() != QG_OK) return QG_ERR_DEVICE;
@@ -608,16 +647,12 @@ extern "C" int qg_gemv_grouped_narrow(const qg_gemv_desc *descs, int count, void
                 const NarrowLayout &Lk = L[idx[k]];
                 const qg_gemv_desc &d = descs[idx[k]];
                 NarrowProblem &P = A.p[k];
-                const char *base = (const char *)d.packed;
-                P.codes = (const uint4 *)(base + Lk.codes_off);
-                P.scales = (const float *)(base + Lk.scales_off);
-                P.zeros = (const uint32_t *)(base + Lk.zeros_off);
+                P.blob = (const char *)d.packed;
                 P.x = d.x;
                 P.y = d.y;
                 P.N = (int)Lk.N;
                 P.steps = (int)Lk.steps;
                 P.wsteps = (int)Lk.wsteps;
-                P.zwords = (int)Lk.zwords;
                 P.tiles16 = (int)Lk.tiles16;
                 P.spw = (int)((Lk.wsteps + NW_MAX_TEAM - 1) / NW_MAX_TEAM);
                 P.team = (int)((Lk.wsteps + P.spw - 1) / P.spw);
