@@ -14,9 +14,9 @@
 // Eight wavefronts with one wave-step each then cover K = 4096 (4 bits) of their 16 outputs, a
 // workgroup owns its outputs, and nothing is added across workgroups: no workspace, no atomics.
 //
-// What a wavefront needs for one wave-step is one contiguous record (scales and zero-points in
-// sections of their own, 2 KB and 256 B per workgroup apart from its 32 KB of codes, cost C2 1.6 us:
-// measured with the loads of the two taken out):
+// What a wavefront needs for one wave-step is one contiguous record (with scales and zero-points
+// in sections of their own -- three distant pieces per wave-step -- a 3-bit layer set of 140 MB ran
+// 1 us longer; at 4 bits the two forms measured alike):
 //
 //   record [tile16][wave-step]:
 //     codes : uint4  [load][lane]                       lane = 16 * slice + output
