@@ -88,3 +88,34 @@ def test_bad_shapes_are_rejected_without_a_gpu(qg):
     assert L.qg_set_gemv_tuning(99, 0, 0) == 2 and L.qg_set_gemv_tuning(0, 0, 5) == 2
     assert L.qg_set_gemv_tuning(0, 0, 0) == 0
     assert b"aligned" in L.qg_status_string(4)
+
+
+@pytest.mark.parametrize("N,K,bits,group", [(4096, 4096, 4, 128), (4096, 11008, 4, 128), (100, 1024, 4, 16),
+                                            (5120, 13824, 3, 64), (8192, 22016, 2, 32), (70, 512, 2, 16), (1, 256, 3, 256)])
+def test_narrow_bytes_follow_the_record_formula(qg, N, K, bits, group):
+    # one record per 16 outputs and 4 steps of K: the steps' codes, a scale per group and lane of
+    # 64, the zero-points of the 64 lanes packed and padded to 16 bytes; the blob to 256 bytes
+    step = 128 if bits == 4 else 256
+    groups = step // group
+    zero_bits = 2 if bits == 2 else 4
+    record = 4 * 16 * step * bits // 8 + groups * 64 * 4 + -(-(64 * groups * zero_bits // 8) // 16) * 16
+    records = -(-N // 16) * -(-(K // step) // 4)
+    assert qg.qg_packed_bytes(N, K, bits, group, qg.QG_LAYOUT_DEVICE_NARROW) == -(-records * record // 256) * 256
+    # algorithmic bytes plus padding only
+    assert records * record >= N * K * bits // 8 + N * (K // group) * 4
+
+
+def test_narrow_calls_reject_bad_arguments_without_a_gpu(qg):
+    L = qg.lib()
+    for (N, K, bits, group) in [(64, 192, 4, 64), (64, 1024, 4, 256), (64, 1024, 4, 8), (16, 65536, 4, 128),
+                                (64, 1024, 3, 1024), (64, 1024, 3, 16)]:
+        assert qg.qg_packed_bytes(N, K, bits, group, qg.QG_LAYOUT_DEVICE_NARROW) == 0
+        assert L.qg_to_narrow(16, N, K, bits, group, 16, None) in (2, 3)
+    assert L.qg_to_narrow(None, 64, 1024, 4, 128, 16, None) == 1
+    assert L.qg_to_narrow(16, 64, 1024, 4, 128, 24, None) == 4              # narrow not 16-byte aligned
+    assert L.qg_from_narrow(16, 64, 1024, 4, 128, None, None) == 1
+    assert L.qg_gemv_narrow(None, 64, 1024, 4, 128, 64, 64, None) == 1
+    assert L.qg_gemv_narrow(16, 64, 1024, 4, 128, 16, 64, None) == 4        # x not 64-byte aligned
+    assert L.qg_gemv_narrow(16, 64, 1000, 4, 128, 64, 64, None) == 2        # K % G != 0
+    assert L.qg_gemv_grouped_narrow(None, 1, None) == 1
+    assert L.qg_set_narrow_tuning(3) == 2 and L.qg_set_narrow_tuning(0) == 0
