@@ -412,6 +412,9 @@ def test_calls_run_on_the_stream_they_are_given(qg, oracle):
             ballast.fill_(1.0)
         y = qg.qg_gemv(blob, N, K, bits, group, x0, None, ws)
         y2 = qg.qg_gemv_noalloc(blob, N, K, bits, group, x0, torch.empty(N, dtype=torch.float32, device="cuda"))
+        narrow = qg.qg_to_narrow(blob, N, K, bits, group)
+        yn = qg.qg_gemv_narrow(narrow, N, K, bits, group, x0)
+        back = qg.qg_from_narrow(narrow, N, K, bits, group)
         Y = qg.qg_gemm_small(blob, N, K, bits, group, Xd, None, wsm)
         qg.qg_set_gemm_tuning(0, 13)
         try:
@@ -421,6 +424,8 @@ def test_calls_run_on_the_stream_they_are_given(qg, oracle):
     side.synchronize()
     assert scaled_error(host(y), y_ref, norms, X[0]) <= TOL_FP32
     assert np.array_equal(host(y), host(y2))
+    assert scaled_error(host(yn), y_ref, norms, X[0]) <= TOL_FP32
+    assert np.array_equal(host(back), host(blob))
     assert scaled_error(host(Y), Y_ref, norms, X) <= gemm_model_bound(K)
     assert scaled_error(host(Yc), Y_ref, norms, X) <= gemm_model_bound(K)
     torch.cuda.synchronize()
