@@ -167,6 +167,42 @@ def test_gemv_narrow_hard_activations(qg, oracle, N, K, bits, group, kind):
         assert err <= 2e-6, (err, kind)
 
 
+def test_gemv_narrow_replayed_from_a_graph(qg, oracle):
+    # a serving loop captures the call once and replays it: every replay, with eager work and
+    # synchronizations of the program in between, gives what the eager call gives on the same x
+    _announce("gemv narrow in a graph")
+    specs = [(300, 4096, 4, 128), (130, 1536, 3, 64), (96, 2048, 2, 32)]
+    problems, refs = [], []
+    for i, (N, K, bits, group) in enumerate(specs):
+        W, x = synth.small_case(9100 + i, N, K, 0.02, True)
+        q0, s0, z0 = oracle.quantize(W, bits, group)
+        refs.append((q0, s0, z0, oracle.row_norms(q0, s0, z0, group)))
+        q, s, z = qg.qg_quantize(dev(W), bits, group)
+        problems.append(dict(packed=qg.qg_to_narrow(qg.qg_pack(q, s, z, bits, group), N, K, bits, group), N=N, K=K,
+                             bits=bits, group=group, x=dev(x), y=torch.zeros(N, dtype=torch.float32, device="cuda")))
+    launch = qg.GroupedGemvNarrow(problems)
+    launch.launch()                                   # the kernels are loaded before the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        launch.launch()
+    rng = np.random.default_rng(77)
+    for replay in range(4):
+        xs = [rng.standard_normal(p["K"]).astype(np.float32) * (replay + 1) for p in problems]
+        for p, x in zip(problems, xs):
+            p["x"].copy_(dev(x))
+            p["y"].fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = [host(p["y"]).copy() for p in problems]
+        launch.launch()
+        torch.cuda.synchronize()
+        for p, x, yr, (q0, s0, z0, norms) in zip(problems, xs, replayed, refs):
+            assert np.array_equal(yr, host(p["y"])), (replay, p["N"], p["K"], p["bits"])
+            assert scaled_error(yr, oracle.matvec(q0, s0, z0, p["group"], x), norms, x) <= TOL_FP32
+
+
 def test_gemv_narrow_grouped_mixed_problems(qg, oracle):
     # one call, three kernel classes, K of different lengths inside a class, ragged N
     _announce("gemv narrow grouped")
